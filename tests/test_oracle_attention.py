@@ -1,0 +1,290 @@
+"""Pins for the oracle's masked attention (Eq. 5-7) and generation form (Sec. 3.1, App. A).
+
+Each test checks the oracle against something that is not the oracle: a closed form,
+a library routine on a special case, brute-force enumeration over the hand-written
+Fig. 1 mask, or an invariant of the definition.  CPU only.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import loma_oracle as lo
+from paper_2401_09486_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "fig1_mask_t2_c2_n3.txt")
+
+
+def golden_mask():
+    rows = [ln.strip() for ln in open(GOLDEN) if ln.strip() and not ln.startswith("#")]
+    return np.array([[int(ch) for ch in r] for r in rows], dtype=np.uint8)
+
+
+def rand_qkv(rng, B, H, S, d, scale=1.0):
+    return tuple((scale * rng.standard_normal((B, H, S, d))).astype(np.float32) for _ in range(3))
+
+
+def both_oracles(c_oracle, q, k, v, t, c, n, scale):
+    a = lo.mask_attn_fwd(q, k, v, t, c, n, scale)
+    b = c_oracle.mask_attn(q, k, v, t, c, n, scale)
+    return a, b
+
+
+# ---- brute force over the hand-written mask -------------------------------------------
+def test_brute_force_on_fig1_example(c_oracle):
+    t, c, n, d = 2, 2, 3, 5
+    rng = np.random.default_rng(11)
+    q, k, v = rand_qkv(rng, 1, 2, 30, d)
+    scale = 0.37
+    g = golden_mask()
+    a, b = both_oracles(c_oracle, q, k, v, t, c, n, scale)
+    for h in range(2):
+        for p in range(30):
+            keys = [j for j in range(30) if g[p, j]]
+            sc = [scale * sum(float(q[0, h, p, e]) * float(k[0, h, j, e]) for e in range(d)) for j in keys]
+            den = sum(math.exp(x) for x in sc)
+            for e in range(d):
+                want = sum(math.exp(x) / den * float(v[0, h, j, e]) for x, j in zip(sc, keys))
+                assert abs(a[0, h, p, e] - want) < 1e-13
+                assert abs(b[0, h, p, e] - want) < 1e-13
+
+
+# ---- closed forms ------------------------------------------------------------------------
+@pytest.mark.parametrize("t,c,n", [(2, 2, 3), (4, 4, 4), (3, 2, 2)])
+def test_zero_query_gives_mean_of_visible_values(c_oracle, t, c, n):
+    R, s = t * c, t * (2 * c + 1)
+    S, d = n * s, 6
+    rng = np.random.default_rng(5)
+    _, k, v = rand_qkv(rng, 1, 1, S, d)
+    q = np.zeros_like(k)
+    a, b = both_oracles(c_oracle, q, k, v, t, c, n, 1.0)
+    V = v[0, 0].astype(np.float64)
+    for p in range(S):
+        y, o = divmod(p, s)
+        if o < R:       # earlier memory zones + causal prefix of the own reading zone
+            idx = [yy * s + R + j for yy in range(y) for j in range(t)] + [y * s + j for j in range(o + 1)]
+        elif o < R + t:  # own reading + memory zone
+            idx = list(range(y * s, y * s + R + t))
+        else:            # own memory zone + itself
+            idx = list(range(y * s + R, y * s + R + t)) + [p]
+        want = V[idx].mean(axis=0)
+        np.testing.assert_allclose(a[0, 0, p], want, atol=1e-14)
+        np.testing.assert_allclose(b[0, 0, p], want, atol=1e-14)
+
+
+def test_constant_values_pass_through(c_oracle):
+    t, c, n, d = 3, 2, 3, 4
+    S = n * t * (2 * c + 1)
+    rng = np.random.default_rng(6)
+    q, k, _ = rand_qkv(rng, 2, 2, S, d)
+    v0 = np.array([0.25, -1.5, 3.0, 0.125], dtype=np.float32)
+    v = np.broadcast_to(v0, (2, 2, S, d)).copy()
+    a, b = both_oracles(c_oracle, q, k, v, t, c, n, 0.5)
+    np.testing.assert_allclose(a, np.broadcast_to(v0, a.shape), atol=1e-14)
+    np.testing.assert_allclose(b, np.broadcast_to(v0, b.shape), atol=1e-14)
+
+
+def test_weights_rows_sum_to_one_and_vanish_off_mask():
+    t, c, n, d = 2, 3, 3, 8
+    S = n * t * (2 * c + 1)
+    rng = np.random.default_rng(7)
+    q, k, v = rand_qkv(rng, 1, 1, S, d, 2.0)
+    m = lo.mask_from_blocks(t, c, n)
+    _, _, W = lo.masked_softmax_attention(q[0, 0], k[0, 0], v[0, 0], m, 0.7)
+    np.testing.assert_allclose(W.sum(axis=1), 1.0, atol=1e-14)
+    assert (W[m == 0] == 0).all() and (W[m == 1] > 0).all()
+
+
+def test_lse_matches_logsumexp_of_visible_scores(c_oracle):
+    from scipy.special import logsumexp
+    t, c, n, d = 2, 2, 3, 7
+    rng = np.random.default_rng(8)
+    q, k, v = rand_qkv(rng, 1, 1, 30, d)
+    g = golden_mask().astype(bool)
+    _, lse_np = lo.mask_attn_fwd(q, k, v, t, c, n, 0.41, return_lse=True)
+    _, lse_c = c_oracle.mask_attn(q, k, v, t, c, n, 0.41, return_lse=True)
+    A = 0.41 * q[0, 0].astype(np.float64) @ k[0, 0].astype(np.float64).T
+    for p in range(30):
+        want = logsumexp(A[p, g[p]])
+        assert abs(lse_np[0, 0, p] - want) < 1e-13 and abs(lse_c[0, 0, p] - want) < 1e-13
+
+
+# ---- each zone reduces to a library SDPA call on gathered keys ---------------------------------
+def sdpa64(q, k, v, scale, causal=False):
+    tq, tk, tv = (torch.from_numpy(np.asarray(x, dtype=np.float64))[None, None] for x in (q, k, v))
+    return F.scaled_dot_product_attention(tq, tk, tv, is_causal=causal, scale=scale)[0, 0].numpy()
+
+
+@pytest.mark.parametrize("t,c,n,d", [(4, 4, 4, 64), (2, 3, 3, 16), (5, 1, 3, 8)])
+def test_zones_reduce_to_library_attention(c_oracle, t, c, n, d):
+    R, s = t * c, t * (2 * c + 1)
+    S = n * s
+    rng = np.random.default_rng(9)
+    q, k, v = rand_qkv(rng, 1, 2, S, d)
+    scale = 1.0 / math.sqrt(d)
+    a, b = both_oracles(c_oracle, q, k, v, t, c, n, scale)
+    for h in range(2):
+        Q, K, V = q[0, h], k[0, h], v[0, h]
+        # first chunk's reading zone is ordinary causal attention over the first R tokens
+        want = sdpa64(Q[:R], K[:R], V[:R], scale, causal=True)
+        np.testing.assert_allclose(a[0, h, :R], want, atol=1e-12)
+        np.testing.assert_allclose(b[0, h, :R], want, atol=1e-12)
+        for y in range(n):
+            base = y * s
+            # memory rows: full attention over the chunk's reading + memory zone
+            want = sdpa64(Q[base + R:base + R + t], K[base:base + R + t], V[base:base + R + t], scale)
+            np.testing.assert_allclose(a[0, h, base + R:base + R + t], want, atol=1e-12)
+            np.testing.assert_allclose(b[0, h, base + R:base + R + t], want, atol=1e-12)
+            mem_idx = [yy * s + R + j for yy in range(y) for j in range(t)]
+            for o in range(R):
+                # reading row: earlier memory zones + own causal prefix
+                idx = mem_idx + list(range(base, base + o + 1))
+                want = sdpa64(Q[base + o:base + o + 1], K[idx], V[idx], scale)[0]
+                np.testing.assert_allclose(a[0, h, base + o], want, atol=1e-12)
+                np.testing.assert_allclose(b[0, h, base + o], want, atol=1e-12)
+                # repetition row: own memory zone + itself
+                p = base + R + t + o
+                idx = list(range(base + R, base + R + t)) + [p]
+                want = sdpa64(Q[p:p + 1], K[idx], V[idx], scale)[0]
+                np.testing.assert_allclose(a[0, h, p], want, atol=1e-12)
+                np.testing.assert_allclose(b[0, h, p], want, atol=1e-12)
+
+
+# ---- visibility: Eq. 8-9, masked K/V never reach a row ------------------------------------------
+def test_masked_keys_do_not_influence_rows_bitwise(c_oracle):
+    t, c, n, d = 2, 2, 3, 4
+    rng = np.random.default_rng(10)
+    q, k, v = rand_qkv(rng, 1, 1, 30, d)
+    g = golden_mask()
+    base_np, base_c = both_oracles(c_oracle, q, k, v, t, c, n, 0.5)
+    for p in [0, 3, 5, 6, 9, 12, 14, 17, 23, 25, 29]:
+        k2, v2 = k.copy(), v.copy()
+        hidden = np.nonzero(g[p] == 0)[0]
+        k2[0, 0, hidden] = np.nan
+        v2[0, 0, hidden] = np.inf
+        # the dense numpy oracle multiplies q @ k.T first; NaN rows only poison masked scores
+        with np.errstate(invalid="ignore"):
+            o_np = lo.mask_attn_fwd(q, k2, v2, t, c, n, 0.5)
+        o_c = c_oracle.mask_attn(q, k2, v2, t, c, n, 0.5)
+        assert np.array_equal(o_np[0, 0, p], base_np[0, 0, p])
+        assert np.array_equal(o_c[0, 0, p], base_c[0, 0, p])
+
+
+def test_visible_key_change_does_influence_row():
+    t, c, n, d = 2, 2, 3, 4
+    rng = np.random.default_rng(12)
+    q, k, v = rand_qkv(rng, 1, 1, 30, d)
+    g = golden_mask()
+    base = lo.mask_attn_fwd(q, k, v, t, c, n, 0.5)
+    for p in range(30):
+        for j in np.nonzero(g[p])[0]:
+            v2 = v.copy()
+            v2[0, 0, j] += 1.0
+            assert not np.array_equal(lo.mask_attn_fwd(q, k, v2, t, c, n, 0.5)[0, 0, p], base[0, 0, p])
+
+
+def test_scale_multiplies_scores(c_oracle):
+    t, c, n, d = 2, 2, 2, 8
+    rng = np.random.default_rng(13)
+    q, k, v = rand_qkv(rng, 1, 1, 20, d)
+    a = c_oracle.mask_attn(q, k, v, t, c, n, 0.5)
+    b = c_oracle.mask_attn((2 * q).astype(np.float32), k, v, t, c, n, 0.25)
+    np.testing.assert_allclose(a, b, atol=1e-13)
+
+
+# ---- C oracle plumbing: row subsets, bf16 input path ----------------------------------------------
+def test_c_oracle_row_subset_and_bf16_inputs(c_oracle):
+    t, c, n, d = 4, 2, 3, 16
+    S = n * t * (2 * c + 1)
+    rng = np.random.default_rng(14)
+    q, k, v = rand_qkv(rng, 2, 3, S, d)
+    qb, kb, vb = (wl.f32_to_bf16_bits(x) for x in (q, k, v))
+    qf, kf, vf = (wl.bf16_bits_to_f32(x) for x in (qb, kb, vb))
+    full = c_oracle.mask_attn(qf, kf, vf, t, c, n, 0.25)
+    rows = np.array([0, 7, 8, 11, 12, 35, 36, S - 1], dtype=np.int32)
+    sub = c_oracle.mask_attn(qb, kb, vb, t, c, n, 0.25, rows=rows)
+    assert np.array_equal(sub, full[:, :, rows])
+    np.testing.assert_allclose(full, lo.mask_attn_fwd(qf, kf, vf, t, c, n, 0.25), atol=1e-13)
+
+
+def test_bf16_rounding_is_nearest_even():
+    x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.140625, 1e-3], dtype=np.float32)
+    # 1 + 2^-8 is a tie between 1.0 and 1 + 2^-7 -> even mantissa (1.0); 1 + 3*2^-8 ties up to 1 + 2^-6
+    got = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(x))
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(got, want)
+    assert got[1] == 1.0 and got[2] == 1.015625
+
+
+# ---- generation form == rows of the mask pass (Sec. 3.1 vs Sec. 4.3) ------------------------------
+@pytest.mark.parametrize("t,c,n,d", [(2, 2, 3, 8), (4, 4, 3, 16), (3, 1, 4, 4)])
+def test_generation_equals_mask_pass_rows(c_oracle, t, c, n, d):
+    R, s = t * c, t * (2 * c + 1)
+    S = n * s
+    B, H = 2, 2
+    rng = np.random.default_rng(15)
+    q, k, v = rand_qkv(rng, B, H, S, d)
+    scale = 1.0 / math.sqrt(d)
+    full = lo.mask_attn_fwd(q, k, v, t, c, n, scale)
+    full_c = c_oracle.mask_attn(q, k, v, t, c, n, scale)
+
+    gen = lo.GenerationCache(B, H, d, t, c, scale)
+    cg = c_oracle.GenerationCache(np.zeros((B, H, n * t, d), np.float32), np.zeros((B, H, n * t, d), np.float32), 0,
+                                  np.zeros((B, H, R, d), np.float32), np.zeros((B, H, R, d), np.float32), 0,
+                                  t, c, scale)
+    for y in range(n):
+        base = y * s
+        for o in range(R):
+            p = base + o
+            # App. A invariants: the reading zone is shorter than t*c before every token
+            assert gen.read_fill == o < R and cg.read_fill == o
+            assert gen.k_mem.shape[2] == y * t and cg.n_mem_chunks == y
+            got = gen.decode(q[:, :, p:p + 1], k[:, :, p:p + 1], v[:, :, p:p + 1])
+            np.testing.assert_allclose(got[:, :, 0], full[:, :, p], atol=1e-12)
+            got_c = cg.decode(q[:, :, p:p + 1], k[:, :, p:p + 1], v[:, :, p:p + 1])
+            np.testing.assert_allclose(got_c.reshape(B, H, d), full_c[:, :, p], atol=1e-12)
+        m0, m1 = base + R, base + R + t
+        got = gen.compress(q[:, :, m0:m1], k[:, :, m0:m1], v[:, :, m0:m1])
+        np.testing.assert_allclose(got, full[:, :, m0:m1], atol=1e-12)
+        got_c = cg.compress(q[:, :, m0:m1].copy(), k[:, :, m0:m1].copy(), v[:, :, m0:m1].copy())
+        np.testing.assert_allclose(got_c.reshape(B, H, t, d), full_c[:, :, m0:m1], atol=1e-12)
+        # cache length after compression = (chunks so far) * t, reading zone empty
+        assert gen.k_mem.shape[2] == (y + 1) * t and gen.read_fill == 0
+        assert cg.n_mem_chunks == y + 1 and cg.read_fill == 0
+
+
+def test_generation_state_machine_rejects_illegal_moves():
+    gen = lo.GenerationCache(1, 1, 4, 2, 2, 0.5)
+    z = np.zeros((1, 1, 1, 4))
+    with pytest.raises(ValueError):
+        gen.compress(np.zeros((1, 1, 2, 4)), np.zeros((1, 1, 2, 4)), np.zeros((1, 1, 2, 4)))
+    for _ in range(4):
+        gen.decode(z, z, z)
+    with pytest.raises(ValueError):
+        gen.decode(z, z, z)
+
+
+def test_compress_ignores_older_memory(c_oracle):
+    # <m> queries see their chunk's reading zone and themselves only (Eq. 1 row 2; Eq. 3 memory rows are 0)
+    t, c, d = 2, 2, 4
+    rng = np.random.default_rng(16)
+    k_mem = rng.standard_normal((1, 1, 8, d)).astype(np.float32)
+    v_mem = rng.standard_normal((1, 1, 8, d)).astype(np.float32)
+    k_read = rng.standard_normal((1, 1, 4, d)).astype(np.float32)
+    v_read = rng.standard_normal((1, 1, 4, d)).astype(np.float32)
+    qm, km, vm = (rng.standard_normal((1, 1, t, d)).astype(np.float32) for _ in range(3))
+    outs = []
+    for junk in (0.0, 100.0):
+        cg = c_oracle.GenerationCache(k_mem + junk, v_mem + junk, 2, k_read.copy(), v_read.copy(), 4, t, c, 0.5)
+        outs.append(cg.compress(qm, km, vm))
+    assert np.array_equal(outs[0], outs[1])
+
+
+def test_workload_generation_schedule():
+    c3, c5 = wl.CONFIGS[2], wl.CONFIGS[4]
+    assert (c3.n_compress, c3.mem_capacity) == (4, 1088)
+    assert (c5.n_compress, c5.mem_capacity) == (1, 8208)
+    assert wl.CONFIGS[1].S == 4032 and wl.CONFIGS[3].S == 32640 and wl.CONFIGS[0].S == 144
