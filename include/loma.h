@@ -1,0 +1,151 @@
+/*
+ * loma.h -- C ABI of the LoMA attention hot path for AMD MI355X (gfx950).
+ *
+ * LoMA (Lossless Compressed Memory Attention) restructures a sequence into chunks of
+ *     [ reading zone, R = t*c tokens | memory zone, t <m> tokens | repetition zone, R <r> tokens ]
+ * (Sec. 4.1) and trains/generates under a block attention mask (Sec. 4.3, Eq. 1-3).
+ * This library computes scaled-dot-product attention under that mask, in the two
+ * forms the paper uses:
+ *   - the training / compression-pass form over a whole restructured sample
+ *     (loma_mask_attn_fwd), and
+ *   - the generation form of Sec. 3.1 / Appendix A over a compressed KV cache
+ *     (loma_decode_attn per generated token, loma_compress_step every R tokens).
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers (HIP, current device), 16-byte aligned,
+ *     dense row-major tensors [B, H, L, head_dim] (length on axis 2, as in the
+ *     appendix's cache).  The caller owns every buffer; the library borrows it
+ *     until the work enqueued on `stream` has completed.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue kernels and return; they never allocate, free or synchronise.
+ *   - `dtype` selects the storage type of q/k/v/out and of the caches: LOMA_F32 or
+ *     LOMA_BF16.  Arithmetic: bf16 inputs are multiplied on the matrix cores with
+ *     fp32 accumulation, softmax in fp32, probabilities rounded to bf16 before the
+ *     PV product; f32 inputs use fp32 throughout.  Outputs are written in `dtype`.
+ *   - `scale` multiplies the scores before the softmax (the paper leaves 1/sqrt(d_k)
+ *     implicit, Sec. 4.4); it must be finite and > 0.
+ *   - head_dim must be a multiple of 8 in [8, 256].  bf16 with head_dim 64 or 128
+ *     takes the MFMA kernels; everything else takes a slower generic kernel.
+ *   - Return value: LOMA_OK, or a negative LOMA_ERR_* code.  Argument checking is
+ *     done on the host before anything is enqueued; on error nothing was launched
+ *     (LOMA_ERR_LAUNCH excepted, which reports a failed hipLaunch).
+ *   - A masked (query, key) pair is excluded from the softmax: its weight is exactly
+ *     0 and its K/V values never influence the result (Eq. 8-9).
+ */
+#ifndef LOMA_H_
+#define LOMA_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LOMA_OK 0
+#define LOMA_ERR_INVALID_ARG (-1) /* null/misaligned pointer, non-positive size, state the method forbids */
+#define LOMA_ERR_UNSUPPORTED (-2) /* well-formed but outside what the kernels handle (dtype, head_dim, size) */
+#define LOMA_ERR_WORKSPACE (-3)   /* workspace missing or smaller than loma_decode_workspace_bytes() */
+#define LOMA_ERR_LAUNCH (-4)      /* the HIP runtime refused a kernel launch */
+
+#define LOMA_F32 0
+#define LOMA_BF16 1
+
+/* Human-readable name of a status code; never NULL. */
+const char* loma_status_string(int status);
+
+/* ABI version of this library (bumped on any signature change). */
+int loma_abi_version(void);
+
+/*
+ * Training / compression-pass form (Sec. 4.3 Eq. 1-3, Sec. 4.4 Eq. 5-7).
+ *
+ * q, k, v, out: [B, H, S, head_dim] with S = n_chunks * t * (2c + 1); row p of a
+ * sequence lies in chunk y = p / s (s = t(2c+1)) at offset o = p % s.
+ *   reading row  (o < R):        sees the memory zones of all chunks < y, and rows
+ *                                0..o of its own reading zone (causal, self included);
+ *   memory row   (R <= o < R+t): sees its chunk's whole reading and memory zone;
+ *   repetition row (o >= R+t):   sees its chunk's memory zone and itself.
+ * out[p] = sum_j softmax_j(scale * q[p].k[j]) v[j] over the visible j.
+ * lse (optional, may be NULL): [B, H, S] float, log-sum-exp of the scaled visible scores.
+ * Masked tiles are never loaded; the mask is derived from (chunk, zone), not stored.
+ */
+int loma_mask_attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
+                       int B, int H, int head_dim, int t, int c, int n_chunks,
+                       float scale, int dtype, void* stream);
+
+/*
+ * Generation form, compression boundary (Sec. 3.1 step 2-3; Appendix A, compress_last_chunk).
+ *
+ * Precondition: the reading zone is full (R = t*c live tokens).
+ *   q_mem, k_mem, v_mem: [B, H, t, head_dim]   the t <m> tokens of this chunk
+ *   k_read, v_read:      [B, H, R, head_dim]   the live reading zone
+ *   out:                 [B, H, t, head_dim]   attention output of the <m> queries
+ *   k_memcache, v_memcache: [B, H, mem_capacity, head_dim], rows [0, n_mem_chunks*t) valid
+ * The t queries attend, unmasked, over [reading zone || the t <m> tokens' own K/V]
+ * (row 2 of Eq. 1); they do NOT see older memory zones.  Then k_mem/v_mem are copied
+ * into the memory cache at rows [n_mem_chunks*t, (n_mem_chunks+1)*t) (the appendix's
+ * splice).  The library is stateless: afterwards the caller sets n_mem_chunks += 1
+ * and read_fill = 0 (the reading zone is discarded).
+ * Errors: (n_mem_chunks + 1) * t > mem_capacity -> LOMA_ERR_INVALID_ARG.
+ */
+int loma_compress_step(const void* q_mem, const void* k_mem, const void* v_mem,
+                       const void* k_read, const void* v_read,
+                       void* k_memcache, void* v_memcache, void* out,
+                       int B, int H, int head_dim, int t, int c,
+                       int n_mem_chunks, int mem_capacity,
+                       float scale, int dtype, void* stream);
+
+/*
+ * Generation form, one new token per sequence (Sec. 3.1 step 1 and 3; Appendix A,
+ * inference_input with one input token: the mask row is all ones over cache + self).
+ *
+ *   q:             [B, H, 1, head_dim]
+ *   k_new, v_new:  [B, H, 1, head_dim] or both NULL
+ *   k_memcache, v_memcache: [B, H, mem_capacity, head_dim], rows [0, n_mem_chunks*t) valid
+ *                  (may be NULL when n_mem_chunks == 0)
+ *   k_read, v_read:[B, H, R, head_dim], rows [0, read_fill) valid
+ *   out:           [B, H, 1, head_dim]
+ * With k_new/v_new: they are written to reading-zone row read_fill (requires
+ * read_fill < R, the appendix's invariant) and the query attends over
+ * n_mem_chunks*t + read_fill + 1 keys; the caller then sets read_fill += 1.
+ * Without: the query attends over n_mem_chunks*t + read_fill keys (>= 1 required,
+ * read_fill <= R) and the cache is not modified.
+ * workspace: device scratch of at least loma_decode_workspace_bytes(...) bytes for the
+ * split-K partial results (may be NULL when that function returns 0).  Contents are
+ * don't-care on entry and exit; calls sharing a workspace must be stream-ordered.
+ * The result is deterministic (fixed combine order, no atomics).
+ */
+int loma_decode_attn(const void* q, const void* k_new, const void* v_new,
+                     const void* k_memcache, const void* v_memcache,
+                     void* k_read, void* v_read, void* out,
+                     int B, int H, int head_dim, int t, int c,
+                     int n_mem_chunks, int mem_capacity, int read_fill,
+                     float scale, int dtype,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Bytes of workspace loma_decode_attn needs for this shape at ANY read_fill in [0, R]
+ * (with or without k_new).  0 on invalid arguments.  Host-only arithmetic.
+ */
+size_t loma_decode_workspace_bytes(int B, int H, int head_dim, int t, int c,
+                                   int n_mem_chunks, int dtype);
+
+/*
+ * Host-only view of the mask pass's tile schedule (Sec. 4.3 mask -> work list), for
+ * inspection and tests; launches nothing.
+ *   loma_mask_schedule_size: number of workgroups the MFMA mask-pass kernel launches
+ *     for this shape (0 if the shape does not take that kernel).
+ *   loma_mask_schedule_item: decodes workgroup `block` into
+ *     item[0] = b*H + h, item[1] = chunk, item[2] = zone (0 read, 1 memory, 2 repetition),
+ *     item[3] = first row of the zone handled, item[4] = number of rows handled,
+ *     item[5] = number of keys it visits;  returns 1 if the workgroup has work, 0 if it
+ *     is padding, negative on bad arguments.
+ */
+long long loma_mask_schedule_size(int B, int H, int head_dim, int t, int c, int n_chunks, int dtype);
+int loma_mask_schedule_item(int B, int H, int head_dim, int t, int c, int n_chunks, int dtype,
+                            long long block, int item[6]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOMA_H_ */

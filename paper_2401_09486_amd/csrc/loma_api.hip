@@ -1,0 +1,144 @@
+// C ABI of libloma: argument checking on the host, then dispatch to the kernels.
+// Nothing here allocates, frees or synchronises; every error is detected before a launch.
+#include <cmath>
+#include <cstdint>
+
+#include "loma_internal.h"
+
+namespace {
+
+using loma::Geometry;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool good_ptr(const void* p) { return p != nullptr && aligned16(p); }
+
+// B, H, head_dim, t, c, dtype, scale: shared by all entry points
+int check_common(int B, int H, int head_dim, int t, int c, float scale, int dtype) {
+    if (B < 1 || H < 1 || t < 1 || c < 1) return LOMA_ERR_INVALID_ARG;
+    if (!(scale > 0.f) || !std::isfinite(scale)) return LOMA_ERR_INVALID_ARG;
+    if (dtype != LOMA_F32 && dtype != LOMA_BF16) return LOMA_ERR_UNSUPPORTED;
+    if (head_dim < 8 || head_dim > 256 || head_dim % 8 != 0) return LOMA_ERR_UNSUPPORTED;
+    if ((long long)B * H > 0x7fffffffLL) return LOMA_ERR_UNSUPPORTED;
+    if ((long long)t * c > (1 << 24)) return LOMA_ERR_UNSUPPORTED;
+    return LOMA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* loma_status_string(int status) {
+    switch (status) {
+        case LOMA_OK: return "ok";
+        case LOMA_ERR_INVALID_ARG: return "invalid argument";
+        case LOMA_ERR_UNSUPPORTED: return "unsupported dtype, head_dim or size";
+        case LOMA_ERR_WORKSPACE: return "workspace missing or too small";
+        case LOMA_ERR_LAUNCH: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int loma_abi_version(void) { return 1; }
+
+int loma_mask_attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
+                       int B, int H, int head_dim, int t, int c, int n_chunks,
+                       float scale, int dtype, void* stream) {
+    if (int rc = check_common(B, H, head_dim, t, c, scale, dtype)) return rc;
+    if (n_chunks < 1) return LOMA_ERR_INVALID_ARG;
+    if (!good_ptr(q) || !good_ptr(k) || !good_ptr(v) || !good_ptr(out)) return LOMA_ERR_INVALID_ARG;
+    if (lse != nullptr && (reinterpret_cast<uintptr_t>(lse) & 3u)) return LOMA_ERR_INVALID_ARG;
+    Geometry g;
+    g.t = t; g.c = c; g.n = n_chunks; g.R = t * c; g.s = t * (2 * c + 1);
+    const long long S = (long long)n_chunks * g.s;
+    if (S > (1LL << 30)) return LOMA_ERR_UNSUPPORTED;
+    g.S = (int)S;
+    const int nbh = B * H;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (loma::use_mfma_path(dtype, head_dim))
+        return loma::launch_mask_attn_mfma(q, k, v, out, lse, nbh, head_dim, g, scale, st);
+    return loma::launch_mask_attn_generic(q, k, v, out, lse, nbh, head_dim, g, scale, dtype, st);
+}
+
+int loma_compress_step(const void* q_mem, const void* k_mem, const void* v_mem,
+                       const void* k_read, const void* v_read,
+                       void* k_memcache, void* v_memcache, void* out,
+                       int B, int H, int head_dim, int t, int c,
+                       int n_mem_chunks, int mem_capacity,
+                       float scale, int dtype, void* stream) {
+    if (int rc = check_common(B, H, head_dim, t, c, scale, dtype)) return rc;
+    if (n_mem_chunks < 0 || mem_capacity < 1) return LOMA_ERR_INVALID_ARG;
+    if (((long long)n_mem_chunks + 1) * t > mem_capacity) return LOMA_ERR_INVALID_ARG;
+    if (!good_ptr(q_mem) || !good_ptr(k_mem) || !good_ptr(v_mem) || !good_ptr(k_read) || !good_ptr(v_read) ||
+        !good_ptr(k_memcache) || !good_ptr(v_memcache) || !good_ptr(out))
+        return LOMA_ERR_INVALID_ARG;
+    const int nbh = B * H;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (loma::use_mfma_path(dtype, head_dim))
+        return loma::launch_compress_mfma(q_mem, k_mem, v_mem, k_read, v_read, k_memcache, v_memcache, out,
+                                          nbh, head_dim, t, c, n_mem_chunks, mem_capacity, scale, st);
+    return loma::launch_compress_generic(q_mem, k_mem, v_mem, k_read, v_read, k_memcache, v_memcache, out,
+                                         nbh, head_dim, t, c, n_mem_chunks, mem_capacity, scale, dtype, st);
+}
+
+size_t loma_decode_workspace_bytes(int B, int H, int head_dim, int t, int c, int n_mem_chunks, int dtype) {
+    if (check_common(B, H, head_dim, t, c, 1.f, dtype) != LOMA_OK || n_mem_chunks < 0) return 0;
+    if (!loma::use_mfma_path(dtype, head_dim)) return 0;
+    const long long nmax = (long long)n_mem_chunks * t + (long long)t * c;
+    if (nmax > 0x7fffffffLL) return 0;
+    return loma::decode_workspace_bytes(B * H, head_dim, (int)nmax);
+}
+
+int loma_decode_attn(const void* q, const void* k_new, const void* v_new,
+                     const void* k_memcache, const void* v_memcache,
+                     void* k_read, void* v_read, void* out,
+                     int B, int H, int head_dim, int t, int c,
+                     int n_mem_chunks, int mem_capacity, int read_fill,
+                     float scale, int dtype,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+    if (int rc = check_common(B, H, head_dim, t, c, scale, dtype)) return rc;
+    const int R = t * c;
+    if (n_mem_chunks < 0 || mem_capacity < 0 || read_fill < 0) return LOMA_ERR_INVALID_ARG;
+    const long long n_mem_keys = (long long)n_mem_chunks * t;
+    if (n_mem_keys > mem_capacity) return LOMA_ERR_INVALID_ARG;
+    if ((k_new == nullptr) != (v_new == nullptr)) return LOMA_ERR_INVALID_ARG;
+    const bool has_new = k_new != nullptr;
+    // Appendix A keeps the reading zone shorter than t*c whenever a token is fed
+    if (has_new ? read_fill >= R : read_fill > R) return LOMA_ERR_INVALID_ARG;
+    if (n_mem_keys + read_fill + (has_new ? 1 : 0) < 1) return LOMA_ERR_INVALID_ARG;
+    if (!good_ptr(q) || !good_ptr(out) || !good_ptr(k_read) || !good_ptr(v_read)) return LOMA_ERR_INVALID_ARG;
+    if (has_new && (!aligned16(k_new) || !aligned16(v_new))) return LOMA_ERR_INVALID_ARG;
+    if (n_mem_chunks > 0 && (!good_ptr(k_memcache) || !good_ptr(v_memcache))) return LOMA_ERR_INVALID_ARG;
+    const int nbh = B * H;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (loma::use_mfma_path(dtype, head_dim)) {
+        const size_t need = loma::decode_workspace_bytes(nbh, head_dim, (int)n_mem_keys + R);
+        if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned16(workspace)))
+            return LOMA_ERR_WORKSPACE;
+        if (nbh > 65535) return LOMA_ERR_UNSUPPORTED;
+        return loma::launch_decode_splitk(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, nbh,
+                                          head_dim, R, (int)n_mem_keys, mem_capacity, read_fill, scale,
+                                          need > 0 ? workspace : nullptr, st);
+    }
+    return loma::launch_decode_generic(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, nbh,
+                                       head_dim, R, (int)n_mem_keys, mem_capacity, read_fill, scale, dtype, st);
+}
+
+long long loma_mask_schedule_size(int B, int H, int head_dim, int t, int c, int n_chunks, int dtype) {
+    if (check_common(B, H, head_dim, t, c, 1.f, dtype) != LOMA_OK || n_chunks < 1) return 0;
+    if (!loma::use_mfma_path(dtype, head_dim)) return 0;
+    return loma::MaskSchedule::make(B * H, t, c, n_chunks, loma::mask_block_rows(t * c)).size();
+}
+
+int loma_mask_schedule_item(int B, int H, int head_dim, int t, int c, int n_chunks, int dtype,
+                            long long block, int item[6]) {
+    if (int rc = check_common(B, H, head_dim, t, c, 1.f, dtype)) return rc;
+    if (n_chunks < 1 || item == nullptr) return LOMA_ERR_INVALID_ARG;
+    if (!loma::use_mfma_path(dtype, head_dim)) return LOMA_ERR_UNSUPPORTED;
+    const loma::MaskSchedule sch = loma::MaskSchedule::make(B * H, t, c, n_chunks, loma::mask_block_rows(t * c));
+    if (block < 0 || block >= sch.size()) return LOMA_ERR_INVALID_ARG;
+    const loma::MaskJob j = sch.decode(block);
+    item[0] = j.bh; item[1] = j.y; item[2] = j.zone; item[3] = j.o0; item[4] = j.rows; item[5] = j.nkeys;
+    return 1;
+}
+
+}  // extern "C"

@@ -1,0 +1,254 @@
+// Split-K decode attention for the generation form (Sec. 3.1 steps 1 and 3; Appendix A,
+// one new token against the compressed cache).  The query of each (b,h) sees
+//     [ n_mem_chunks*t memory-zone KVs | read_fill live reading-zone KVs | the new token ]
+// with no mask, so the step is one pass over K and V: HBM-bound (2 flop per byte).
+//
+// Grid = (key splits, B*H).  A workgroup of 4 waves streams its key range with 16-byte
+// loads: D/8 lanes cover one 2*D-byte row, so a wave-wide load instruction fetches 64/(D/8)
+// whole rows, fully coalesced; each wave keeps 8 K and 8 V loads in flight.  Scores use
+// packed bf16 dot products with fp32 accumulation and a butterfly over the lanes of a row;
+// every lane group carries its own online-softmax state (m, l, acc[8]) so the loop needs no
+// cross-group traffic.  Groups are merged through LDS at the end; splits are merged by a
+// second tiny kernel in a fixed order (deterministic, no atomics).  The new token's K/V are
+// read from k_new/v_new and appended to the reading zone by split 0 -- no workgroup reads
+// the row another one is writing.
+#include "loma_internal.h"
+
+namespace loma {
+namespace {
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef uint16_t bf16_t;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr int DEC_WAVES = 4;
+constexpr int DEC_UNROLL = 8;      // row-loads in flight per wave, for K and for V
+constexpr int DEC_TARGET_WGS = 4096;
+
+struct DecodeParams {
+    const bf16_t *q, *k_new, *v_new, *k_mem, *v_mem;
+    bf16_t *k_read, *v_read, *out;
+    float* ws_acc;   // [nbh * nsplit, D]
+    float* ws_ml;    // [nbh * nsplit, 2]
+    long mem_rows;   // mem_capacity
+    int R, n_mem, n_read, has_new, L;
+    int nsplit, keys_per_split;
+    float sc;        // scale * log2(e)
+};
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float x) {
+    uint32_t u = __float_as_uint(x);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// sum over the LPR consecutive lanes that share a key row; every lane gets the total.
+// DPP lane permutes inside a row of 16 lanes: swap neighbours, swap pairs, mirror 8, mirror 16.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+    const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false);
+    return x + __int_as_float(y);
+}
+template <int LPR>
+__device__ __forceinline__ float row_sum(float x) {
+    x = dpp_add<0xB1>(x);   // quad_perm [1,0,3,2]
+    x = dpp_add<0x4E>(x);   // quad_perm [2,3,0,1]
+    x = dpp_add<0x141>(x);  // row_half_mirror
+    if (LPR == 16) x = dpp_add<0x140>(x);  // row_mirror
+    return x;
+}
+
+template <int D>
+__global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodeParams P) {
+    constexpr int LPR = D / 8;            // lanes per key row
+    constexpr int RPL = 64 / LPR;         // rows per wave-wide load
+    constexpr int KPW = RPL * DEC_UNROLL; // keys per wave iteration
+    constexpr int NG = DEC_WAVES * RPL;   // lane groups per workgroup
+    __shared__ float sm_acc[NG][D];
+    __shared__ float sm_m[NG], sm_l[NG];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int sp = blockIdx.x;
+    const long bh = blockIdx.y;
+    const int col = lane % LPR, sub = lane / LPR;
+    const int kbeg = sp * P.keys_per_split;
+    const int kend = min(P.L, kbeg + P.keys_per_split);
+
+    const bf16_t* kmem = P.k_mem + bh * P.mem_rows * D;
+    const bf16_t* vmem = P.v_mem + bh * P.mem_rows * D;
+    const bf16_t* kread = P.k_read + bh * (long)P.R * D;
+    const bf16_t* vread = P.v_read + bh * (long)P.R * D;
+    const bf16_t* knew = P.k_new + bh * D;
+    const bf16_t* vnew = P.v_new + bh * D;
+
+    const uint4 qv = *reinterpret_cast<const uint4*>(P.q + bh * D + col * 8);
+    const bf16x2 q0 = __builtin_bit_cast(bf16x2, qv.x), q1 = __builtin_bit_cast(bf16x2, qv.y);
+    const bf16x2 q2 = __builtin_bit_cast(bf16x2, qv.z), q3 = __builtin_bit_cast(bf16x2, qv.w);
+
+    float m = -INFINITY, l = 0.f;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    for (int base = kbeg + w * KPW; base < kend; base += DEC_WAVES * KPW) {
+        u32x4 kk[DEC_UNROLL], vv[DEC_UNROLL];
+#pragma unroll
+        for (int u = 0; u < DEC_UNROLL; ++u) {
+            const int j = base + u * RPL + sub;
+            kk[u] = u32x4{0, 0, 0, 0};
+            vv[u] = u32x4{0, 0, 0, 0};
+            if (j < kend) {
+                const bf16_t *kp, *vp;
+                if (j < P.n_mem) { kp = kmem + (long)j * D; vp = vmem + (long)j * D; }
+                else if (j < P.n_mem + P.n_read) { kp = kread + (long)(j - P.n_mem) * D; vp = vread + (long)(j - P.n_mem) * D; }
+                else { kp = knew; vp = vnew; }
+                kk[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + col * 8));
+                vv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vp + col * 8));
+            }
+        }
+        float s[DEC_UNROLL];
+        float mx = m;
+#pragma unroll
+        for (int u = 0; u < DEC_UNROLL; ++u) {
+            float a = __builtin_amdgcn_fdot2_f32_bf16(q0, __builtin_bit_cast(bf16x2, kk[u].x), 0.f, false);
+            a = __builtin_amdgcn_fdot2_f32_bf16(q1, __builtin_bit_cast(bf16x2, kk[u].y), a, false);
+            a = __builtin_amdgcn_fdot2_f32_bf16(q2, __builtin_bit_cast(bf16x2, kk[u].z), a, false);
+            a = __builtin_amdgcn_fdot2_f32_bf16(q3, __builtin_bit_cast(bf16x2, kk[u].w), a, false);
+            a = row_sum<LPR>(a) * P.sc;
+            s[u] = (base + u * RPL + sub < kend) ? a : -INFINITY;
+            mx = fmaxf(mx, s[u]);
+        }
+        // mx stays -inf only while this lane group has seen no key at all
+        const float alpha = (mx == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m - mx);
+        float ps = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] *= alpha;
+#pragma unroll
+        for (int u = 0; u < DEC_UNROLL; ++u) {
+            const float p = (s[u] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(s[u] - mx);
+            ps += p;
+            acc[0] = fmaf(p, bf16_lo(vv[u].x), acc[0]);
+            acc[1] = fmaf(p, bf16_hi(vv[u].x), acc[1]);
+            acc[2] = fmaf(p, bf16_lo(vv[u].y), acc[2]);
+            acc[3] = fmaf(p, bf16_hi(vv[u].y), acc[3]);
+            acc[4] = fmaf(p, bf16_lo(vv[u].z), acc[4]);
+            acc[5] = fmaf(p, bf16_hi(vv[u].z), acc[5]);
+            acc[6] = fmaf(p, bf16_lo(vv[u].w), acc[6]);
+            acc[7] = fmaf(p, bf16_hi(vv[u].w), acc[7]);
+        }
+        l = l * alpha + ps;
+        m = mx;
+    }
+
+    // merge the lane groups of the workgroup
+    const int grp = w * RPL + sub;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sm_acc[grp][col * 8 + e] = acc[e];
+    if (col == 0) { sm_m[grp] = m; sm_l[grp] = l; }
+    __syncthreads();
+    if (tid < D) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int gidx = 0; gidx < NG; ++gidx) M = fmaxf(M, sm_m[gidx]);
+        float Lsum = 0.f, o = 0.f;
+#pragma unroll
+        for (int gidx = 0; gidx < NG; ++gidx) {
+            const float wgt = (sm_m[gidx] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sm_m[gidx] - M);
+            Lsum = fmaf(sm_l[gidx], wgt, Lsum);
+            o = fmaf(sm_acc[gidx][tid], wgt, o);
+        }
+        if (P.nsplit == 1) {
+            P.out[bh * D + tid] = f32_to_bf16(o / Lsum);
+        } else {
+            const long pi = bh * P.nsplit + sp;
+            P.ws_acc[pi * D + tid] = o;
+            if (tid == 0) { P.ws_ml[pi * 2] = M; P.ws_ml[pi * 2 + 1] = Lsum; }
+        }
+    }
+    // append the new token to the reading zone (Appendix A: the cache grows by the input token)
+    if (P.has_new && sp == 0 && tid < 2 * LPR) {
+        const int which = tid / LPR, piece = tid % LPR;
+        const uint4 x = *reinterpret_cast<const uint4*>((which ? vnew : knew) + piece * 8);
+        bf16_t* dst = (which ? P.v_read : P.k_read) + (bh * (long)P.R + P.n_read) * D;
+        *reinterpret_cast<uint4*>(dst + piece * 8) = x;
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(D) void decode_combine_kernel(DecodeParams P) {
+    const long bh = blockIdx.x;
+    const int tid = threadIdx.x;
+    float M = -INFINITY;
+    for (int sp = 0; sp < P.nsplit; ++sp) M = fmaxf(M, P.ws_ml[(bh * P.nsplit + sp) * 2]);
+    float Lsum = 0.f, o = 0.f;
+    for (int sp = 0; sp < P.nsplit; ++sp) {
+        const long pi = bh * P.nsplit + sp;
+        const float ms = P.ws_ml[pi * 2];
+        const float wgt = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
+        Lsum = fmaf(P.ws_ml[pi * 2 + 1], wgt, Lsum);
+        o = fmaf(P.ws_acc[pi * D + tid], wgt, o);
+    }
+    P.out[bh * D + tid] = f32_to_bf16(o / Lsum);
+}
+
+inline int target_splits(int nbh) { return (DEC_TARGET_WGS + nbh - 1) / nbh; }
+
+// keys per split: whole workgroup iterations, at most target_splits(nbh) splits
+template <int D>
+void plan_splits(int nbh, int n_keys, int& nsplit, int& keys_per_split) {
+    constexpr int KPI = DEC_WAVES * (64 / (D / 8)) * DEC_UNROLL;  // keys per workgroup iteration
+    const int units = (n_keys + KPI - 1) / KPI;
+    const int tgt = target_splits(nbh);
+    const int ups = (units + tgt - 1) / tgt;
+    nsplit = (units + ups - 1) / ups;
+    keys_per_split = ups * KPI;
+}
+
+template <int D>
+int launch_decode_d(DecodeParams& P, int nbh, void* workspace, hipStream_t st) {
+    plan_splits<D>(nbh, P.L, P.nsplit, P.keys_per_split);
+    P.ws_acc = static_cast<float*>(workspace);
+    P.ws_ml = P.ws_acc ? P.ws_acc + (size_t)nbh * target_splits(nbh) * D : nullptr;
+    if (nbh > 65535) return LOMA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(decode_split_kernel<D>, dim3(P.nsplit, nbh), dim3(64 * DEC_WAVES), 0, st, P);
+    if (hipGetLastError() != hipSuccess) return LOMA_ERR_LAUNCH;
+    if (P.nsplit > 1) {
+        hipLaunchKernelGGL(decode_combine_kernel<D>, dim3(nbh), dim3(D), 0, st, P);
+        if (hipGetLastError() != hipSuccess) return LOMA_ERR_LAUNCH;
+    }
+    return LOMA_OK;
+}
+
+}  // namespace
+
+int decode_num_splits(int nbh, int n_keys) {
+    int ns, kps;
+    plan_splits<128>(nbh, n_keys, ns, kps);
+    return ns;
+}
+
+size_t decode_workspace_bytes(int nbh, int D, int /*n_keys_max*/) {
+    const int tgt = target_splits(nbh);
+    if (tgt <= 1) return 0;
+    return (size_t)nbh * tgt * (D + 2) * sizeof(float);
+}
+
+int launch_decode_splitk(const void* q, const void* k_new, const void* v_new,
+                         const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
+                         void* out, int nbh, int D, int R, int n_mem_keys, int mem_capacity, int read_fill,
+                         float scale, void* workspace, hipStream_t st) {
+    DecodeParams P;
+    P.q = static_cast<const bf16_t*>(q);
+    P.k_new = static_cast<const bf16_t*>(k_new); P.v_new = static_cast<const bf16_t*>(v_new);
+    P.k_mem = static_cast<const bf16_t*>(k_memcache); P.v_mem = static_cast<const bf16_t*>(v_memcache);
+    P.k_read = static_cast<bf16_t*>(k_read); P.v_read = static_cast<bf16_t*>(v_read);
+    P.out = static_cast<bf16_t*>(out);
+    P.mem_rows = mem_capacity; P.R = R; P.n_mem = n_mem_keys; P.n_read = read_fill;
+    P.has_new = k_new != nullptr;
+    P.L = n_mem_keys + read_fill + (P.has_new ? 1 : 0);
+    P.sc = scale * LOG2E;
+    return D == 128 ? launch_decode_d<128>(P, nbh, workspace, st) : launch_decode_d<64>(P, nbh, workspace, st);
+}
+
+}  // namespace loma

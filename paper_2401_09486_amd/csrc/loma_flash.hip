@@ -1,0 +1,511 @@
+// MFMA kernels of the LoMA hot path for gfx950: the mask pass (Sec. 4.3 Eq. 1-3 with
+// Sec. 4.4 Eq. 5-7) and the compression pass of the generation form (Sec. 3.1 step 2).
+//
+// One workgroup owns up to 32*NW query rows of ONE zone of ONE chunk; every wave owns 32 of
+// them.  The keys such a block can see form a short list of contiguous row ranges that
+// follows from (chunk, zone) alone -- the mask is never stored and tiles outside the list
+// are never touched:
+//     reading rows   : memory zones of chunks 0..y-1 (t rows every s rows), then rows
+//                      0..o of the own reading zone (causal, only the last tiles are cut);
+//     memory rows    : the own reading zone followed by the own memory zone, uncut;
+//     repetition rows: the own memory zone, plus each row's own key (done on the vector
+//                      ALU from registers: a diagonal is no MFMA tile).
+// Per 32x32 tile the scores are produced TRANSPOSED, S^T = K Q^T (keys down the rows,
+// queries across the lanes), so a query's softmax statistics live in two lanes (l, l^32)
+// and the probabilities come out of the accumulators already in the register layout the
+// second product O^T += V^T P^T wants as its B operand.  K tiles sit in LDS row-major; V tiles
+// are written to LDS transposed (head-dim major, keys permuted to match that layout) so both
+// MFMA A operands are single 16-byte LDS reads.  Tiles are double-buffered: global loads for
+// tile i+1 are in flight while tile i is multiplied; one barrier per tile.
+#include "loma_internal.h"
+
+namespace loma {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef uint16_t bf16_t;  // storage type of bf16 tensors
+
+constexpr int NO_CAUSAL = 1 << 29;
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+struct FlashJob {
+    const bf16_t* q;   // first query row of this block, rows contiguous
+    bf16_t* out;
+    float* lse;        // first row's slot, or nullptr
+    int q_rows;        // valid rows in this block
+    // keys: three ranges walked back to back; range 0 is slab-strided
+    const bf16_t *k0, *k1, *k2, *v0, *v1, *v2;
+    int n0, n1, n2;
+    int slab;          // rows per slab in range 0
+    long slab_stride;  // elements between slabs
+    int causal_base;   // key j is visible to block row r iff j <= causal_base + r
+    const bf16_t *k_self, *v_self;  // rows aligned with q (repetition zone) or nullptr
+};
+
+template <int D, int NW, int BN>
+struct Cfg {
+    static constexpr int NT = 64 * NW;
+    static constexpr int BM = 32 * NW;
+    static constexpr int CPR = D / 8;        // 16-byte pieces per row
+    static constexpr int KSTR = D + 8;       // K tile row stride (elements): 16B-aligned, bank-spread
+    static constexpr int VSTR = BN + 8;      // transposed V tile row stride
+    static constexpr int KBUF = BN * KSTR;
+    static constexpr int VBUF = D * VSTR;
+    static constexpr int SMEM_BYTES = 2 * (KBUF + VBUF) * 2;
+    static constexpr int NTASK = (BN / 4) * CPR;          // (4 keys) x (8 head-dim) load tasks
+    static constexpr int TPT = (NTASK + NT - 1) / NT;     // tasks per thread
+    static constexpr int NSUB = BN / 32;
+    static constexpr int KSTEPS = D / 16;
+    static constexpr int DT = D / 32;
+    static_assert(BN % 32 == 0 && D % 32 == 0, "tile shape");
+    static_assert(2 * KBUF >= NW * 32 * KSTR, "output staging must fit in the K buffers");
+};
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// two floats -> packed bf16 pair, round to nearest even
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    f32x2 f = {a, b};
+    bf16x2 h = __builtin_convertvector(f, bf16x2);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+// value held by the other half-wave's lane (l ^ 32) and own value: returns max / sum over the pair
+__device__ __forceinline__ float pair_max(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pair_sum(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+template <int D>
+__device__ __forceinline__ void key_row(const FlashJob& J, int j, const bf16_t*& kp, const bf16_t*& vp) {
+    if (j < J.n0) {
+        const int a = j / J.slab;
+        const long off = (long)a * J.slab_stride + (long)(j - a * J.slab) * D;
+        kp = J.k0 + off; vp = J.v0 + off;
+    } else if (j < J.n0 + J.n1) {
+        const long off = (long)(j - J.n0) * D;
+        kp = J.k1 + off; vp = J.v1 + off;
+    } else {
+        const long off = (long)(j - J.n0 - J.n1) * D;
+        kp = J.k2 + off; vp = J.v2 + off;
+    }
+}
+
+template <int D, int NW, int BN>
+__device__ __forceinline__ void load_tile(const FlashJob& J, int k0, int nkeys, int tid,
+                                          uint4 (&kreg)[Cfg<D, NW, BN>::TPT][4],
+                                          uint4 (&vreg)[Cfg<D, NW, BN>::TPT][4]) {
+    using C = Cfg<D, NW, BN>;
+#pragma unroll
+    for (int i = 0; i < C::TPT; ++i) {
+        const int task = tid + i * C::NT;
+        const int dch = task % C::CPR, kg = task / C::CPR;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int j = k0 + 4 * kg + b;
+            kreg[i][b] = make_uint4(0, 0, 0, 0);
+            vreg[i][b] = make_uint4(0, 0, 0, 0);
+            if (task < C::NTASK && j < nkeys) {
+                const bf16_t *kp, *vp;
+                key_row<D>(J, j, kp, vp);
+                kreg[i][b] = *reinterpret_cast<const uint4*>(kp + dch * 8);
+                vreg[i][b] = *reinterpret_cast<const uint4*>(vp + dch * 8);
+            }
+        }
+    }
+}
+
+// K: row-major.  V: transposed, and inside every group of 16 keys the key 8a+4g+b sits at
+// slot 8g+4a+b -- the order in which the probabilities sit in the score accumulators.
+template <int D, int NW, int BN>
+__device__ __forceinline__ void store_tile(bf16_t* Kb, bf16_t* Vb, int tid,
+                                           const uint4 (&kreg)[Cfg<D, NW, BN>::TPT][4],
+                                           const uint4 (&vreg)[Cfg<D, NW, BN>::TPT][4]) {
+    using C = Cfg<D, NW, BN>;
+#pragma unroll
+    for (int i = 0; i < C::TPT; ++i) {
+        const int task = tid + i * C::NT;
+        if (task >= C::NTASK) continue;
+        const int dch = task % C::CPR, kg = task / C::CPR;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+            *reinterpret_cast<uint4*>(Kb + (4 * kg + b) * C::KSTR + dch * 8) = kreg[i][b];
+        // kg = 4*j16 + 2*a + g  ->  first slot 16*j16 + 8*g + 4*a
+        const int slot = 16 * (kg >> 2) + 8 * (kg & 1) + 4 * ((kg >> 1) & 1);
+        const uint32_t r0[4] = {vreg[i][0].x, vreg[i][0].y, vreg[i][0].z, vreg[i][0].w};
+        const uint32_t r1[4] = {vreg[i][1].x, vreg[i][1].y, vreg[i][1].z, vreg[i][1].w};
+        const uint32_t r2[4] = {vreg[i][2].x, vreg[i][2].y, vreg[i][2].z, vreg[i][2].w};
+        const uint32_t r3[4] = {vreg[i][3].x, vreg[i][3].y, vreg[i][3].z, vreg[i][3].w};
+#pragma unroll
+        for (int wd = 0; wd < 4; ++wd) {
+            // element 2*wd (low halves) and 2*wd+1 (high halves) of the four keys
+            uint2 lo, hi;
+            lo.x = __builtin_amdgcn_perm(r1[wd], r0[wd], 0x05040100u);
+            lo.y = __builtin_amdgcn_perm(r3[wd], r2[wd], 0x05040100u);
+            hi.x = __builtin_amdgcn_perm(r1[wd], r0[wd], 0x07060302u);
+            hi.y = __builtin_amdgcn_perm(r3[wd], r2[wd], 0x07060302u);
+            *reinterpret_cast<uint2*>(Vb + (dch * 8 + 2 * wd) * C::VSTR + slot) = lo;
+            *reinterpret_cast<uint2*>(Vb + (dch * 8 + 2 * wd + 1) * C::VSTR + slot) = hi;
+        }
+    }
+}
+
+template <int D, int NW, int BN>
+__device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* smem) {
+    using C = Cfg<D, NW, BN>;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int g = lane >> 5, l32 = lane & 31;
+    bf16_t* Ks = smem;
+    bf16_t* Vt = smem + 2 * C::KBUF;
+
+    const int nkeys = J.n0 + J.n1 + J.n2;
+    const int kend_wg = min(nkeys, J.causal_base + J.q_rows);
+    const int ntiles = (kend_wg + BN - 1) / BN;
+    const int row0 = 32 * w;                       // first block row of this wave
+    const bool has_rows = row0 < J.q_rows;
+    const int row_hi = min(row0 + 32, J.q_rows);   // exclusive
+    const int kend_w = has_rows ? min(nkeys, J.causal_base + row_hi) : 0;
+    const int my_row = min(row0 + l32, J.q_rows - 1);          // padded lanes replay the last row
+    const int my_lim = min(J.causal_base + my_row, nkeys - 1);  // last key this lane's query sees
+    const int wave_lim = min(J.causal_base + row0, nkeys - 1);  // the smallest such limit in the wave
+
+    // Q^T as the B operand: lane (query l32, half g) holds head-dim 16*ks + 8*g .. +7
+    bf16x8 qreg[C::KSTEPS];
+    {
+        const bool ok = row0 + l32 < J.q_rows;
+        const bf16_t* qp = J.q + (long)(row0 + l32) * D + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < C::KSTEPS; ++ks) {
+            uint4 x = make_uint4(0, 0, 0, 0);
+            if (ok) x = *reinterpret_cast<const uint4*>(qp + 16 * ks);
+            qreg[ks] = __builtin_bit_cast(bf16x8, x);
+        }
+    }
+
+    f32x16 O[C::DT];
+#pragma unroll
+    for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[dt][i] = 0.f;
+    float m = -INFINITY, lsum = 0.f;
+
+    uint4 kreg[C::TPT][4], vreg[C::TPT][4];
+    if (ntiles > 0) {
+        load_tile<D, NW, BN>(J, 0, nkeys, tid, kreg, vreg);
+        store_tile<D, NW, BN>(Ks, Vt, tid, kreg, vreg);
+    }
+    __syncthreads();
+
+    for (int kt = 0; kt < ntiles; ++kt) {
+        const int buf = kt & 1;
+        const bool more = kt + 1 < ntiles;
+        if (more) load_tile<D, NW, BN>(J, (kt + 1) * BN, nkeys, tid, kreg, vreg);
+
+        const int k0 = kt * BN;
+        if (k0 < kend_w) {
+            const bf16_t* Kb = Ks + buf * C::KBUF;
+            const bf16_t* Vb = Vt + buf * C::VBUF;
+            const int nsub = min(C::NSUB, (kend_w - k0 + 31) >> 5);
+
+            f32x16 S[C::NSUB];
+#pragma unroll
+            for (int sub = 0; sub < C::NSUB; ++sub) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) S[sub][i] = 0.f;
+                if (sub < nsub) {
+                    const bf16_t* kp = Kb + (32 * sub + l32) * C::KSTR + 8 * g;
+#pragma unroll
+                    for (int ks = 0; ks < C::KSTEPS; ++ks) {
+                        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
+                        S[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], S[sub], 0, 0, 0);
+                    }
+                }
+            }
+            // accumulator i of lane (l32, g) is key 8*(i/4) + 4*g + i%4 of the sub-tile
+            if (k0 + 32 * nsub - 1 > wave_lim) {
+#pragma unroll
+                for (int sub = 0; sub < C::NSUB; ++sub)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int j = k0 + 32 * sub + 8 * (i >> 2) + 4 * g + (i & 3);
+                        if (j > my_lim) S[sub][i] = -INFINITY;
+                    }
+            }
+            float mx = m;
+#pragma unroll
+            for (int sub = 0; sub < C::NSUB; ++sub)
+                if (sub < nsub) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[sub][i]);
+                }
+            mx = pair_max(mx);
+            const float alpha = __builtin_amdgcn_exp2f((m - mx) * sc);
+            const float mc = mx * sc;
+            float ps = 0.f;
+#pragma unroll
+            for (int sub = 0; sub < C::NSUB; ++sub)
+                if (sub < nsub) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float p = __builtin_amdgcn_exp2f(S[sub][i] * sc - mc);
+                        ps += p;
+                        S[sub][i] = p;
+                    }
+                }
+            lsum = lsum * alpha + ps;
+            m = mx;
+#pragma unroll
+            for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) O[dt][i] *= alpha;
+#pragma unroll
+            for (int sub = 0; sub < C::NSUB; ++sub)
+                if (sub < nsub) {
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj) {
+                        uint4 pw;
+                        pw.x = pack_bf16(S[sub][8 * jj + 0], S[sub][8 * jj + 1]);
+                        pw.y = pack_bf16(S[sub][8 * jj + 2], S[sub][8 * jj + 3]);
+                        pw.z = pack_bf16(S[sub][8 * jj + 4], S[sub][8 * jj + 5]);
+                        pw.w = pack_bf16(S[sub][8 * jj + 6], S[sub][8 * jj + 7]);
+                        const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
+                        const bf16_t* vp = Vb + l32 * C::VSTR + 16 * (2 * sub + jj) + 8 * g;
+#pragma unroll
+                        for (int dt = 0; dt < C::DT; ++dt) {
+                            const bf16x8 a = *reinterpret_cast<const bf16x8*>(vp + 32 * dt * C::VSTR);
+                            O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, O[dt], 0, 0, 0);
+                        }
+                    }
+                }
+        }
+
+        if (more) store_tile<D, NW, BN>(Ks + (buf ^ 1) * C::KBUF, Vt + (buf ^ 1) * C::VBUF, tid, kreg, vreg);
+        __syncthreads();
+    }
+
+    // the row's own key (identity block of Eq. 1, second term of Eq. 9), on the vector ALU
+    if (J.k_self != nullptr && has_rows) {
+        const bool ok = row0 + l32 < J.q_rows;
+        const bf16_t* kp = J.k_self + (long)(row0 + l32) * D + 8 * g;
+        float part = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < C::KSTEPS; ++ks) {
+            uint4 x = make_uint4(0, 0, 0, 0);
+            if (ok) x = *reinterpret_cast<const uint4*>(kp + 16 * ks);
+            const bf16x8 kk = __builtin_bit_cast(bf16x8, x);
+            const bf16x8 qq = qreg[ks];
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const bf16x2 a = {qq[e], qq[e + 1]};
+                const bf16x2 b = {kk[e], kk[e + 1]};
+                part = __builtin_amdgcn_fdot2_f32_bf16(a, b, part, false);
+            }
+        }
+        const float sself = pair_sum(part);
+        const float mx = fmaxf(m, sself);
+        const float alpha = __builtin_amdgcn_exp2f((m - mx) * sc);
+        const float p = __builtin_amdgcn_exp2f((sself - mx) * sc);
+        lsum = lsum * alpha + (g == 0 ? p : 0.f);
+        m = mx;
+        const bf16_t* vp = J.v_self + (long)(row0 + l32) * D + 4 * g;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                uint2 x = make_uint2(0, 0);
+                if (ok) x = *reinterpret_cast<const uint2*>(vp + 32 * dt + 8 * i4);
+                O[dt][4 * i4 + 0] = O[dt][4 * i4 + 0] * alpha + p * bf16_lo(x.x);
+                O[dt][4 * i4 + 1] = O[dt][4 * i4 + 1] * alpha + p * bf16_hi(x.x);
+                O[dt][4 * i4 + 2] = O[dt][4 * i4 + 2] * alpha + p * bf16_lo(x.y);
+                O[dt][4 * i4 + 3] = O[dt][4 * i4 + 3] * alpha + p * bf16_hi(x.y);
+            }
+    }
+
+    // normalise, transpose through LDS (the K buffers are free now), store rows coalesced
+    const float ltot = pair_sum(lsum);
+    const float inv = 1.f / ltot;
+    bf16_t* Os = smem + w * 32 * C::KSTR;
+    if (has_rows) {
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                uint2 x;
+                x.x = pack_bf16(O[dt][4 * i4 + 0] * inv, O[dt][4 * i4 + 1] * inv);
+                x.y = pack_bf16(O[dt][4 * i4 + 2] * inv, O[dt][4 * i4 + 3] * inv);
+                *reinterpret_cast<uint2*>(Os + l32 * C::KSTR + 32 * dt + 8 * i4 + 4 * g) = x;
+            }
+        if (J.lse != nullptr && g == 0 && row0 + l32 < J.q_rows)
+            J.lse[row0 + l32] = (m * sc + __builtin_amdgcn_logf(ltot)) * LN2;
+    }
+    __syncthreads();
+    if (has_rows) {
+#pragma unroll
+        for (int it = 0; it < 32 * C::CPR / 64; ++it) {
+            const int idx = it * 64 + lane;
+            const int r = idx / C::CPR, ch = idx % C::CPR;
+            if (row0 + r < J.q_rows)
+                *reinterpret_cast<uint4*>(J.out + (long)(row0 + r) * D + ch * 8) =
+                    *reinterpret_cast<const uint4*>(Os + r * C::KSTR + ch * 8);
+        }
+    }
+}
+
+// ---- mask pass -------------------------------------------------------------------------------
+struct MaskParams {
+    const bf16_t *q, *k, *v;
+    bf16_t* out;
+    float* lse;
+    MaskSchedule sched;
+    float sc;  // scale * log2(e)
+};
+
+template <int D, int NW, int BN>
+__global__ __launch_bounds__(64 * NW) void mask_attn_kernel(MaskParams P) {
+    extern __shared__ __align__(16) bf16_t smem[];
+    const MaskSchedule& sch = P.sched;
+    const MaskJob mj = sch.decode(blockIdx.x);
+    const long seq = (long)mj.bh * sch.n * sch.s;   // first row of this (b,h)
+    const long chunk = seq + (long)mj.y * sch.s;    // first row of the chunk
+    FlashJob J;
+    J.k0 = J.k1 = J.k2 = P.k;
+    J.v0 = J.v1 = J.v2 = P.v;
+    J.n0 = J.n1 = J.n2 = 0;
+    J.slab = 1; J.slab_stride = 0;
+    J.causal_base = NO_CAUSAL;
+    J.k_self = J.v_self = nullptr;
+    J.q_rows = mj.rows;
+    long qrow;
+    if (mj.zone == ZONE_READ) {
+        qrow = chunk + mj.o0;
+        J.k0 = P.k + (seq + sch.R) * D; J.v0 = P.v + (seq + sch.R) * D;   // memory zone of chunk 0
+        J.n0 = mj.y * sch.t; J.slab = sch.t; J.slab_stride = (long)sch.s * D;
+        J.k1 = P.k + chunk * D; J.v1 = P.v + chunk * D;
+        J.n1 = mj.o0 + mj.rows;
+        J.causal_base = mj.y * sch.t + mj.o0;
+    } else if (mj.zone == ZONE_MEM) {
+        qrow = chunk + sch.R + mj.o0;
+        J.k1 = P.k + chunk * D; J.v1 = P.v + chunk * D;
+        J.n1 = sch.R + sch.t;
+    } else {
+        qrow = chunk + sch.R + sch.t + mj.o0;
+        J.k1 = P.k + (chunk + sch.R) * D; J.v1 = P.v + (chunk + sch.R) * D;
+        J.n1 = sch.t;
+        J.k_self = P.k + qrow * D; J.v_self = P.v + qrow * D;
+    }
+    J.q = P.q + qrow * D;
+    J.out = P.out + qrow * D;
+    J.lse = P.lse ? P.lse + qrow : nullptr;
+    flash_job<D, NW, BN>(J, P.sc, smem);
+}
+
+// ---- compression pass ----------------------------------------------------------------------------
+struct CompressParams {
+    const bf16_t *q_mem, *k_mem, *v_mem, *k_read, *v_read;
+    bf16_t *k_cache, *v_cache, *out;
+    int t, R, nblk;         // nblk = row blocks per (b,h)
+    long cache_row0;        // n_mem_chunks * t
+    long cache_rows;        // mem_capacity
+    float sc;
+};
+
+template <int D, int NW, int BN>
+__global__ __launch_bounds__(64 * NW) void compress_kernel(CompressParams P) {
+    extern __shared__ __align__(16) bf16_t smem[];
+    constexpr int BM = 32 * NW;
+    const int bh = blockIdx.x / P.nblk, blk = blockIdx.x % P.nblk;
+    const int o0 = blk * BM;
+    FlashJob J;
+    J.k0 = J.v0 = nullptr; J.n0 = 0; J.slab = 1; J.slab_stride = 0;
+    J.k1 = P.k_read + (long)bh * P.R * D; J.v1 = P.v_read + (long)bh * P.R * D; J.n1 = P.R;
+    J.k2 = P.k_mem + (long)bh * P.t * D;  J.v2 = P.v_mem + (long)bh * P.t * D;  J.n2 = P.t;
+    J.causal_base = NO_CAUSAL;
+    J.k_self = J.v_self = nullptr;
+    J.q_rows = min(BM, P.t - o0);
+    J.q = P.q_mem + ((long)bh * P.t + o0) * D;
+    J.out = P.out + ((long)bh * P.t + o0) * D;
+    J.lse = nullptr;
+    flash_job<D, NW, BN>(J, P.sc, smem);
+    // splice: the t new memory KVs join the compressed cache (Sec. 3.1 step 3)
+    if (blk == 0) {
+        const int pieces = P.t * D / 8;
+        const uint4* ks = reinterpret_cast<const uint4*>(J.k2);
+        const uint4* vs = reinterpret_cast<const uint4*>(J.v2);
+        uint4* kd = reinterpret_cast<uint4*>(P.k_cache + ((long)bh * P.cache_rows + P.cache_row0) * D);
+        uint4* vd = reinterpret_cast<uint4*>(P.v_cache + ((long)bh * P.cache_rows + P.cache_row0) * D);
+        for (int i = threadIdx.x; i < pieces; i += 64 * NW) { kd[i] = ks[i]; vd[i] = vs[i]; }
+    }
+}
+
+template <typename K, typename P>
+int launch(K kernel, long long grid, int threads, int smem_bytes, const P& params, hipStream_t st) {
+    if (grid <= 0) return LOMA_OK;
+    if (grid > 0x7fffffffLL) return LOMA_ERR_UNSUPPORTED;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            smem_bytes) != hipSuccess)
+        return LOMA_ERR_LAUNCH;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(threads), smem_bytes, st, params);
+    return hipGetLastError() == hipSuccess ? LOMA_OK : LOMA_ERR_LAUNCH;
+}
+
+template <int D>
+int launch_mask_d(const MaskParams& P, int bm, hipStream_t st) {
+    const long long grid = P.sched.size();
+    if (bm == 128) return launch(mask_attn_kernel<D, 4, 64>, grid, 256, Cfg<D, 4, 64>::SMEM_BYTES, P, st);
+    if (bm == 64) return launch(mask_attn_kernel<D, 2, 32>, grid, 128, Cfg<D, 2, 32>::SMEM_BYTES, P, st);
+    return launch(mask_attn_kernel<D, 1, 32>, grid, 64, Cfg<D, 1, 32>::SMEM_BYTES, P, st);
+}
+
+template <int D>
+int launch_compress_d(CompressParams& P, int nbh, hipStream_t st) {
+    if (P.t > 64) {
+        P.nblk = (P.t + 127) / 128;
+        return launch(compress_kernel<D, 4, 64>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64>::SMEM_BYTES, P, st);
+    }
+    if (P.t > 32) {
+        P.nblk = 1;
+        return launch(compress_kernel<D, 2, 32>, nbh, 128, Cfg<D, 2, 32>::SMEM_BYTES, P, st);
+    }
+    P.nblk = 1;
+    return launch(compress_kernel<D, 1, 32>, nbh, 64, Cfg<D, 1, 32>::SMEM_BYTES, P, st);
+}
+
+}  // namespace
+
+int launch_mask_attn_mfma(const void* q, const void* k, const void* v, void* out, float* lse,
+                          int nbh, int D, const Geometry& g, float scale, hipStream_t st) {
+    MaskParams P;
+    P.q = static_cast<const bf16_t*>(q); P.k = static_cast<const bf16_t*>(k); P.v = static_cast<const bf16_t*>(v);
+    P.out = static_cast<bf16_t*>(out); P.lse = lse;
+    const int bm = mask_block_rows(g.R);
+    P.sched = MaskSchedule::make(nbh, g.t, g.c, g.n, bm);
+    P.sc = scale * LOG2E;
+    return D == 128 ? launch_mask_d<128>(P, bm, st) : launch_mask_d<64>(P, bm, st);
+}
+
+int launch_compress_mfma(const void* q_mem, const void* k_mem, const void* v_mem,
+                         const void* k_read, const void* v_read, void* k_memcache, void* v_memcache,
+                         void* out, int nbh, int D, int t, int c, int n_mem_chunks, int mem_capacity,
+                         float scale, hipStream_t st) {
+    CompressParams P;
+    P.q_mem = static_cast<const bf16_t*>(q_mem); P.k_mem = static_cast<const bf16_t*>(k_mem);
+    P.v_mem = static_cast<const bf16_t*>(v_mem); P.k_read = static_cast<const bf16_t*>(k_read);
+    P.v_read = static_cast<const bf16_t*>(v_read);
+    P.k_cache = static_cast<bf16_t*>(k_memcache); P.v_cache = static_cast<bf16_t*>(v_memcache);
+    P.out = static_cast<bf16_t*>(out);
+    P.t = t; P.R = t * c; P.nblk = 1;
+    P.cache_row0 = (long)n_mem_chunks * t; P.cache_rows = mem_capacity;
+    P.sc = scale * LOG2E;
+    return D == 128 ? launch_compress_d<128>(P, nbh, st) : launch_compress_d<64>(P, nbh, st);
+}
+
+}  // namespace loma

@@ -1,0 +1,116 @@
+// Internal declarations shared by the translation units of libloma (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/loma.h"
+
+namespace loma {
+
+// Geometry of a restructured sample (Sec. 4.1): chunk = [R reading | t memory | R repetition].
+struct Geometry {
+    int t, c, n;
+    int R;  // t*c
+    int s;  // t*(2c+1)
+    int S;  // n*s
+};
+
+enum Zone : int { ZONE_READ = 0, ZONE_MEM = 1, ZONE_REP = 2 };
+
+// One workgroup's share of the mask pass: `rows` query rows of one zone of one chunk.
+struct MaskJob {
+    int bh;     // b*H + h
+    int y;      // chunk
+    int zone;   // Zone
+    int o0;     // first row inside the zone
+    int rows;   // rows handled (<= block rows)
+    int nkeys;  // keys this workgroup walks over (visible to its last row)
+};
+
+// Tile-schedule arithmetic, identical on host (tests, grid sizing) and device (job decode).
+// Work list per (b,h), longest first: reading blocks of the last chunk down to the first
+// (they see y*t earlier memory keys), then memory blocks, then repetition blocks.
+// Workgroup id -> (b,h) fastest, so that with B*H a multiple of 8 every (b,h) stays on one
+// XCD (workgroups are dealt round-robin to the 8 XCDs) and its memory-zone K/V stays in
+// that XCD's L2.
+struct MaskSchedule {
+    int nbh, n, t, R, s, bm;
+    int nRB, nMB;        // row blocks per reading (= repetition) zone, per memory zone
+    int jobs_per_bh;
+
+    __host__ __device__ static MaskSchedule make(int nbh, int t, int c, int n, int bm) {
+        MaskSchedule m;
+        m.nbh = nbh; m.n = n; m.t = t; m.R = t * c; m.s = t * (2 * c + 1); m.bm = bm;
+        m.nRB = (m.R + bm - 1) / bm;
+        m.nMB = (t + bm - 1) / bm;
+        m.jobs_per_bh = n * (2 * m.nRB + m.nMB);
+        return m;
+    }
+    __host__ __device__ long long size() const { return (long long)nbh * jobs_per_bh; }
+
+    __host__ __device__ MaskJob decode(long long id) const {
+        MaskJob j;
+        j.bh = (int)(id % nbh);
+        int w = (int)(id / nbh);
+        const int nread = n * nRB, nmem = n * nMB;
+        if (w < nread) {
+            j.zone = ZONE_READ;
+            j.y = n - 1 - w / nRB;
+            j.o0 = (nRB - 1 - w % nRB) * bm;
+            j.rows = (R - j.o0 < bm) ? R - j.o0 : bm;
+            j.nkeys = j.y * t + j.o0 + j.rows;
+        } else if (w < nread + nmem) {
+            w -= nread;
+            j.zone = ZONE_MEM;
+            j.y = w / nMB;
+            j.o0 = (w % nMB) * bm;
+            j.rows = (t - j.o0 < bm) ? t - j.o0 : bm;
+            j.nkeys = R + t;
+        } else {
+            w -= nread + nmem;
+            j.zone = ZONE_REP;
+            j.y = w / nRB;
+            j.o0 = (w % nRB) * bm;
+            j.rows = (R - j.o0 < bm) ? R - j.o0 : bm;
+            j.nkeys = t;  // + the row itself, handled outside the key walk
+        }
+        return j;
+    }
+};
+
+// Rows per workgroup of the MFMA mask-pass kernel for a reading-zone length R.
+inline int mask_block_rows(int R) { return R >= 128 ? 128 : (R >= 64 ? 64 : 32); }
+
+inline bool use_mfma_path(int dtype, int head_dim) {
+    return dtype == LOMA_BF16 && (head_dim == 64 || head_dim == 128);
+}
+
+// ---- launchers (each returns LOMA_OK or LOMA_ERR_LAUNCH) -----------------------------------
+int launch_mask_attn_mfma(const void* q, const void* k, const void* v, void* out, float* lse,
+                          int nbh, int D, const Geometry& g, float scale, hipStream_t st);
+int launch_compress_mfma(const void* q_mem, const void* k_mem, const void* v_mem,
+                         const void* k_read, const void* v_read, void* k_memcache, void* v_memcache,
+                         void* out, int nbh, int D, int t, int c, int n_mem_chunks, int mem_capacity,
+                         float scale, hipStream_t st);
+
+int launch_mask_attn_generic(const void* q, const void* k, const void* v, void* out, float* lse,
+                             int nbh, int D, const Geometry& g, float scale, int dtype, hipStream_t st);
+int launch_compress_generic(const void* q_mem, const void* k_mem, const void* v_mem,
+                            const void* k_read, const void* v_read, void* k_memcache, void* v_memcache,
+                            void* out, int nbh, int D, int t, int c, int n_mem_chunks, int mem_capacity,
+                            float scale, int dtype, hipStream_t st);
+int launch_decode_generic(const void* q, const void* k_new, const void* v_new,
+                          const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
+                          void* out, int nbh, int D, int R, int n_mem_keys, int mem_capacity, int read_fill,
+                          float scale, int dtype, hipStream_t st);
+
+// Split-K decode over [memory cache || reading zone || new token].
+int decode_num_splits(int nbh, int n_keys);
+size_t decode_workspace_bytes(int nbh, int D, int n_keys_max);
+int launch_decode_splitk(const void* q, const void* k_new, const void* v_new,
+                         const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
+                         void* out, int nbh, int D, int R, int n_mem_keys, int mem_capacity, int read_fill,
+                         float scale, void* workspace, hipStream_t st);
+
+}  // namespace loma

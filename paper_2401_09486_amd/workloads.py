@@ -209,3 +209,31 @@ def compress_bytes(B, H, d, t, c, dtype) -> int:
 
 def compress_useful_flops(B, H, d, t, c) -> int:
     return 4 * d * t * (t * c + t) * B * H
+
+
+# ---- device-side generation for the large generation configurations -------------------------
+def gen_initial_state_device(cfg: GenConfig, device="cuda"):
+    """Same layout as gen_initial_state, drawn on the GPU (torch generator, seed = cfg.seed):
+    the 9 GB caches of the largest configuration are not worth a trip through host memory.
+    Returns torch tensors in the storage dtype."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(cfg.seed)
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    Lm = cfg.prior_chunks * cfg.t
+
+    def draw(shape, scale):
+        out = torch.empty(shape, dtype=dt, device=device)
+        flat = out.view(shape[0] * shape[1], -1)
+        for i in range(flat.shape[0]):   # one (b,h) slab at a time keeps the fp32 temporary small
+            flat[i] = (torch.randn(flat.shape[1], generator=g, device=device, dtype=torch.float32) * scale).to(dt)
+        return out
+
+    state = {}
+    for name in ("k_mem", "v_mem"):
+        buf = torch.zeros((cfg.B, cfg.H, cfg.mem_capacity, cfg.d), dtype=dt, device=device)
+        buf[:, :, :Lm] = draw((cfg.B, cfg.H, Lm, cfg.d), cfg.kv_scale)
+        state[name] = buf
+    for name in ("k_read", "v_read"):
+        state[name] = draw((cfg.B, cfg.H, cfg.R, cfg.d), cfg.kv_scale)
+    return state

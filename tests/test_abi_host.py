@@ -1,0 +1,168 @@
+"""Host-side checks of the C ABI: exported symbols, argument validation, tile schedule.
+
+No kernel is launched here: every call below is rejected by the host-side checks (or is
+host-only arithmetic), so the tests run without a GPU.
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "loma.h")
+LIB = os.path.join(ROOT, "paper_2401_09486_amd", "libloma.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libloma.so not built (python -m paper_2401_09486_amd.build)")
+
+OK, EINVAL, EUNSUP, EWS, ELAUNCH = 0, -1, -2, -3, -4
+F32, BF16 = 0, 1
+P = 0x10000  # a non-null, 16-byte aligned fake device address; never dereferenced on the host
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2401_09486_amd import loma
+    return loma.lib
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(loma_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert {"loma_mask_attn_fwd", "loma_compress_step", "loma_decode_attn",
+            "loma_decode_workspace_bytes", "loma_status_string"} <= set(names)
+    raw = ctypes.CDLL(LIB)
+    for n in names:
+        assert hasattr(raw, n), f"{n} declared in loma.h but not exported"
+
+
+def test_status_strings(lib):
+    from paper_2401_09486_amd import loma
+    assert loma.status_string(OK) == "ok"
+    for code in (EINVAL, EUNSUP, EWS, ELAUNCH, -99):
+        assert loma.status_string(code)
+    assert loma.abi_version() >= 1
+
+
+def mask_call(lib, **kw):
+    a = dict(q=P, k=P, v=P, out=P, lse=None, B=1, H=1, d=128, t=16, c=4, n=2, scale=0.1, dtype=BF16)
+    a.update(kw)
+    return lib.loma_mask_attn_fwd(a["q"], a["k"], a["v"], a["out"], a["lse"], a["B"], a["H"], a["d"], a["t"], a["c"],
+                                  a["n"], a["scale"], a["dtype"], None)
+
+
+def test_mask_attn_rejects_bad_arguments(lib):
+    assert mask_call(lib, q=None) == EINVAL
+    assert mask_call(lib, out=None) == EINVAL
+    assert mask_call(lib, k=P + 2) == EINVAL          # misaligned
+    assert mask_call(lib, t=0) == EINVAL
+    assert mask_call(lib, c=-1) == EINVAL
+    assert mask_call(lib, n=0) == EINVAL
+    assert mask_call(lib, B=0) == EINVAL
+    assert mask_call(lib, scale=0.0) == EINVAL
+    assert mask_call(lib, scale=float("nan")) == EINVAL
+    assert mask_call(lib, scale=float("inf")) == EINVAL
+    assert mask_call(lib, dtype=7) == EUNSUP
+    assert mask_call(lib, d=100) == EUNSUP            # not a multiple of 8
+    assert mask_call(lib, d=512) == EUNSUP
+    assert mask_call(lib, n=1 << 28) == EUNSUP        # sequence too long
+
+
+def compress_call(lib, **kw):
+    a = dict(qm=P, km=P, vm=P, kr=P, vr=P, kc=P, vc=P, out=P, B=1, H=1, d=128, t=16, c=4, nmem=2, cap=64,
+             scale=0.1, dtype=BF16)
+    a.update(kw)
+    return lib.loma_compress_step(a["qm"], a["km"], a["vm"], a["kr"], a["vr"], a["kc"], a["vc"], a["out"], a["B"],
+                                  a["H"], a["d"], a["t"], a["c"], a["nmem"], a["cap"], a["scale"], a["dtype"], None)
+
+
+def test_compress_rejects_bad_arguments(lib):
+    assert compress_call(lib, kc=None) == EINVAL
+    assert compress_call(lib, vr=P + 8) == EINVAL
+    assert compress_call(lib, nmem=-1) == EINVAL
+    assert compress_call(lib, nmem=4, cap=64) == EINVAL    # (4+1)*16 > 64: cache full
+    assert compress_call(lib, nmem=3, cap=63) == EINVAL
+    assert compress_call(lib, t=0) == EINVAL
+    assert compress_call(lib, dtype=2) == EUNSUP
+    assert compress_call(lib, d=4) == EUNSUP
+
+
+def decode_call(lib, **kw):
+    a = dict(q=P, kn=P, vn=P, kc=P, vc=P, kr=P, vr=P, out=P, B=8, H=32, d=128, t=16, c=4, nmem=4, cap=64, fill=3,
+             scale=0.1, dtype=BF16, ws=P, wsb=1 << 30)
+    a.update(kw)
+    return lib.loma_decode_attn(a["q"], a["kn"], a["vn"], a["kc"], a["vc"], a["kr"], a["vr"], a["out"], a["B"], a["H"],
+                                a["d"], a["t"], a["c"], a["nmem"], a["cap"], a["fill"], a["scale"], a["dtype"],
+                                a["ws"], a["wsb"], None)
+
+
+def test_decode_rejects_bad_arguments(lib):
+    assert decode_call(lib, q=None) == EINVAL
+    assert decode_call(lib, kn=None) == EINVAL                    # k_new without v_new
+    assert decode_call(lib, fill=64) == EINVAL                    # reading zone full, token cannot be appended
+    assert decode_call(lib, fill=65, kn=None, vn=None) == EINVAL  # longer than t*c
+    assert decode_call(lib, fill=-1) == EINVAL
+    assert decode_call(lib, nmem=5) == EINVAL                     # 80 memory rows > capacity 64
+    assert decode_call(lib, kc=None) == EINVAL                    # memory rows but no cache
+    assert decode_call(lib, nmem=0, fill=0, kn=None, vn=None) == EINVAL   # nothing to attend to
+    assert decode_call(lib, kr=P + 4) == EINVAL
+    assert decode_call(lib, dtype=-1) == EUNSUP
+    # split-K needs its workspace
+    need = lib.loma_decode_workspace_bytes(8, 32, 128, 16, 4, 4, BF16)
+    assert need > 0
+    assert decode_call(lib, ws=None) == EWS
+    assert decode_call(lib, wsb=need - 1) == EWS
+
+
+def test_decode_workspace_bytes(lib):
+    f = lib.loma_decode_workspace_bytes
+    assert f(0, 32, 128, 16, 4, 4, BF16) == 0
+    assert f(8, 32, 100, 16, 4, 4, BF16) == 0
+    assert f(8, 32, 128, 16, 4, -1, BF16) == 0
+    a = f(8, 32, 128, 16, 4, 64, BF16)
+    assert a > 0 and a % 4 == 0
+    # large batches do not split: no workspace
+    assert f(64, 64, 128, 16, 16, 512, BF16) == 0
+
+
+@pytest.mark.parametrize("B,H,d,t,c,n", [(1, 1, 128, 16, 4, 3), (2, 4, 128, 32, 8, 5), (1, 3, 64, 4, 4, 4),
+                                         (1, 2, 128, 5, 7, 3), (1, 8, 128, 48, 3, 2), (1, 1, 128, 200, 1, 2)])
+def test_mask_schedule_covers_every_row_once(B, H, d, t, c, n):
+    from paper_2401_09486_amd import loma
+    import torch
+    items = loma.mask_schedule(B, H, d, t, c, n, torch.bfloat16)
+    R = t * c
+    nbh = B * H
+    seen = {}
+    for blk, (bh, y, zone, o0, rows, keys) in enumerate(items):
+        assert bh == blk % nbh                      # (b,h) fastest: XCD affinity when nbh % 8 == 0
+        assert 0 <= bh < nbh and 0 <= y < n and zone in (0, 1, 2) and rows >= 1
+        zlen = t if zone == 1 else R
+        assert 0 <= o0 and o0 + rows <= zlen
+        if zone == 0:
+            assert keys == y * t + o0 + rows        # earlier memory zones + causal prefix up to the last row
+        elif zone == 1:
+            assert keys == R + t
+        else:
+            assert keys == t
+        for r in range(o0, o0 + rows):
+            key = (bh, y, zone, r)
+            assert key not in seen
+            seen[key] = blk
+    assert len(seen) == nbh * n * (2 * R + t)
+    # longest first: reading blocks run from the last chunk (most earlier memory zones) to the first
+    chunks = [y for (bh, y, z, o0, rows, k) in items if bh == 0 and z == 0]
+    assert chunks == sorted(chunks, reverse=True)
+    first_other = min(i for i, it in enumerate(items) if it[2] != 0)
+    assert all(it[2] == 0 for it in items[:first_other]) and all(it[2] != 0 for it in items[first_other:])
+
+
+def test_schedule_size_zero_for_shapes_on_the_generic_path(lib):
+    assert lib.loma_mask_schedule_size(1, 1, 64, 4, 4, 4, F32) == 0
+    assert lib.loma_mask_schedule_size(1, 1, 96, 4, 4, 4, BF16) == 0
+    assert lib.loma_mask_schedule_size(2, 32, 128, 16, 4, 28, BF16) == 2 * 32 * 28 * 3

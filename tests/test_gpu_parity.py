@@ -1,0 +1,218 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU fp64 oracle, element by element.
+
+Small shapes that still span several tiles, ragged tails and every kernel variant; the
+full-size configurations are in test_gpu_full_configs.py.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import check, host_bits, to_dev, to_host_f64
+from paper_2401_09486_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def loma():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2401_09486_amd import loma as m
+    return m
+
+
+def run_mask(loma, c_oracle, cfg, want_lse=False):
+    print(f"[case] mask pass {cfg}", flush=True)
+    q, k, v = wl.mask_inputs(cfg)
+    dq, dk, dv = to_dev(q), to_dev(k), to_dev(v)
+    lse = torch.empty((cfg.B, cfg.H, cfg.S), dtype=torch.float32, device="cuda") if want_lse else None
+    out = loma.loma_mask_attn_fwd(dq, dk, dv, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, lse=lse)
+    torch.cuda.synchronize()
+    ref, ref_lse = c_oracle.mask_attn(q, k, v, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, return_lse=True)
+    mx, mean = check(to_host_f64(out), ref, cfg.dtype, cfg.name)
+    if want_lse:
+        tol = 1e-5 if cfg.dtype == "f32" else 2e-3
+        assert np.abs(lse.cpu().numpy().astype(np.float64) - ref_lse).max() <= tol
+    return out, ref, mx, mean
+
+
+def small(name, B, H, d, t, c, n, dtype="bf16", scale=0.5, index=1):
+    return wl.MaskConfig(index, name, B, H, d, t, c, n, dtype, scale)
+
+
+def test_config1_tiny_fp32(loma, c_oracle):
+    run_mask(loma, c_oracle, wl.CONFIGS[0], want_lse=True)
+
+
+@pytest.mark.parametrize("cfg", [
+    small("bf16_t16c4_bm64", 1, 2, 128, 16, 4, 3),          # 2-wave kernel, BN 32
+    small("bf16_t32c8_bm128", 1, 2, 128, 32, 8, 3),         # 4-wave kernel, BN 64, two row blocks per zone
+    small("bf16_t4c4_bm32", 2, 1, 128, 4, 4, 4),            # 1-wave kernel, R = 16 < 32 rows
+    small("bf16_t5c7_ragged", 1, 3, 128, 5, 7, 3),          # R = 35, t = 5: nothing aligned
+    small("bf16_t24c6_ragged128", 1, 1, 128, 24, 6, 3),     # R = 144: 128 + 16 ragged row block
+    small("bf16_t40c1", 1, 2, 128, 40, 1, 2),               # memory zone needs 2 waves
+    small("bf16_t1c1", 1, 1, 128, 1, 1, 5),                 # degenerate: every zone one token
+    small("bf16_d64_t16c4", 1, 2, 64, 16, 4, 3),
+    small("bf16_d64_t32c8", 1, 1, 64, 32, 8, 2),
+    small("bf16_nbh8_xcd", 1, 8, 128, 16, 2, 6),            # B*H multiple of 8
+], ids=lambda c: c.name)
+def test_mask_pass_mfma_small(loma, c_oracle, cfg):
+    run_mask(loma, c_oracle, cfg, want_lse=True)
+
+
+@pytest.mark.parametrize("cfg", [
+    small("f32_d128_t16c2", 1, 2, 128, 16, 2, 3, dtype="f32", scale=1.0),
+    small("f32_d40_t3c3", 2, 1, 40, 3, 3, 4, dtype="f32", scale=1.0),
+    small("bf16_d96_generic", 1, 2, 96, 8, 2, 3),
+    small("bf16_d256_generic", 1, 1, 256, 4, 3, 2),
+], ids=lambda c: c.name)
+def test_mask_pass_generic_small(loma, c_oracle, cfg):
+    run_mask(loma, c_oracle, cfg, want_lse=True)
+
+
+def test_mask_pass_is_deterministic(loma):
+    cfg = small("det", 1, 4, 128, 32, 4, 4)
+    q, k, v = (to_dev(x) for x in wl.mask_inputs(cfg))
+    a = loma.loma_mask_attn_fwd(q, k, v, cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
+    b = loma.loma_mask_attn_fwd(q, k, v, cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+@pytest.mark.parametrize("cfg", [small("poison_mfma", 1, 1, 128, 16, 4, 3), small("poison_f32", 1, 1, 64, 4, 4, 3, dtype="f32")],
+                         ids=lambda c: c.name)
+def test_masked_keys_never_reach_a_row(loma, cfg):
+    """Eq. 8-9: overwrite everything a repetition / memory / reading row may not see with NaN
+    (K) and Inf (V): its output must stay bit-identical."""
+    from oracle import loma_oracle as lo
+    q, k, v = wl.mask_inputs(cfg)
+    dq, dk, dv = to_dev(q), to_dev(k), to_dev(v)
+    base = loma.loma_mask_attn_fwd(dq, dk, dv, cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
+    torch.cuda.synchronize()
+    mask = lo.mask_from_blocks(cfg.t, cfg.c, cfg.n_chunks)
+    R, s = cfg.R, cfg.s
+    y = cfg.n_chunks - 1
+    for p in [y * s + R + cfg.t + 3, y * s + R + 1, y * s + 5, 2, s + R + cfg.t]:
+        hidden = torch.from_numpy(np.nonzero(mask[p] == 0)[0]).cuda()
+        k2, v2 = dk.clone(), dv.clone()
+        k2[:, :, hidden] = float("nan")
+        v2[:, :, hidden] = float("inf")
+        out = loma.loma_mask_attn_fwd(dq, k2, v2, cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
+        torch.cuda.synchronize()
+        a = out[:, :, p].contiguous().view(torch.int16 if cfg.dtype == "bf16" else torch.int32)
+        b = base[:, :, p].contiguous().view(torch.int16 if cfg.dtype == "bf16" else torch.int32)
+        assert torch.equal(a, b), f"row {p} changed when masked K/V were poisoned"
+
+
+# ---- generation form ---------------------------------------------------------------------------
+def run_generation(loma, c_oracle, cfg, check_every=1):
+    """Drive compress/decode exactly as the appendix's loop does, on the GPU and in the oracle."""
+    print(f"[case] generation {cfg}", flush=True)
+    st = wl.gen_initial_state(cfg)
+    dev = {k: to_dev(v) for k, v in st.items()}
+    orc = c_oracle.GenerationCache(st["k_mem"].copy(), st["v_mem"].copy(), cfg.prior_chunks,
+                                   st["k_read"].copy(), st["v_read"].copy(), cfg.R, cfg.t, cfg.c, cfg.scale)
+    nws = loma.loma_decode_workspace_bytes(cfg.B, cfg.H, cfg.d, cfg.t, cfg.c, cfg.prior_chunks + cfg.n_compress,
+                                           torch.bfloat16 if cfg.dtype == "bf16" else torch.float32)
+    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")
+    n_mem, fill, events = cfg.prior_chunks, cfg.R, 0
+    worst = 0.0
+    for step in range(cfg.steps):
+        if fill == cfg.R:
+            qm, km, vm = wl.gen_compress_inputs(cfg, events)
+            out = loma.loma_compress_step(to_dev(qm), to_dev(km), to_dev(vm), dev["k_read"], dev["v_read"],
+                                          dev["k_mem"], dev["v_mem"], cfg.t, cfg.c, n_mem, cfg.scale)
+            ref = orc.compress(qm, km, vm).reshape(cfg.B, cfg.H, cfg.t, cfg.d)
+            mx, _ = check(to_host_f64(out), ref, cfg.dtype, f"compress event {events}")
+            worst = max(worst, mx)
+            n_mem, fill, events = n_mem + 1, 0, events + 1
+            # the splice: the cache rows just written are the <m> tokens' K/V, bit for bit
+            lo_, hi_ = (n_mem - 1) * cfg.t, n_mem * cfg.t
+            assert np.array_equal(host_bits(dev["k_mem"][:, :, lo_:hi_]), km)
+            assert np.array_equal(host_bits(dev["v_mem"][:, :, lo_:hi_]), vm)
+        q, kn, vn = wl.gen_step_inputs(cfg, step)
+        out = loma.loma_decode_attn(to_dev(q), to_dev(kn), to_dev(vn), dev["k_mem"], dev["v_mem"],
+                                    dev["k_read"], dev["v_read"], cfg.t, cfg.c, n_mem, fill, cfg.scale, workspace=ws)
+        ref = orc.decode(q, kn, vn).reshape(cfg.B, cfg.H, 1, cfg.d)
+        fill += 1
+        if step % check_every == 0 or step == cfg.steps - 1:
+            mx, _ = check(to_host_f64(out), ref, cfg.dtype, f"decode step {step}")
+            worst = max(worst, mx)
+    # the appended tokens sit in the reading zone, bit for bit
+    assert np.array_equal(host_bits(dev["k_read"][:, :, :fill]), orc.k_read[:, :, :fill])
+    assert np.array_equal(host_bits(dev["v_read"][:, :, :fill]), orc.v_read[:, :, :fill])
+    assert np.array_equal(host_bits(dev["k_mem"][:, :, :n_mem * cfg.t]), orc.k_mem[:, :, :n_mem * cfg.t])
+    return worst
+
+
+def gen_small(name, B, H, d, t, c, prior, steps, dtype="bf16", index=2):
+    return wl.GenConfig(index, name, B, H, d, t, c, prior, steps, dtype, 1.0, 1.0)
+
+
+@pytest.mark.parametrize("cfg", [
+    gen_small("gen_bf16_t16c4", 2, 4, 128, 16, 4, 8, 150),          # split-K, 3 compressions
+    gen_small("gen_bf16_noprior", 1, 2, 128, 16, 2, 0, 70),         # empty memory cache at the start
+    gen_small("gen_bf16_d64", 1, 3, 64, 8, 4, 5, 70),
+    gen_small("gen_bf16_t4c3", 1, 2, 128, 4, 3, 40, 30),            # odd reading-zone length 12
+    gen_small("gen_bf16_t40", 1, 2, 128, 40, 2, 3, 90),             # compression with 2 waves
+    gen_small("gen_bf16_t100", 1, 1, 128, 100, 1, 2, 110),          # compression with 4 waves
+    gen_small("gen_bf16_longcache", 1, 2, 128, 16, 4, 300, 10),     # 4800 memory rows: several iterations per split
+    gen_small("gen_f32_generic", 1, 2, 64, 4, 4, 6, 40, dtype="f32"),
+    gen_small("gen_bf16_d96_generic", 1, 2, 96, 4, 4, 6, 20),
+], ids=lambda c: c.name)
+def test_generation_small(loma, c_oracle, cfg):
+    run_generation(loma, c_oracle, cfg)
+
+
+def test_decode_without_new_token(loma, c_oracle):
+    cfg = gen_small("nonew", 2, 2, 128, 16, 4, 4, 1)
+    st = wl.gen_initial_state(cfg)
+    dev = {k: to_dev(v) for k, v in st.items()}
+    q, _, _ = wl.gen_step_inputs(cfg, 0)
+    nws = loma.loma_decode_workspace_bytes(cfg.B, cfg.H, cfg.d, cfg.t, cfg.c, cfg.prior_chunks)
+    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")
+    for fill in (0, 1, 37, cfg.R):
+        before = dev["k_read"].clone()
+        out = loma.loma_decode_attn(to_dev(q), None, None, dev["k_mem"], dev["v_mem"], dev["k_read"], dev["v_read"],
+                                    cfg.t, cfg.c, cfg.prior_chunks, fill, cfg.scale, workspace=ws)
+        ref = c_oracle.attend_segments(q, st["k_mem"], st["v_mem"], cfg.prior_chunks * cfg.t,
+                                       st["k_read"], st["v_read"], fill, cfg.scale).reshape(cfg.B, cfg.H, 1, cfg.d)
+        check(to_host_f64(out), ref, cfg.dtype, f"fill {fill}")
+        assert torch.equal(before.view(torch.int16), dev["k_read"].view(torch.int16))   # cache untouched
+
+
+def test_generation_matches_mask_pass_rows_on_gpu(loma):
+    """Sec. 3.1 vs Sec. 4.3 on the device: decode outputs equal reading rows and compress outputs
+    equal memory rows of the full-mask pass over the same Q/K/V (both bf16; equal up to rounding)."""
+    cfg = small("equiv", 1, 2, 128, 16, 4, 3)
+    q, k, v = (to_dev(x) for x in wl.mask_inputs(cfg))
+    full = loma.loma_mask_attn_fwd(q, k, v, cfg.t, cfg.c, cfg.n_chunks, cfg.scale).float()
+    B, H, d, t, c, R, s = cfg.B, cfg.H, cfg.d, cfg.t, cfg.c, cfg.R, cfg.s
+    k_mem = torch.zeros((B, H, cfg.n_chunks * t, d), dtype=torch.bfloat16, device="cuda")
+    v_mem = torch.zeros_like(k_mem)
+    k_read = torch.zeros((B, H, R, d), dtype=torch.bfloat16, device="cuda")
+    v_read = torch.zeros_like(k_read)
+    ws = torch.empty(max(loma.loma_decode_workspace_bytes(B, H, d, t, c, cfg.n_chunks), 16), dtype=torch.uint8, device="cuda")
+    worst = 0.0
+    for y in range(cfg.n_chunks):
+        for o in range(R):
+            p = y * s + o
+            out = loma.loma_decode_attn(q[:, :, p:p + 1].contiguous(), k[:, :, p:p + 1].contiguous(),
+                                        v[:, :, p:p + 1].contiguous(), k_mem, v_mem, k_read, v_read, t, c, y, o,
+                                        cfg.scale, workspace=ws)
+            worst = max(worst, (out.float()[:, :, 0] - full[:, :, p]).abs().max().item())
+        m0 = y * s + R
+        out = loma.loma_compress_step(q[:, :, m0:m0 + t].contiguous(), k[:, :, m0:m0 + t].contiguous(),
+                                      v[:, :, m0:m0 + t].contiguous(), k_read, v_read, k_mem, v_mem, t, c, y, cfg.scale)
+        worst = max(worst, (out.float() - full[:, :, m0:m0 + t]).abs().max().item())
+    assert worst <= 2e-2, worst
+
+
+def test_binding_reports_errors(loma):
+    q = torch.zeros((1, 1, 144, 64), device="cuda")
+    with pytest.raises(ValueError):
+        loma.loma_mask_attn_fwd(q, q, q, 4, 4, 5, 0.125)        # S != n*s
+    with pytest.raises(loma.LomaError) as e:
+        loma.loma_mask_attn_fwd(q, q, q, 4, 4, 4, -1.0)
+    assert e.value.status == loma.ERR_INVALID_ARG
