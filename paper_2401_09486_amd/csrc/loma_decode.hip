@@ -39,6 +39,9 @@ struct DecodeParams {
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// bit pattern of two packed bf16 -> vector operand (taken by value: element references of
+// ext-vectors must not be handed to __builtin_bit_cast directly)
+__device__ __forceinline__ bf16x2 as_bf16x2(uint32_t w) { return __builtin_bit_cast(bf16x2, w); }
 __device__ __forceinline__ uint16_t f32_to_bf16(float x) {
     uint32_t u = __float_as_uint(x);
     u += 0x7fffu + ((u >> 16) & 1u);
@@ -85,8 +88,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodePara
     const bf16_t* vnew = P.v_new + bh * D;
 
     const uint4 qv = *reinterpret_cast<const uint4*>(P.q + bh * D + col * 8);
-    const bf16x2 q0 = __builtin_bit_cast(bf16x2, qv.x), q1 = __builtin_bit_cast(bf16x2, qv.y);
-    const bf16x2 q2 = __builtin_bit_cast(bf16x2, qv.z), q3 = __builtin_bit_cast(bf16x2, qv.w);
+    const bf16x2 q0 = as_bf16x2(qv.x), q1 = as_bf16x2(qv.y), q2 = as_bf16x2(qv.z), q3 = as_bf16x2(qv.w);
 
     float m = -INFINITY, l = 0.f;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -111,10 +113,11 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodePara
         float mx = m;
 #pragma unroll
         for (int u = 0; u < DEC_UNROLL; ++u) {
-            float a = __builtin_amdgcn_fdot2_f32_bf16(q0, __builtin_bit_cast(bf16x2, kk[u].x), 0.f, false);
-            a = __builtin_amdgcn_fdot2_f32_bf16(q1, __builtin_bit_cast(bf16x2, kk[u].y), a, false);
-            a = __builtin_amdgcn_fdot2_f32_bf16(q2, __builtin_bit_cast(bf16x2, kk[u].z), a, false);
-            a = __builtin_amdgcn_fdot2_f32_bf16(q3, __builtin_bit_cast(bf16x2, kk[u].w), a, false);
+            const uint32_t k0 = kk[u][0], k1 = kk[u][1], k2 = kk[u][2], k3 = kk[u][3];
+            float a = __builtin_amdgcn_fdot2_f32_bf16(q0, as_bf16x2(k0), 0.f, false);
+            a = __builtin_amdgcn_fdot2_f32_bf16(q1, as_bf16x2(k1), a, false);
+            a = __builtin_amdgcn_fdot2_f32_bf16(q2, as_bf16x2(k2), a, false);
+            a = __builtin_amdgcn_fdot2_f32_bf16(q3, as_bf16x2(k3), a, false);
             a = row_sum<LPR>(a) * P.sc;
             s[u] = (base + u * RPL + sub < kend) ? a : -INFINITY;
             mx = fmaxf(mx, s[u]);
