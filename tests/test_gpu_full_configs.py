@@ -1,0 +1,100 @@
+"""GPU parity at the full sizes of the five named configurations, in the launch configuration
+bench.py times.  The oracle computes sampled outputs (rows / (b,h) pairs) one by one."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import check, host_bits, to_dev, to_host_f64
+from paper_2401_09486_amd import workloads as wl
+from test_gpu_parity import run_generation
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def loma():
+    assert torch.cuda.is_available()
+    from paper_2401_09486_amd import loma as m
+    return m
+
+
+def sampled_rows(cfg, stride):
+    """Every stride-th row, plus whole zones of the first and last chunk and all zone borders."""
+    R, t, s, n = cfg.R, cfg.t, cfg.s, cfg.n_chunks
+    rows = set(range(0, cfg.S, stride))
+    for y in (0, n // 2, n - 1):
+        base = y * s
+        rows.update(range(base, base + min(R, 40)))                   # start of the reading zone
+        rows.update(range(base + R - 3, base + R + t + 3))           # read/memory/repetition borders
+        rows.update(range(base + s - 3, base + s))                   # end of the chunk
+        rows.update(range(base + R + t + R // 2, base + R + t + R // 2 + 4))
+    return np.array(sorted(r for r in rows if 0 <= r < cfg.S), dtype=np.int32)
+
+
+@pytest.mark.parametrize("idx,stride", [(1, 31), (3, 257)], ids=["config2_llama7b_mask", "config4_long_mask"])
+def test_mask_pass_full_size(loma, c_oracle, idx, stride):
+    cfg = wl.CONFIGS[idx]
+    print(f"[case] full-size mask pass {cfg}", flush=True)
+    q, k, v = wl.mask_inputs(cfg)
+    out = loma.loma_mask_attn_fwd(to_dev(q), to_dev(k), to_dev(v), cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
+    torch.cuda.synchronize()
+    rows = sampled_rows(cfg, stride)
+    ref = c_oracle.mask_attn(q, k, v, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, rows=rows)
+    got = to_host_f64(out[:, :, torch.from_numpy(rows.astype(np.int64)).cuda()])
+    mx, mean = check(got, ref, cfg.dtype, cfg.name)
+    print(f"[result] {cfg.name}: {rows.size} rows x {cfg.B * cfg.H} (b,h): max abs {mx:.3e} mean abs {mean:.3e}", flush=True)
+    # every output element finite, also outside the sample
+    assert torch.isfinite(out.float()).all()
+
+
+def test_generation_config3_full(loma, c_oracle):
+    worst = run_generation(loma, c_oracle, wl.CONFIGS[2])
+    print(f"[result] config 3: all 256 steps, all (b,h): worst max abs {worst:.3e}", flush=True)
+
+
+def test_generation_config5_full(loma, c_oracle):
+    """B64 H32, 8192 memory KVs + 256-token reading zone, 128 steps; the caches are drawn on the
+    device (9 GB); the oracle follows 24 sampled (b,h) pairs through every step."""
+    cfg = wl.CONFIGS[4]
+    print(f"[case] full-size generation {cfg}", flush=True)
+    st = wl.gen_initial_state_device(cfg)
+    nbh = cfg.B * cfg.H
+    sel = np.array(sorted(set(np.linspace(0, nbh - 1, 24).astype(int))), dtype=np.int64)
+    tsel = torch.from_numpy(sel).cuda()
+
+    def pick(x):   # [B, H, L, d] device -> [1, nsel, L, d] host bits
+        flat = x.view(nbh, x.shape[2], x.shape[3])
+        return host_bits(flat[tsel].contiguous())[None]
+
+    orc = c_oracle.GenerationCache(pick(st["k_mem"]), pick(st["v_mem"]), cfg.prior_chunks,
+                                   pick(st["k_read"]), pick(st["v_read"]), cfg.R, cfg.t, cfg.c, cfg.scale)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(cfg.seed + 1000)
+
+    def draw(L, scale):
+        return (torch.randn((cfg.B, cfg.H, L, cfg.d), generator=gen, device="cuda") * scale).to(torch.bfloat16)
+
+    ws = torch.empty(max(loma.loma_decode_workspace_bytes(cfg.B, cfg.H, cfg.d, cfg.t, cfg.c, cfg.prior_chunks + 1), 16),
+                     dtype=torch.uint8, device="cuda")
+    n_mem, fill = cfg.prior_chunks, cfg.R
+    worst = 0.0
+    for step in range(cfg.steps):
+        if fill == cfg.R:
+            qm, km, vm = draw(cfg.t, cfg.q_scale), draw(cfg.t, cfg.kv_scale), draw(cfg.t, cfg.kv_scale)
+            out = loma.loma_compress_step(qm, km, vm, st["k_read"], st["v_read"], st["k_mem"], st["v_mem"],
+                                          cfg.t, cfg.c, n_mem, cfg.scale)
+            ref = orc.compress(pick(qm), pick(km), pick(vm))
+            mx, _ = check(to_host_f64(out.view(nbh, cfg.t, cfg.d)[tsel]), ref, cfg.dtype, "compress")
+            worst = max(worst, mx)
+            n_mem, fill = n_mem + 1, 0
+        q, kn, vn = draw(1, cfg.q_scale), draw(1, cfg.kv_scale), draw(1, cfg.kv_scale)
+        out = loma.loma_decode_attn(q, kn, vn, st["k_mem"], st["v_mem"], st["k_read"], st["v_read"],
+                                    cfg.t, cfg.c, n_mem, fill, cfg.scale, workspace=ws)
+        ref = orc.decode(pick(q), pick(kn), pick(vn))
+        fill += 1
+        mx, _ = check(to_host_f64(out.view(nbh, 1, cfg.d)[tsel]), ref, cfg.dtype, f"decode step {step}")
+        worst = max(worst, mx)
+        if step % 32 == 0:
+            print(f"[progress] config 5 step {step} worst {worst:.3e}", flush=True)
+            assert torch.isfinite(out.float()).all()
+    print(f"[result] config 5: {cfg.steps} steps, {sel.size} sampled (b,h): worst max abs {worst:.3e}", flush=True)
