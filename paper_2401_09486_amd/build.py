@@ -19,6 +19,8 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA accumulators stay in ordinary VGPRs (no AGPR copies around the softmax arithmetic)
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
 ]
 
 

@@ -13,10 +13,12 @@
 // Per 32x32 tile the scores are produced TRANSPOSED, S^T = K Q^T (keys down the rows,
 // queries across the lanes), so a query's softmax statistics live in two lanes (l, l^32)
 // and the probabilities come out of the accumulators already in the register layout the
-// second product O^T += V^T P^T wants as its B operand.  K tiles sit in LDS row-major; V tiles
-// are written to LDS transposed (head-dim major, keys permuted to match that layout) so both
-// MFMA A operands are single 16-byte LDS reads.  Tiles are double-buffered: global loads for
-// tile i+1 are in flight while tile i is multiplied; one barrier per tile.
+// second product O^T += V^T P^T wants as its B operand.  K and V tiles both sit in LDS
+// row-major, exactly as they lie in HBM (16-byte stores, no shuffling): the K operand is a plain
+// 16-byte LDS read, the V^T operand comes from the transposing LDS read of gfx950
+// (ds_read_b64_tr_b16: inside 16 lanes, lane i receives the i-th 16-bit column of four rows).
+// Tiles are double-buffered: global loads for tile i+1 are in flight while tile i is
+// multiplied; one barrier per tile.
 #include "loma_internal.h"
 
 namespace loma {
@@ -26,6 +28,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 typedef uint16_t bf16_t;  // storage type of bf16 tensors
 
 constexpr int NO_CAUSAL = 1 << 29;
@@ -41,6 +44,7 @@ struct FlashJob {
     const bf16_t *k0, *k1, *k2, *v0, *v1, *v2;
     int n0, n1, n2;
     int slab;          // rows per slab in range 0
+    unsigned slab_magic;  // floor(2^32 / slab) + 1: j / slab == umulhi(j, magic) while j * slab < 2^32
     long slab_stride;  // elements between slabs
     int causal_base;   // key j is visible to block row r iff j <= causal_base + r
     const bf16_t *k_self, *v_self;  // rows aligned with q (repetition zone) or nullptr
@@ -51,10 +55,13 @@ struct Cfg {
     static constexpr int NT = 64 * NW;
     static constexpr int BM = 32 * NW;
     static constexpr int CPR = D / 8;        // 16-byte pieces per row
-    static constexpr int KSTR = D + 8;       // K tile row stride (elements): 16B-aligned, bank-spread
-    static constexpr int VSTR = BN + 8;      // transposed V tile row stride
+    // row strides in elements.  K rows are read 16 B per lane by 16 lanes on 16 consecutive rows:
+    // D/2+4 dwords (== 4 mod 8) spreads them over all banks.  V rows are read by the transposing
+    // load, 4 rows x 32 B per 16 lanes, two column halves at once: D/2+16 dwords keeps them apart.
+    static constexpr int KSTR = D + 8;
+    static constexpr int VSTR = D + 32;
     static constexpr int KBUF = BN * KSTR;
-    static constexpr int VBUF = D * VSTR;
+    static constexpr int VBUF = BN * VSTR;
     static constexpr int SMEM_BYTES = 2 * (KBUF + VBUF) * 2;
     static constexpr int NTASK = (BN / 4) * CPR;          // (4 keys) x (8 head-dim) load tasks
     static constexpr int TPT = (NTASK + NT - 1) / NT;     // tasks per thread
@@ -85,78 +92,67 @@ __device__ __forceinline__ float pair_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// Global row of key j of the job's key list.  Branch-free (selects only) so that the loads
+// that follow stay in one basic block and can be left in flight across the tile's math.
 template <int D>
 __device__ __forceinline__ void key_row(const FlashJob& J, int j, const bf16_t*& kp, const bf16_t*& vp) {
-    if (j < J.n0) {
-        const int a = j / J.slab;
-        const long off = (long)a * J.slab_stride + (long)(j - a * J.slab) * D;
-        kp = J.k0 + off; vp = J.v0 + off;
-    } else if (j < J.n0 + J.n1) {
-        const long off = (long)(j - J.n0) * D;
-        kp = J.k1 + off; vp = J.v1 + off;
-    } else {
-        const long off = (long)(j - J.n0 - J.n1) * D;
-        kp = J.k2 + off; vp = J.v2 + off;
-    }
+    const unsigned a = J.slab == 1 ? (unsigned)j : __umulhi((unsigned)j, J.slab_magic);
+    const long off0 = (long)a * J.slab_stride + (long)(j - (int)a * J.slab) * D;
+    const int j1 = j - J.n0, j2 = j1 - J.n1;
+    const bool in0 = j < J.n0, in1 = j1 < J.n1;
+    const long off = in0 ? off0 : (long)(in1 ? j1 : j2) * D;
+    kp = (in0 ? J.k0 : (in1 ? J.k1 : J.k2)) + off;
+    vp = (in0 ? J.v0 : (in1 ? J.v1 : J.v2)) + off;
 }
 
+// A thread fetches one 16-byte piece of four consecutive keys, for K and for V.  Keys past the
+// end of the list are clamped to the last key: their scores are masked and their
+// probabilities are exactly 0, so any finite row will do and no lane ever branches.
 template <int D, int NW, int BN>
 __device__ __forceinline__ void load_tile(const FlashJob& J, int k0, int nkeys, int tid,
-                                          uint4 (&kreg)[Cfg<D, NW, BN>::TPT][4],
-                                          uint4 (&vreg)[Cfg<D, NW, BN>::TPT][4]) {
+                                          u32x4 (&kreg)[Cfg<D, NW, BN>::TPT][4],
+                                          u32x4 (&vreg)[Cfg<D, NW, BN>::TPT][4]) {
     using C = Cfg<D, NW, BN>;
 #pragma unroll
     for (int i = 0; i < C::TPT; ++i) {
-        const int task = tid + i * C::NT;
+        const int task = (tid + i * C::NT) % C::NTASK;   // surplus threads repeat a task
         const int dch = task % C::CPR, kg = task / C::CPR;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            const int j = k0 + 4 * kg + b;
-            kreg[i][b] = make_uint4(0, 0, 0, 0);
-            vreg[i][b] = make_uint4(0, 0, 0, 0);
-            if (task < C::NTASK && j < nkeys) {
-                const bf16_t *kp, *vp;
-                key_row<D>(J, j, kp, vp);
-                kreg[i][b] = *reinterpret_cast<const uint4*>(kp + dch * 8);
-                vreg[i][b] = *reinterpret_cast<const uint4*>(vp + dch * 8);
-            }
+            const int j = min(k0 + 4 * kg + b, nkeys - 1);
+            const bf16_t *kp, *vp;
+            key_row<D>(J, j, kp, vp);
+            kreg[i][b] = *reinterpret_cast<const u32x4*>(kp + dch * 8);
+            vreg[i][b] = *reinterpret_cast<const u32x4*>(vp + dch * 8);
         }
     }
 }
 
-// K: row-major.  V: transposed, and inside every group of 16 keys the key 8a+4g+b sits at
-// slot 8g+4a+b -- the order in which the probabilities sit in the score accumulators.
+// Both tiles row-major; 16 consecutive lanes write one whole row.
 template <int D, int NW, int BN>
 __device__ __forceinline__ void store_tile(bf16_t* Kb, bf16_t* Vb, int tid,
-                                           const uint4 (&kreg)[Cfg<D, NW, BN>::TPT][4],
-                                           const uint4 (&vreg)[Cfg<D, NW, BN>::TPT][4]) {
+                                           const u32x4 (&kreg)[Cfg<D, NW, BN>::TPT][4],
+                                           const u32x4 (&vreg)[Cfg<D, NW, BN>::TPT][4]) {
     using C = Cfg<D, NW, BN>;
 #pragma unroll
     for (int i = 0; i < C::TPT; ++i) {
-        const int task = tid + i * C::NT;
-        if (task >= C::NTASK) continue;
+        const int task = (tid + i * C::NT) % C::NTASK;
         const int dch = task % C::CPR, kg = task / C::CPR;
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
-            *reinterpret_cast<uint4*>(Kb + (4 * kg + b) * C::KSTR + dch * 8) = kreg[i][b];
-        // kg = 4*j16 + 2*a + g  ->  first slot 16*j16 + 8*g + 4*a
-        const int slot = 16 * (kg >> 2) + 8 * (kg & 1) + 4 * ((kg >> 1) & 1);
-        const uint32_t r0[4] = {vreg[i][0].x, vreg[i][0].y, vreg[i][0].z, vreg[i][0].w};
-        const uint32_t r1[4] = {vreg[i][1].x, vreg[i][1].y, vreg[i][1].z, vreg[i][1].w};
-        const uint32_t r2[4] = {vreg[i][2].x, vreg[i][2].y, vreg[i][2].z, vreg[i][2].w};
-        const uint32_t r3[4] = {vreg[i][3].x, vreg[i][3].y, vreg[i][3].z, vreg[i][3].w};
-#pragma unroll
-        for (int wd = 0; wd < 4; ++wd) {
-            // element 2*wd (low halves) and 2*wd+1 (high halves) of the four keys
-            uint2 lo, hi;
-            lo.x = __builtin_amdgcn_perm(r1[wd], r0[wd], 0x05040100u);
-            lo.y = __builtin_amdgcn_perm(r3[wd], r2[wd], 0x05040100u);
-            hi.x = __builtin_amdgcn_perm(r1[wd], r0[wd], 0x07060302u);
-            hi.y = __builtin_amdgcn_perm(r3[wd], r2[wd], 0x07060302u);
-            *reinterpret_cast<uint2*>(Vb + (dch * 8 + 2 * wd) * C::VSTR + slot) = lo;
-            *reinterpret_cast<uint2*>(Vb + (dch * 8 + 2 * wd + 1) * C::VSTR + slot) = hi;
+        for (int b = 0; b < 4; ++b) {
+            *reinterpret_cast<u32x4*>(Kb + (4 * kg + b) * C::KSTR + dch * 8) = kreg[i][b];
+            *reinterpret_cast<u32x4*>(Vb + (4 * kg + b) * C::VSTR + dch * 8) = vreg[i][b];
         }
     }
+}
+
+// Transposing LDS read: the 16 lanes of a group each point at 8 bytes; lane i of the group
+// receives element (i % 4) of the lanes 4e + i/4, e = 0..3.  With lane i pointing at row i/4,
+// columns 4*(i%4).., lane i ends up with column i of four consecutive rows.
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+__device__ __forceinline__ s16x4 lds_read_tr(const bf16_t* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(const_cast<bf16_t*>(p)));
 }
 
 template <int D, int NW, int BN>
@@ -198,7 +194,7 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
         for (int i = 0; i < 16; ++i) O[dt][i] = 0.f;
     float m = -INFINITY, lsum = 0.f;
 
-    uint4 kreg[C::TPT][4], vreg[C::TPT][4];
+    u32x4 kreg[C::TPT][4], vreg[C::TPT][4];
     if (ntiles > 0) {
         load_tile<D, NW, BN>(J, 0, nkeys, tid, kreg, vreg);
         store_tile<D, NW, BN>(Ks, Vt, tid, kreg, vreg);
@@ -248,8 +244,17 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
                     for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[sub][i]);
                 }
             mx = pair_max(mx);
-            const float alpha = __builtin_amdgcn_exp2f((m - mx) * sc);
-            const float mc = mx * sc;
+            // the running maximum moved for some query of this wave: rescale (rare after the first tiles)
+            if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {
+                const float alpha = __builtin_amdgcn_exp2f((m - mx) * sc);
+                lsum *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) O[dt][i] *= alpha;
+                m = mx;
+            }
+            const float mc = m * sc;
             float ps = 0.f;
 #pragma unroll
             for (int sub = 0; sub < C::NSUB; ++sub)
@@ -261,12 +266,9 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
                         S[sub][i] = p;
                     }
                 }
-            lsum = lsum * alpha + ps;
-            m = mx;
-#pragma unroll
-            for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) O[dt][i] *= alpha;
+            lsum += ps;
+            // V^T operand: lane (d = 32*dt + l32, half g) needs keys 16*step + 8*a + 4*g + 0..3, a = 0,1
+            const bf16_t* vbase = Vb + (4 * g + ((lane & 15) >> 2)) * C::VSTR + (l32 & 16) + 4 * (lane & 3);
 #pragma unroll
             for (int sub = 0; sub < C::NSUB; ++sub)
                 if (sub < nsub) {
@@ -278,10 +280,13 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
                         pw.z = pack_bf16(S[sub][8 * jj + 4], S[sub][8 * jj + 5]);
                         pw.w = pack_bf16(S[sub][8 * jj + 6], S[sub][8 * jj + 7]);
                         const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
-                        const bf16_t* vp = Vb + l32 * C::VSTR + 16 * (2 * sub + jj) + 8 * g;
+                        const bf16_t* vp = vbase + 16 * (2 * sub + jj) * C::VSTR;
 #pragma unroll
                         for (int dt = 0; dt < C::DT; ++dt) {
-                            const bf16x8 a = *reinterpret_cast<const bf16x8*>(vp + 32 * dt * C::VSTR);
+                            const s16x4 lo = lds_read_tr(vp + 32 * dt);
+                            const s16x4 hi = lds_read_tr(vp + 32 * dt + 8 * C::VSTR);
+                            const bf16x8 a = __builtin_bit_cast(
+                                bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
                             O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, O[dt], 0, 0, 0);
                         }
                     }
@@ -366,7 +371,8 @@ struct MaskParams {
     bf16_t* out;
     float* lse;
     MaskSchedule sched;
-    float sc;  // scale * log2(e)
+    unsigned slab_magic;  // floor(2^32 / t) + 1
+    float sc;             // scale * log2(e)
 };
 
 template <int D, int NW, int BN>
@@ -380,7 +386,7 @@ __global__ __launch_bounds__(64 * NW) void mask_attn_kernel(MaskParams P) {
     J.k0 = J.k1 = J.k2 = P.k;
     J.v0 = J.v1 = J.v2 = P.v;
     J.n0 = J.n1 = J.n2 = 0;
-    J.slab = 1; J.slab_stride = 0;
+    J.slab = 1; J.slab_magic = 0; J.slab_stride = 0;
     J.causal_base = NO_CAUSAL;
     J.k_self = J.v_self = nullptr;
     J.q_rows = mj.rows;
@@ -388,7 +394,7 @@ __global__ __launch_bounds__(64 * NW) void mask_attn_kernel(MaskParams P) {
     if (mj.zone == ZONE_READ) {
         qrow = chunk + mj.o0;
         J.k0 = P.k + (seq + sch.R) * D; J.v0 = P.v + (seq + sch.R) * D;   // memory zone of chunk 0
-        J.n0 = mj.y * sch.t; J.slab = sch.t; J.slab_stride = (long)sch.s * D;
+        J.n0 = mj.y * sch.t; J.slab = sch.t; J.slab_magic = P.slab_magic; J.slab_stride = (long)sch.s * D;
         J.k1 = P.k + chunk * D; J.v1 = P.v + chunk * D;
         J.n1 = mj.o0 + mj.rows;
         J.causal_base = mj.y * sch.t + mj.o0;
@@ -425,7 +431,7 @@ __global__ __launch_bounds__(64 * NW) void compress_kernel(CompressParams P) {
     const int bh = blockIdx.x / P.nblk, blk = blockIdx.x % P.nblk;
     const int o0 = blk * BM;
     FlashJob J;
-    J.k0 = J.v0 = nullptr; J.n0 = 0; J.slab = 1; J.slab_stride = 0;
+    J.k0 = J.k1 = P.k_read; J.v0 = J.v1 = P.v_read; J.n0 = 0; J.slab = 1; J.slab_magic = 0; J.slab_stride = 0;
     J.k1 = P.k_read + (long)bh * P.R * D; J.v1 = P.v_read + (long)bh * P.R * D; J.n1 = P.R;
     J.k2 = P.k_mem + (long)bh * P.t * D;  J.v2 = P.v_mem + (long)bh * P.t * D;  J.n2 = P.t;
     J.causal_base = NO_CAUSAL;
@@ -488,6 +494,7 @@ int launch_mask_attn_mfma(const void* q, const void* k, const void* v, void* out
     P.out = static_cast<bf16_t*>(out); P.lse = lse;
     const int bm = mask_block_rows(g.R);
     P.sched = MaskSchedule::make(nbh, g.t, g.c, g.n, bm);
+    P.slab_magic = g.t > 1 ? (unsigned)((1ULL << 32) / (unsigned)g.t) + 1u : 0u;
     P.sc = scale * LOG2E;
     return D == 128 ? launch_mask_d<128>(P, bm, st) : launch_mask_d<64>(P, bm, st);
 }
