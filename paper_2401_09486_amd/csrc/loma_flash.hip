@@ -158,7 +158,8 @@ __device__ __forceinline__ s16x4 lds_read_tr(const bf16_t* p) {
 template <int D, int NW, int BN>
 __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* smem) {
     using C = Cfg<D, NW, BN>;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, kept in a scalar register
     const int g = lane >> 5, l32 = lane & 31;
     bf16_t* Ks = smem;
     bf16_t* Vt = smem + 2 * C::KBUF;
@@ -204,9 +205,8 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     for (int kt = 0; kt < ntiles; ++kt) {
         const int buf = kt & 1;
         const bool more = kt + 1 < ntiles;
-        if (more) load_tile<D, NW, BN>(J, (kt + 1) * BN, nkeys, tid, kreg, vreg);
-
         const int k0 = kt * BN;
+        bool loaded = false;
         if (k0 < kend_w) {
             const bf16_t* Kb = Ks + buf * C::KBUF;
             const bf16_t* Vb = Vt + buf * C::VBUF;
@@ -226,6 +226,9 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
                     }
                 }
             }
+            // next tile's global loads go out here, behind the score MFMAs, and are only waited
+            // for when the tile is written to LDS at the end of the iteration
+            if (more) { load_tile<D, NW, BN>(J, (kt + 1) * BN, nkeys, tid, kreg, vreg); loaded = true; }
             // accumulator i of lane (l32, g) is key 8*(i/4) + 4*g + i%4 of the sub-tile
             if (k0 + 32 * nsub - 1 > wave_lim) {
 #pragma unroll
@@ -293,7 +296,10 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
                 }
         }
 
-        if (more) store_tile<D, NW, BN>(Ks + (buf ^ 1) * C::KBUF, Vt + (buf ^ 1) * C::VBUF, tid, kreg, vreg);
+        if (more) {
+            if (!loaded) load_tile<D, NW, BN>(J, (kt + 1) * BN, nkeys, tid, kreg, vreg);   // waves past their causal limit
+            store_tile<D, NW, BN>(Ks + (buf ^ 1) * C::KBUF, Vt + (buf ^ 1) * C::VBUF, tid, kreg, vreg);
+        }
         __syncthreads();
     }
 
