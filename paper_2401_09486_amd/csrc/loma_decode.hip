@@ -3,15 +3,19 @@
 //     [ n_mem_chunks*t memory-zone KVs | read_fill live reading-zone KVs | the new token ]
 // with no mask, so the step is one pass over K and V: HBM-bound (2 flop per byte).
 //
-// Grid = (key splits, B*H).  A workgroup of 4 waves streams its key range with 16-byte
-// loads: D/8 lanes cover one 2*D-byte row, so a wave-wide load instruction fetches 64/(D/8)
-// whole rows, fully coalesced; each wave keeps 8 K and 8 V loads in flight.  Scores use
-// packed bf16 dot products with fp32 accumulation and a butterfly over the lanes of a row;
-// every lane group carries its own online-softmax state (m, l, acc[8]) so the loop needs no
-// cross-group traffic.  Groups are merged through LDS at the end; splits are merged by a
-// second tiny kernel in a fixed order (deterministic, no atomics).  The new token's K/V are
-// read from k_new/v_new and appended to the reading zone by split 0 -- no workgroup reads
-// the row another one is writing.
+// Grid = (key splits, B*H).  A workgroup streams its key range with 16-byte loads: D/8 lanes
+// cover one 2*D-byte row, so a wave-wide load instruction fetches 64/(D/8) whole rows, fully
+// coalesced; each wave keeps 8 K and 8 V loads in flight.  Scores use packed bf16 dot products
+// with fp32 accumulation and a butterfly over the lanes of a row; every lane group carries its
+// own online-softmax state (m, l, acc[8]) so the loop needs no cross-group traffic.  The lane
+// groups of a wave are merged with lane permutes, the waves through LDS.  Two shapes:
+//   few (b,h) pairs (< 1024): 16 waves per workgroup, one workgroup per (b,h) when that already
+//       gives one workgroup per CU -- a single launch, no partial results in HBM;
+//   many (b,h) pairs: 4 waves per workgroup, thousands of workgroups.
+// When one (b,h) is split over several workgroups, the partial (m, l, acc) go to the workspace
+// and a second tiny kernel merges them in a fixed order (deterministic, no atomics).  The new
+// token's K/V are read from k_new/v_new and appended to the reading zone by split 0 -- no
+// workgroup reads the row another one is writing.
 #include "loma_internal.h"
 
 namespace loma {
@@ -22,9 +26,10 @@ typedef uint16_t bf16_t;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 constexpr float LOG2E = 1.4426950408889634f;
-constexpr int DEC_WAVES = 4;
-constexpr int DEC_UNROLL = 8;      // row-loads in flight per wave, for K and for V
-constexpr int DEC_TARGET_WGS = 4096;
+constexpr int DEC_UNROLL = 8;          // row-loads in flight per wave, for K and for V
+constexpr int DEC_SMALL_NBH = 1024;    // below: 16-wave workgroups, ~1 per CU; from here on: 4-wave workgroups
+constexpr int DEC_TARGET_WGS_16 = 256;
+constexpr int DEC_TARGET_WGS_4 = 4096;
 
 struct DecodeParams {
     const bf16_t *q, *k_new, *v_new, *k_mem, *v_mem;
@@ -64,14 +69,13 @@ __device__ __forceinline__ float row_sum(float x) {
     return x;
 }
 
-template <int D>
+template <int D, int DEC_WAVES>
 __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodeParams P) {
     constexpr int LPR = D / 8;            // lanes per key row
     constexpr int RPL = 64 / LPR;         // rows per wave-wide load
     constexpr int KPW = RPL * DEC_UNROLL; // keys per wave iteration
-    constexpr int NG = DEC_WAVES * RPL;   // lane groups per workgroup
-    __shared__ float sm_acc[NG][D];
-    __shared__ float sm_m[NG], sm_l[NG];
+    __shared__ float sm_acc[DEC_WAVES][D];
+    __shared__ float sm_m[DEC_WAVES], sm_l[DEC_WAVES];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int sp = blockIdx.x;
@@ -144,19 +148,32 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodePara
         m = mx;
     }
 
-    // merge the lane groups of the workgroup
-    const int grp = w * RPL + sub;
+    // merge the lane groups of the wave: partner groups sit 16 and 32 lanes away (and 8 for D = 64)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) sm_acc[grp][col * 8 + e] = acc[e];
-    if (col == 0) { sm_m[grp] = m; sm_l[grp] = l; }
+    for (int off = LPR; off < 64; off <<= 1) {
+        const float m2 = __shfl_xor(m, off), l2 = __shfl_xor(l, off);
+        const float M = fmaxf(m, m2);
+        const float w1 = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - M);
+        const float w2 = (m2 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m2 - M);
+        l = l * w1 + l2 * w2;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = acc[e] * w1 + __shfl_xor(acc[e], off) * w2;
+        m = M;
+    }
+    // merge the waves of the workgroup
+    if (sub == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sm_acc[w][col * 8 + e] = acc[e];
+        if (col == 0) { sm_m[w] = m; sm_l[w] = l; }
+    }
     __syncthreads();
     if (tid < D) {
         float M = -INFINITY;
 #pragma unroll
-        for (int gidx = 0; gidx < NG; ++gidx) M = fmaxf(M, sm_m[gidx]);
+        for (int gidx = 0; gidx < DEC_WAVES; ++gidx) M = fmaxf(M, sm_m[gidx]);
         float Lsum = 0.f, o = 0.f;
 #pragma unroll
-        for (int gidx = 0; gidx < NG; ++gidx) {
+        for (int gidx = 0; gidx < DEC_WAVES; ++gidx) {
             const float wgt = (sm_m[gidx] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sm_m[gidx] - M);
             Lsum = fmaf(sm_l[gidx], wgt, Lsum);
             o = fmaf(sm_acc[gidx][tid], wgt, o);
@@ -195,26 +212,32 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(DecodeParams P) {
     P.out[bh * D + tid] = f32_to_bf16(o / Lsum);
 }
 
-inline int target_splits(int nbh) { return (DEC_TARGET_WGS + nbh - 1) / nbh; }
+inline int wg_waves(int nbh) { return nbh < DEC_SMALL_NBH ? 16 : 4; }
+inline int target_splits(int nbh) {
+    const int target = nbh < DEC_SMALL_NBH ? DEC_TARGET_WGS_16 : DEC_TARGET_WGS_4;
+    return (target + nbh - 1) / nbh;
+}
 
 // keys per split: whole workgroup iterations, at most target_splits(nbh) splits
-template <int D>
-void plan_splits(int nbh, int n_keys, int& nsplit, int& keys_per_split) {
-    constexpr int KPI = DEC_WAVES * (64 / (D / 8)) * DEC_UNROLL;  // keys per workgroup iteration
-    const int units = (n_keys + KPI - 1) / KPI;
+void plan_splits(int nbh, int D, int n_keys, int& nsplit, int& keys_per_split) {
+    const int kpi = wg_waves(nbh) * (64 / (D / 8)) * DEC_UNROLL;  // keys per workgroup iteration
+    const int units = (n_keys + kpi - 1) / kpi;
     const int tgt = target_splits(nbh);
     const int ups = (units + tgt - 1) / tgt;
     nsplit = (units + ups - 1) / ups;
-    keys_per_split = ups * KPI;
+    keys_per_split = ups * kpi;
 }
 
 template <int D>
 int launch_decode_d(DecodeParams& P, int nbh, void* workspace, hipStream_t st) {
-    plan_splits<D>(nbh, P.L, P.nsplit, P.keys_per_split);
+    plan_splits(nbh, D, P.L, P.nsplit, P.keys_per_split);
     P.ws_acc = static_cast<float*>(workspace);
     P.ws_ml = P.ws_acc ? P.ws_acc + (size_t)nbh * target_splits(nbh) * D : nullptr;
     if (nbh > 65535) return LOMA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(decode_split_kernel<D>, dim3(P.nsplit, nbh), dim3(64 * DEC_WAVES), 0, st, P);
+    if (wg_waves(nbh) == 16)
+        hipLaunchKernelGGL((decode_split_kernel<D, 16>), dim3(P.nsplit, nbh), dim3(1024), 0, st, P);
+    else
+        hipLaunchKernelGGL((decode_split_kernel<D, 4>), dim3(P.nsplit, nbh), dim3(256), 0, st, P);
     if (hipGetLastError() != hipSuccess) return LOMA_ERR_LAUNCH;
     if (P.nsplit > 1) {
         hipLaunchKernelGGL(decode_combine_kernel<D>, dim3(nbh), dim3(D), 0, st, P);
@@ -227,7 +250,7 @@ int launch_decode_d(DecodeParams& P, int nbh, void* workspace, hipStream_t st) {
 
 int decode_num_splits(int nbh, int n_keys) {
     int ns, kps;
-    plan_splits<128>(nbh, n_keys, ns, kps);
+    plan_splits(nbh, 128, n_keys, ns, kps);
     return ns;
 }
 

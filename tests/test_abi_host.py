@@ -112,11 +112,11 @@ def test_decode_rejects_bad_arguments(lib):
     assert decode_call(lib, nmem=0, fill=0, kn=None, vn=None) == EINVAL   # nothing to attend to
     assert decode_call(lib, kr=P + 4) == EINVAL
     assert decode_call(lib, dtype=-1) == EUNSUP
-    # split-K needs its workspace
-    need = lib.loma_decode_workspace_bytes(8, 32, 128, 16, 4, 4, BF16)
+    # split-K (few (b,h) pairs) needs its workspace
+    need = lib.loma_decode_workspace_bytes(1, 8, 128, 16, 4, 4, BF16)
     assert need > 0
-    assert decode_call(lib, ws=None) == EWS
-    assert decode_call(lib, wsb=need - 1) == EWS
+    assert decode_call(lib, B=1, H=8, ws=None) == EWS
+    assert decode_call(lib, B=1, H=8, wsb=need - 1) == EWS
 
 
 def test_decode_workspace_bytes(lib):
@@ -124,9 +124,10 @@ def test_decode_workspace_bytes(lib):
     assert f(0, 32, 128, 16, 4, 4, BF16) == 0
     assert f(8, 32, 100, 16, 4, 4, BF16) == 0
     assert f(8, 32, 128, 16, 4, -1, BF16) == 0
-    a = f(8, 32, 128, 16, 4, 64, BF16)
+    a = f(1, 32, 128, 16, 4, 64, BF16)
     assert a > 0 and a % 4 == 0
-    # large batches do not split: no workspace
+    # one workgroup per (b,h) already fills the chip: no split, no workspace
+    assert f(8, 32, 128, 16, 4, 64, BF16) == 0
     assert f(64, 64, 128, 16, 16, 512, BF16) == 0
 
 
