@@ -13,12 +13,13 @@
 // Per 32x32 tile the scores are produced TRANSPOSED, S^T = K Q^T (keys down the rows,
 // queries across the lanes), so a query's softmax statistics live in two lanes (l, l^32)
 // and the probabilities come out of the accumulators already in the register layout the
-// second product O^T += V^T P^T wants as its B operand.  K and V tiles both sit in LDS
-// row-major, exactly as they lie in HBM (16-byte stores, no shuffling): the K operand is a plain
-// 16-byte LDS read, the V^T operand comes from the transposing LDS read of gfx950
-// (ds_read_b64_tr_b16: inside 16 lanes, lane i receives the i-th 16-bit column of four rows).
-// Tiles are double-buffered: global loads for tile i+1 are in flight while tile i is
-// multiplied; one barrier per tile.
+// second product O^T += V^T P^T wants as its B operand.  K and V tiles go from HBM straight into
+// LDS (global_load_lds_dwordx4: no registers, no LDS store instructions), row-major with the
+// 16-byte pieces of every row XOR-permuted so that both read patterns are free of bank
+// conflicts: the K operand is a plain 16-byte LDS read, the V^T operand comes from the
+// transposing LDS read of gfx950 (ds_read_b64_tr_b16: inside 16 lanes, lane i receives the i-th
+// 16-bit column of four rows).  Tiles are double-buffered: the loads for tile i+1 are in flight
+// while tile i is multiplied; one barrier per tile.
 #include "loma_internal.h"
 
 namespace loma {
@@ -55,21 +56,23 @@ struct Cfg {
     static constexpr int NT = 64 * NW;
     static constexpr int BM = 32 * NW;
     static constexpr int CPR = D / 8;        // 16-byte pieces per row
-    // row strides in elements.  K rows are read 16 B per lane by 16 lanes on 16 consecutive rows:
-    // D/2+4 dwords (== 4 mod 8) spreads them over all banks.  V rows are read by the transposing
-    // load, 4 rows x 32 B per 16 lanes, two column halves at once: D/2+16 dwords keeps them apart.
-    static constexpr int KSTR = D + 8;
-    static constexpr int VSTR = D + 32;
-    static constexpr int KBUF = BN * KSTR;
-    static constexpr int VBUF = BN * VSTR;
+    // Tiles are dense [BN][D] in LDS (the direct loads write 1 KB runs); instead of padding, the
+    // 16-byte piece c of tile row r is stored at piece position c ^ swizzle(r):
+    //   K: swizzle = r % CPR        -> 16 lanes reading one piece of 16 consecutive rows hit 16 banks groups
+    //   V: swizzle = 4*(r % 4) % CPR -> the 4 rows x 32 B of a transposing read (two column halves at
+    //                                   once) fall into 8 different 32-byte groups
+    static constexpr int KBUF = BN * D;
+    static constexpr int VBUF = BN * D;
     static constexpr int SMEM_BYTES = 2 * (KBUF + VBUF) * 2;
-    static constexpr int NTASK = (BN / 4) * CPR;          // (4 keys) x (8 head-dim) load tasks
-    static constexpr int TPT = (NTASK + NT - 1) / NT;     // tasks per thread
+    static constexpr int OSTR = D + 8;                   // row stride of the output staging area
+    static constexpr int RPI = 64 / CPR;                 // tile rows one wave-wide direct load covers
+    static constexpr int IPW = BN / RPI / NW;            // direct loads per wave, per tensor, per tile
     static constexpr int NSUB = BN / 32;
     static constexpr int KSTEPS = D / 16;
     static constexpr int DT = D / 32;
     static_assert(BN % 32 == 0 && D % 32 == 0, "tile shape");
-    static_assert(2 * KBUF >= NW * 32 * KSTR, "output staging must fit in the K buffers");
+    static_assert(BN % (RPI * NW) == 0, "tile rows must split evenly over the waves");
+    static_assert(2 * (KBUF + VBUF) >= NW * 32 * OSTR, "output staging must fit in the tile buffers");
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -105,46 +108,33 @@ __device__ __forceinline__ void key_row(const FlashJob& J, int j, const bf16_t*&
     vp = (in0 ? J.v0 : (in1 ? J.v1 : J.v2)) + off;
 }
 
-// A thread fetches one 16-byte piece of four consecutive keys, for K and for V.  Keys past the
-// end of the list are clamped to the last key: their scores are masked and their
-// probabilities are exactly 0, so any finite row will do and no lane ever branches.
+// Direct HBM -> LDS copy of one K and one V tile.  A wave-wide load moves 64 x 16 B into 1 KB of
+// LDS (lane l lands at byte 16*l): RPI whole tile rows.  Each lane picks the global piece that
+// belongs at its LDS position under the row's XOR permutation.  Keys past the end of the list
+// are clamped to the last key: their scores are masked and their probabilities are exactly 0,
+// so any finite row will do and no lane ever branches.
 template <int D, int NW, int BN>
-__device__ __forceinline__ void load_tile(const FlashJob& J, int k0, int nkeys, int tid,
-                                          u32x4 (&kreg)[Cfg<D, NW, BN>::TPT][4],
-                                          u32x4 (&vreg)[Cfg<D, NW, BN>::TPT][4]) {
+__device__ __forceinline__ void load_tile_async(const FlashJob& J, int k0, int nkeys, int w, int lane,
+                                                bf16_t* Kb, bf16_t* Vb) {
     using C = Cfg<D, NW, BN>;
+    const int p = lane % C::CPR;
 #pragma unroll
-    for (int i = 0; i < C::TPT; ++i) {
-        const int task = (tid + i * C::NT) % C::NTASK;   // surplus threads repeat a task
-        const int dch = task % C::CPR, kg = task / C::CPR;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int j = min(k0 + 4 * kg + b, nkeys - 1);
-            const bf16_t *kp, *vp;
-            key_row<D>(J, j, kp, vp);
-            kreg[i][b] = *reinterpret_cast<const u32x4*>(kp + dch * 8);
-            vreg[i][b] = *reinterpret_cast<const u32x4*>(vp + dch * 8);
-        }
+    for (int i = 0; i < C::IPW; ++i) {
+        const int rbase = (w * C::IPW + i) * C::RPI;   // wave-uniform
+        const int r = rbase + lane / C::CPR;
+        const bf16_t *kp, *vp;
+        key_row<D>(J, min(k0 + r, nkeys - 1), kp, vp);
+        const int ck = p ^ (r % C::CPR);
+        const int cv = p ^ ((4 * (r % 4)) % C::CPR);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kp + ck * 8),
+                                         (__attribute__((address_space(3))) void*)(Kb + rbase * D), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vp + cv * 8),
+                                         (__attribute__((address_space(3))) void*)(Vb + rbase * D), 16, 0, 0);
     }
 }
 
-// Both tiles row-major; 16 consecutive lanes write one whole row.
-template <int D, int NW, int BN>
-__device__ __forceinline__ void store_tile(bf16_t* Kb, bf16_t* Vb, int tid,
-                                           const u32x4 (&kreg)[Cfg<D, NW, BN>::TPT][4],
-                                           const u32x4 (&vreg)[Cfg<D, NW, BN>::TPT][4]) {
-    using C = Cfg<D, NW, BN>;
-#pragma unroll
-    for (int i = 0; i < C::TPT; ++i) {
-        const int task = (tid + i * C::NT) % C::NTASK;
-        const int dch = task % C::CPR, kg = task / C::CPR;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            *reinterpret_cast<u32x4*>(Kb + (4 * kg + b) * C::KSTR + dch * 8) = kreg[i][b];
-            *reinterpret_cast<u32x4*>(Vb + (4 * kg + b) * C::VSTR + dch * 8) = vreg[i][b];
-        }
-    }
-}
+// all direct loads of this wave have landed in LDS (vmcnt(0); the other counters untouched)
+__device__ __forceinline__ void wait_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 // Transposing LDS read: the 16 lanes of a group each point at 8 bytes; lane i of the group
 // receives element (i % 4) of the lanes 4e + i/4, e = 0..3.  With lane i pointing at row i/4,
@@ -153,6 +143,146 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 __device__ __forceinline__ s16x4 lds_read_tr(const bf16_t* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
         (__attribute__((address_space(3))) s16x4*)(const_cast<bf16_t*>(p)));
+}
+
+// One key tile for one wave: scores, online softmax, PV.  FULL = every key of the tile is visible
+// to every row of the wave (no mask, no sub-tile skipping): the hot path, written as straight-line
+// code with the LDS operand reads issued well ahead of the MFMAs that consume them.
+template <int D, int NW, int BN, bool FULL>
+__device__ __forceinline__ void score_phase(const bf16_t* Kb, const int (&koff)[Cfg<D, NW, BN>::KSTEPS],
+                                            const bf16x8 (&qreg)[Cfg<D, NW, BN>::KSTEPS],
+                                            f32x16 (&S)[Cfg<D, NW, BN>::NSUB],
+                                            int k0, int nsub, int my_lim, int lane) {
+    using C = Cfg<D, NW, BN>;
+    const int g = lane >> 5, l32 = lane & 31;
+#pragma unroll
+    for (int sub = 0; sub < C::NSUB; ++sub)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) S[sub][i] = 0.f;
+
+    // ---- S^T = K Q^T -------------------------------------------------------------------------
+    if constexpr (FULL) {
+        constexpr int AHEAD = 4;   // K operands in flight: AHEAD k-steps of every sub-tile
+        bf16x8 ka[C::NSUB][AHEAD];
+#pragma unroll
+        for (int ks = 0; ks < AHEAD; ++ks)
+#pragma unroll
+            for (int sub = 0; sub < C::NSUB; ++sub)
+                ka[sub][ks] = *reinterpret_cast<const bf16x8*>(Kb + koff[ks] + 32 * sub * D);
+#pragma unroll
+        for (int ks = 0; ks < C::KSTEPS; ++ks) {
+#pragma unroll
+            for (int sub = 0; sub < C::NSUB; ++sub) {
+                S[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][ks % AHEAD], qreg[ks], S[sub], 0, 0, 0);
+                if (ks + AHEAD < C::KSTEPS)
+                    ka[sub][ks % AHEAD] = *reinterpret_cast<const bf16x8*>(
+                        Kb + koff[(ks + AHEAD) % C::KSTEPS] + 32 * sub * D);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int sub = 0; sub < C::NSUB; ++sub)
+            if (sub < nsub) {
+#pragma unroll
+                for (int ks = 0; ks < C::KSTEPS; ++ks) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(Kb + koff[ks] + 32 * sub * D);
+                    S[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], S[sub], 0, 0, 0);
+                }
+            }
+        // accumulator i of lane (l32, g) is key 8*(i/4) + 4*g + i%4 of the sub-tile
+#pragma unroll
+        for (int sub = 0; sub < C::NSUB; ++sub)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int j = k0 + 32 * sub + 8 * (i >> 2) + 4 * g + (i & 3);
+                if (j > my_lim) S[sub][i] = -INFINITY;
+            }
+    }
+}
+
+template <int D, int NW, int BN, bool FULL>
+__device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&voff)[Cfg<D, NW, BN>::DT],
+                                                 f32x16 (&S)[Cfg<D, NW, BN>::NSUB],
+                                                 f32x16 (&O)[Cfg<D, NW, BN>::DT], float& m, float& lsum,
+                                                 float sc, int nsub, int lane) {
+    using C = Cfg<D, NW, BN>;
+    // ---- online softmax (per query: lanes l and l^32) ---------------------------------------------
+    float mx = m;
+#pragma unroll
+    for (int sub = 0; sub < C::NSUB; ++sub)
+        if (FULL || sub < nsub) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[sub][i]);
+        }
+    mx = pair_max(mx);
+    // rescale by exp2((m_old - m_new) * sc): exactly 1 for the rows whose maximum did not move.
+    // (Unconditional on purpose: a branch around it makes the compiler keep two copies of O.)
+    {
+        const float alpha = __builtin_amdgcn_exp2f((m - mx) * sc);
+        lsum *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[dt][i] *= alpha;
+        m = mx;
+    }
+    const float mc = m * sc;
+    float ps = 0.f;
+#pragma unroll
+    for (int sub = 0; sub < C::NSUB; ++sub)
+        if (FULL || sub < nsub) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float p = __builtin_amdgcn_exp2f(S[sub][i] * sc - mc);
+                ps += p;
+                S[sub][i] = p;
+            }
+        }
+    lsum += ps;
+
+    // ---- O^T += V^T P^T ------------------------------------------------------------------------------
+    // V^T operand: lane (d = 32*dt + l32, half g) needs keys 16*step + 8*a + 4*g + 0..3, a = 0,1
+    auto read_v = [&](int step, int dt) -> bf16x8 {
+        const bf16_t* vp = Vb + voff[dt] + 16 * step * D;
+        const s16x4 lo = lds_read_tr(vp);
+        const s16x4 hi = lds_read_tr(vp + 8 * D);
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    auto pack_p = [&](int step) -> bf16x8 {
+        const int sub = step >> 1, jj = step & 1;
+        uint4 pw;
+        pw.x = pack_bf16(S[sub][8 * jj + 0], S[sub][8 * jj + 1]);
+        pw.y = pack_bf16(S[sub][8 * jj + 2], S[sub][8 * jj + 3]);
+        pw.z = pack_bf16(S[sub][8 * jj + 4], S[sub][8 * jj + 5]);
+        pw.w = pack_bf16(S[sub][8 * jj + 6], S[sub][8 * jj + 7]);
+        return __builtin_bit_cast(bf16x8, pw);
+    };
+    constexpr int NSTEP = 2 * C::NSUB;
+    if constexpr (FULL) {
+        bf16x8 va[2][C::DT];
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt) va[0][dt] = read_v(0, dt);
+#pragma unroll
+        for (int step = 0; step < NSTEP; ++step) {
+            if (step + 1 < NSTEP) {
+#pragma unroll
+                for (int dt = 0; dt < C::DT; ++dt) va[(step + 1) & 1][dt] = read_v(step + 1, dt);
+            }
+            const bf16x8 pb = pack_p(step);
+#pragma unroll
+            for (int dt = 0; dt < C::DT; ++dt)
+                O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[step & 1][dt], pb, O[dt], 0, 0, 0);
+        }
+    } else {
+#pragma unroll
+        for (int step = 0; step < NSTEP; ++step)
+            if ((step >> 1) < nsub) {
+                const bf16x8 pb = pack_p(step);
+#pragma unroll
+                for (int dt = 0; dt < C::DT; ++dt)
+                    O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v(step, dt), pb, O[dt], 0, 0, 0);
+            }
+    }
 }
 
 template <int D, int NW, int BN>
@@ -173,7 +303,6 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     const int kend_w = has_rows ? min(nkeys, J.causal_base + row_hi) : 0;
     const int my_row = min(row0 + l32, J.q_rows - 1);          // padded lanes replay the last row
     const int my_lim = min(J.causal_base + my_row, nkeys - 1);  // last key this lane's query sees
-    const int wave_lim = min(J.causal_base + row0, nkeys - 1);  // the smallest such limit in the wave
 
     // Q^T as the B operand: lane (query l32, half g) holds head-dim 16*ks + 8*g .. +7
     bf16x8 qreg[C::KSTEPS];
@@ -195,111 +324,52 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
         for (int i = 0; i < 16; ++i) O[dt][i] = 0.f;
     float m = -INFINITY, lsum = 0.f;
 
-    u32x4 kreg[C::TPT][4], vreg[C::TPT][4];
-    if (ntiles > 0) {
-        load_tile<D, NW, BN>(J, 0, nkeys, tid, kreg, vreg);
-        store_tile<D, NW, BN>(Ks, Vt, tid, kreg, vreg);
+    // per-lane LDS offsets (elements) of the operand reads, under the tiles' XOR permutations
+    int koff[C::KSTEPS], voff[C::DT];
+#pragma unroll
+    for (int ks = 0; ks < C::KSTEPS; ++ks) koff[ks] = l32 * D + (((2 * ks + g) ^ (l32 % C::CPR)) * 8);
+    {
+        const int i = lane & 15, q = i >> 2;   // source-lane role in the transposing read: row q, columns 4*(i%4)..
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+            voff[dt] = (4 * g + q) * D + (4 * (dt ^ (q % (C::CPR / 4))) + 2 * ((lane >> 4) & 1) + ((i & 3) >> 1)) * 8 +
+                       4 * (i & 1);
     }
+
+    if (ntiles > 0) load_tile_async<D, NW, BN>(J, 0, nkeys, w, lane, Ks, Vt);
+    wait_direct_loads();
     __syncthreads();
 
-    for (int kt = 0; kt < ntiles; ++kt) {
+    // Tiles that every row of the block sees in full come first and run in a loop of their own:
+    // straight-line code, no per-wave decisions (this is where the time goes).  Blocks with
+    // unused waves take the general loop for all their tiles.
+    const int nfull = (J.q_rows == C::BM) ? min(ntiles, (min(J.causal_base, nkeys - 1) + 1) / BN) : 0;
+    for (int kt = 0; kt < nfull; ++kt) {
         const int buf = kt & 1;
-        const bool more = kt + 1 < ntiles;
+        if (kt + 1 < ntiles)
+            load_tile_async<D, NW, BN>(J, (kt + 1) * BN, nkeys, w, lane, Ks + (buf ^ 1) * C::KBUF,
+                                       Vt + (buf ^ 1) * C::VBUF);
+        f32x16 S[C::NSUB];
+        score_phase<D, NW, BN, true>(Ks + buf * C::KBUF, koff, qreg, S, kt * BN, C::NSUB, my_lim, lane);
+        softmax_pv_phase<D, NW, BN, true>(Vt + buf * C::VBUF, voff, S, O, m, lsum, sc, C::NSUB, lane);
+        wait_direct_loads();
+        __syncthreads();
+    }
+    // The remaining tiles: cut by the causal diagonal or by the end of the key list, differently
+    // for every wave (a wave past its last visible key only helps with the loads).
+    for (int kt = nfull; kt < ntiles; ++kt) {
+        const int buf = kt & 1;
         const int k0 = kt * BN;
-        bool loaded = false;
+        if (kt + 1 < ntiles)
+            load_tile_async<D, NW, BN>(J, (kt + 1) * BN, nkeys, w, lane, Ks + (buf ^ 1) * C::KBUF,
+                                       Vt + (buf ^ 1) * C::VBUF);
         if (k0 < kend_w) {
-            const bf16_t* Kb = Ks + buf * C::KBUF;
-            const bf16_t* Vb = Vt + buf * C::VBUF;
             const int nsub = min(C::NSUB, (kend_w - k0 + 31) >> 5);
-
             f32x16 S[C::NSUB];
-#pragma unroll
-            for (int sub = 0; sub < C::NSUB; ++sub) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) S[sub][i] = 0.f;
-                if (sub < nsub) {
-                    const bf16_t* kp = Kb + (32 * sub + l32) * C::KSTR + 8 * g;
-#pragma unroll
-                    for (int ks = 0; ks < C::KSTEPS; ++ks) {
-                        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
-                        S[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], S[sub], 0, 0, 0);
-                    }
-                }
-            }
-            // next tile's global loads go out here, behind the score MFMAs, and are only waited
-            // for when the tile is written to LDS at the end of the iteration
-            if (more) { load_tile<D, NW, BN>(J, (kt + 1) * BN, nkeys, tid, kreg, vreg); loaded = true; }
-            // accumulator i of lane (l32, g) is key 8*(i/4) + 4*g + i%4 of the sub-tile
-            if (k0 + 32 * nsub - 1 > wave_lim) {
-#pragma unroll
-                for (int sub = 0; sub < C::NSUB; ++sub)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int j = k0 + 32 * sub + 8 * (i >> 2) + 4 * g + (i & 3);
-                        if (j > my_lim) S[sub][i] = -INFINITY;
-                    }
-            }
-            float mx = m;
-#pragma unroll
-            for (int sub = 0; sub < C::NSUB; ++sub)
-                if (sub < nsub) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[sub][i]);
-                }
-            mx = pair_max(mx);
-            // the running maximum moved for some query of this wave: rescale (rare after the first tiles)
-            if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {
-                const float alpha = __builtin_amdgcn_exp2f((m - mx) * sc);
-                lsum *= alpha;
-#pragma unroll
-                for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) O[dt][i] *= alpha;
-                m = mx;
-            }
-            const float mc = m * sc;
-            float ps = 0.f;
-#pragma unroll
-            for (int sub = 0; sub < C::NSUB; ++sub)
-                if (sub < nsub) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float p = __builtin_amdgcn_exp2f(S[sub][i] * sc - mc);
-                        ps += p;
-                        S[sub][i] = p;
-                    }
-                }
-            lsum += ps;
-            // V^T operand: lane (d = 32*dt + l32, half g) needs keys 16*step + 8*a + 4*g + 0..3, a = 0,1
-            const bf16_t* vbase = Vb + (4 * g + ((lane & 15) >> 2)) * C::VSTR + (l32 & 16) + 4 * (lane & 3);
-#pragma unroll
-            for (int sub = 0; sub < C::NSUB; ++sub)
-                if (sub < nsub) {
-#pragma unroll
-                    for (int jj = 0; jj < 2; ++jj) {
-                        uint4 pw;
-                        pw.x = pack_bf16(S[sub][8 * jj + 0], S[sub][8 * jj + 1]);
-                        pw.y = pack_bf16(S[sub][8 * jj + 2], S[sub][8 * jj + 3]);
-                        pw.z = pack_bf16(S[sub][8 * jj + 4], S[sub][8 * jj + 5]);
-                        pw.w = pack_bf16(S[sub][8 * jj + 6], S[sub][8 * jj + 7]);
-                        const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
-                        const bf16_t* vp = vbase + 16 * (2 * sub + jj) * C::VSTR;
-#pragma unroll
-                        for (int dt = 0; dt < C::DT; ++dt) {
-                            const s16x4 lo = lds_read_tr(vp + 32 * dt);
-                            const s16x4 hi = lds_read_tr(vp + 32 * dt + 8 * C::VSTR);
-                            const bf16x8 a = __builtin_bit_cast(
-                                bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                            O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, O[dt], 0, 0, 0);
-                        }
-                    }
-                }
+            score_phase<D, NW, BN, false>(Ks + buf * C::KBUF, koff, qreg, S, k0, nsub, my_lim, lane);
+            softmax_pv_phase<D, NW, BN, false>(Vt + buf * C::VBUF, voff, S, O, m, lsum, sc, nsub, lane);
         }
-
-        if (more) {
-            if (!loaded) load_tile<D, NW, BN>(J, (kt + 1) * BN, nkeys, tid, kreg, vreg);   // waves past their causal limit
-            store_tile<D, NW, BN>(Ks + (buf ^ 1) * C::KBUF, Vt + (buf ^ 1) * C::VBUF, tid, kreg, vreg);
-        }
+        wait_direct_loads();
         __syncthreads();
     }
 
@@ -344,7 +414,7 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     // normalise, transpose through LDS (the K buffers are free now), store rows coalesced
     const float ltot = pair_sum(lsum);
     const float inv = 1.f / ltot;
-    bf16_t* Os = smem + w * 32 * C::KSTR;
+    bf16_t* Os = smem + w * 32 * C::OSTR;
     if (has_rows) {
 #pragma unroll
         for (int dt = 0; dt < C::DT; ++dt)
@@ -353,7 +423,7 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
                 uint2 x;
                 x.x = pack_bf16(O[dt][4 * i4 + 0] * inv, O[dt][4 * i4 + 1] * inv);
                 x.y = pack_bf16(O[dt][4 * i4 + 2] * inv, O[dt][4 * i4 + 3] * inv);
-                *reinterpret_cast<uint2*>(Os + l32 * C::KSTR + 32 * dt + 8 * i4 + 4 * g) = x;
+                *reinterpret_cast<uint2*>(Os + l32 * C::OSTR + 32 * dt + 8 * i4 + 4 * g) = x;
             }
         if (J.lse != nullptr && g == 0 && row0 + l32 < J.q_rows)
             J.lse[row0 + l32] = (m * sc + __builtin_amdgcn_logf(ltot)) * LN2;
@@ -366,7 +436,7 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
             const int r = idx / C::CPR, ch = idx % C::CPR;
             if (row0 + r < J.q_rows)
                 *reinterpret_cast<uint4*>(J.out + (long)(row0 + r) * D + ch * 8) =
-                    *reinterpret_cast<const uint4*>(Os + r * C::KSTR + ch * 8);
+                    *reinterpret_cast<const uint4*>(Os + r * C::OSTR + ch * 8);
         }
     }
 }
@@ -382,7 +452,7 @@ struct MaskParams {
 };
 
 template <int D, int NW, int BN>
-__global__ __launch_bounds__(64 * NW) void mask_attn_kernel(MaskParams P) {
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void mask_attn_kernel(MaskParams P) {
     extern __shared__ __align__(16) bf16_t smem[];
     const MaskSchedule& sch = P.sched;
     const MaskJob mj = sch.decode(blockIdx.x);
@@ -431,7 +501,7 @@ struct CompressParams {
 };
 
 template <int D, int NW, int BN>
-__global__ __launch_bounds__(64 * NW) void compress_kernel(CompressParams P) {
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void compress_kernel(CompressParams P) {
     extern __shared__ __align__(16) bf16_t smem[];
     constexpr int BM = 32 * NW;
     const int bh = blockIdx.x / P.nblk, blk = blockIdx.x % P.nblk;

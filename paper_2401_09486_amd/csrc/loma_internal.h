@@ -29,49 +29,58 @@ struct MaskJob {
 };
 
 // Tile-schedule arithmetic, identical on host (tests, grid sizing) and device (job decode).
-// Work list per (b,h), longest first: reading blocks of the last chunk down to the first
-// (they see y*t earlier memory keys), then memory blocks, then repetition blocks.
-// Workgroup id -> (b,h) fastest, so that with B*H a multiple of 8 every (b,h) stays on one
-// XCD (workgroups are dealt round-robin to the 8 XCDs) and its memory-zone K/V stays in
-// that XCD's L2.
+// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  With B*H a multiple of 8
+// workgroup id -> XCD id % 8, and every XCD walks its own (b,h) pairs ONE AFTER THE OTHER, so
+// the memory-zone K/V of a (b,h), re-read by every later chunk, stays in that L2 (about 1 MB
+// per (b,h) at the long-context shape, against 4 MB of L2).  Inside a (b,h): chunk-major from
+// the last chunk to the first (reading blocks of late chunks see the most keys: longest
+// first), and within a chunk reading blocks, memory blocks, repetition blocks side by side,
+// so the MFMA-heavy reading blocks and the HBM-heavy repetition blocks share the CUs.
 struct MaskSchedule {
     int nbh, n, t, R, s, bm;
     int nRB, nMB;        // row blocks per reading (= repetition) zone, per memory zone
-    int jobs_per_bh;
+    int jobs_per_chunk, jobs_per_bh;
 
     __host__ __device__ static MaskSchedule make(int nbh, int t, int c, int n, int bm) {
         MaskSchedule m;
         m.nbh = nbh; m.n = n; m.t = t; m.R = t * c; m.s = t * (2 * c + 1); m.bm = bm;
         m.nRB = (m.R + bm - 1) / bm;
         m.nMB = (t + bm - 1) / bm;
-        m.jobs_per_bh = n * (2 * m.nRB + m.nMB);
+        m.jobs_per_chunk = 2 * m.nRB + m.nMB;
+        m.jobs_per_bh = n * m.jobs_per_chunk;
         return m;
     }
     __host__ __device__ long long size() const { return (long long)nbh * jobs_per_bh; }
 
     __host__ __device__ MaskJob decode(long long id) const {
         MaskJob j;
-        j.bh = (int)(id % nbh);
-        int w = (int)(id / nbh);
-        const int nread = n * nRB, nmem = n * nMB;
-        if (w < nread) {
+        int w;
+        if (nbh % 8 == 0) {
+            const int xcd = (int)(id % 8);
+            const long long k = id / 8;
+            j.bh = xcd + 8 * (int)(k / jobs_per_bh);
+            w = (int)(k % jobs_per_bh);
+        } else {
+            j.bh = (int)(id % nbh);
+            w = (int)(id / nbh);
+        }
+        j.y = n - 1 - w / jobs_per_chunk;
+        int u = w % jobs_per_chunk;
+        if (u < nRB) {
             j.zone = ZONE_READ;
-            j.y = n - 1 - w / nRB;
-            j.o0 = (nRB - 1 - w % nRB) * bm;
+            j.o0 = (nRB - 1 - u) * bm;
             j.rows = (R - j.o0 < bm) ? R - j.o0 : bm;
             j.nkeys = j.y * t + j.o0 + j.rows;
-        } else if (w < nread + nmem) {
-            w -= nread;
+        } else if (u < nRB + nMB) {
+            u -= nRB;
             j.zone = ZONE_MEM;
-            j.y = w / nMB;
-            j.o0 = (w % nMB) * bm;
+            j.o0 = u * bm;
             j.rows = (t - j.o0 < bm) ? t - j.o0 : bm;
             j.nkeys = R + t;
         } else {
-            w -= nread + nmem;
+            u -= nRB + nMB;
             j.zone = ZONE_REP;
-            j.y = w / nRB;
-            j.o0 = (w % nRB) * bm;
+            j.o0 = u * bm;
             j.rows = (R - j.o0 < bm) ? R - j.o0 : bm;
             j.nkeys = t;  // + the row itself, handled outside the key walk
         }

@@ -141,7 +141,8 @@ def test_mask_schedule_covers_every_row_once(B, H, d, t, c, n):
     nbh = B * H
     seen = {}
     for blk, (bh, y, zone, o0, rows, keys) in enumerate(items):
-        assert bh == blk % nbh                      # (b,h) fastest: XCD affinity when nbh % 8 == 0
+        if nbh % 8 == 0:
+            assert bh % 8 == blk % 8                # a (b,h) stays on one XCD (workgroups go round-robin over 8)
         assert 0 <= bh < nbh and 0 <= y < n and zone in (0, 1, 2) and rows >= 1
         zlen = t if zone == 1 else R
         assert 0 <= o0 and o0 + rows <= zlen
@@ -156,11 +157,9 @@ def test_mask_schedule_covers_every_row_once(B, H, d, t, c, n):
             assert key not in seen
             seen[key] = blk
     assert len(seen) == nbh * n * (2 * R + t)
-    # longest first: reading blocks run from the last chunk (most earlier memory zones) to the first
-    chunks = [y for (bh, y, z, o0, rows, k) in items if bh == 0 and z == 0]
+    # longest first: a (b,h) runs from its last chunk (most earlier memory zones) to its first
+    chunks = [y for (bh, y, z, o0, rows, k) in items if bh == 0]
     assert chunks == sorted(chunks, reverse=True)
-    first_other = min(i for i, it in enumerate(items) if it[2] != 0)
-    assert all(it[2] == 0 for it in items[:first_other]) and all(it[2] != 0 for it in items[first_other:])
 
 
 def test_schedule_size_zero_for_shapes_on_the_generic_path(lib):
