@@ -48,6 +48,7 @@ struct FlashJob {
     unsigned slab_magic;  // floor(2^32 / slab) + 1: j / slab == umulhi(j, magic) while j * slab < 2^32
     long slab_stride;  // elements between slabs
     int causal_base;   // key j is visible to block row r iff j <= causal_base + r
+    int rows_grouped;  // every range boundary and the slab length are multiples of the rows one direct load covers
     const bf16_t *k_self, *v_self;  // rows aligned with q (repetition zone) or nullptr
 };
 
@@ -95,10 +96,11 @@ __device__ __forceinline__ float pair_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// Global row of key j of the job's key list.  Branch-free (selects only) so that the loads
-// that follow stay in one basic block and can be left in flight across the tile's math.
+// Global row of key j of the job's key list, written with selects only.  (Takes the job by
+// value: selecting between fields of a struct that lives behind a reference would turn into an
+// indexed load and pin the whole job description in scratch memory.)
 template <int D>
-__device__ __forceinline__ void key_row(const FlashJob& J, int j, const bf16_t*& kp, const bf16_t*& vp) {
+__device__ __forceinline__ void key_row(const FlashJob J, int j, const bf16_t*& kp, const bf16_t*& vp) {
     const unsigned a = J.slab == 1 ? (unsigned)j : __umulhi((unsigned)j, J.slab_magic);
     const long off0 = (long)a * J.slab_stride + (long)(j - (int)a * J.slab) * D;
     const int j1 = j - J.n0, j2 = j1 - J.n1;
@@ -106,6 +108,15 @@ __device__ __forceinline__ void key_row(const FlashJob& J, int j, const bf16_t*&
     const long off = in0 ? off0 : (long)(in1 ? j1 : j2) * D;
     kp = (in0 ? J.k0 : (in1 ? J.k1 : J.k2)) + off;
     vp = (in0 ? J.v0 : (in1 ? J.v1 : J.v2)) + off;
+}
+
+// One wave-wide direct load: lane l's 16 bytes at `src` land at LDS byte 16*l past `lds_dst`
+// (wave-uniform).  Written as inline assembly so that the compiler does not order later LDS
+// reads of the OTHER tile buffer behind it; the waits are placed by hand (wait_direct_loads).
+__device__ __forceinline__ void direct_load_16B(const bf16_t* src, bf16_t* lds_dst) {
+    const unsigned dst = __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)(__attribute__((address_space(3))) bf16_t*)lds_dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory", "m0");
 }
 
 // Direct HBM -> LDS copy of one K and one V tile.  A wave-wide load moves 64 x 16 B into 1 KB of
@@ -126,10 +137,44 @@ __device__ __forceinline__ void load_tile_async(const FlashJob& J, int k0, int n
         key_row<D>(J, min(k0 + r, nkeys - 1), kp, vp);
         const int ck = p ^ (r % C::CPR);
         const int cv = p ^ ((4 * (r % 4)) % C::CPR);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kp + ck * 8),
-                                         (__attribute__((address_space(3))) void*)(Kb + rbase * D), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vp + cv * 8),
-                                         (__attribute__((address_space(3))) void*)(Vb + rbase * D), 16, 0, 0);
+        direct_load_16B(kp + ck * 8, Kb + rbase * D);
+        direct_load_16B(vp + cv * 8, Vb + rbase * D);
+    }
+}
+
+// a pointer every lane agrees on, moved to scalar registers
+__device__ __forceinline__ const bf16_t* uniform_ptr(const bf16_t* p) {
+    const uint64_t x = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+    return reinterpret_cast<const bf16_t*>(((uint64_t)hi << 32) | lo);
+}
+
+// Same copy when the row addresses of a wave-wide load are wave-uniform and advance by a fixed
+// stride from tile to tile: the pointers live in scalar registers and cost two scalar adds per
+// load and tile; every lane adds a loop-invariant offset.  No vector instruction is spent on
+// addresses.  (Possible when the range boundaries and the slab length are multiples of RPI --
+// the RPI rows of one load are then consecutive rows of one range -- and a tile covers whole slabs.)
+template <int D, int NW, int BN>
+__device__ __forceinline__ void load_tile_async_stream(const bf16_t* (&kptr)[Cfg<D, NW, BN>::IPW],
+                                                       const bf16_t* (&vptr)[Cfg<D, NW, BN>::IPW],
+                                                       long tile_stride, int w,
+                                                       const unsigned (&goffk)[Cfg<D, NW, BN>::IPW],
+                                                       unsigned goffv, bf16_t* Kb, bf16_t* Vb) {
+    using C = Cfg<D, NW, BN>;
+#pragma unroll
+    for (int i = 0; i < C::IPW; ++i) {
+        const int rbase = (w * C::IPW + i) * C::RPI;   // wave-uniform
+        const unsigned kdst = __builtin_amdgcn_readfirstlane(
+            (unsigned)(size_t)(__attribute__((address_space(3))) bf16_t*)(Kb + rbase * D));
+        const unsigned vdst = __builtin_amdgcn_readfirstlane(
+            (unsigned)(size_t)(__attribute__((address_space(3))) bf16_t*)(Vb + rbase * D));
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kdst), "v"(goffk[i]), "s"(kptr[i])
+                     : "memory", "m0");
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(vdst), "v"(goffv), "s"(vptr[i])
+                     : "memory", "m0");
+        kptr[i] += tile_stride;
+        vptr[i] += tile_stride;
     }
 }
 
@@ -154,30 +199,42 @@ __device__ __forceinline__ void score_phase(const bf16_t* Kb, const int (&koff)[
                                             f32x16 (&S)[Cfg<D, NW, BN>::NSUB],
                                             int k0, int nsub, int my_lim, int lane) {
     using C = Cfg<D, NW, BN>;
-    const int g = lane >> 5, l32 = lane & 31;
+    const int g = lane >> 5;
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if constexpr (!FULL) {
 #pragma unroll
-    for (int sub = 0; sub < C::NSUB; ++sub)
+        for (int sub = 0; sub < C::NSUB; ++sub)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) S[sub][i] = 0.f;
+            for (int i = 0; i < 16; ++i) S[sub][i] = 0.f;
+    }
 
     // ---- S^T = K Q^T -------------------------------------------------------------------------
     if constexpr (FULL) {
-        constexpr int AHEAD = 4;   // K operands in flight: AHEAD k-steps of every sub-tile
+        // K operands are read AHEAD k-steps before the MFMA that uses them; the scheduling
+        // barriers keep the compiler from sinking the reads back next to their uses.
+        constexpr int AHEAD = (C::KSTEPS >= 4) ? 4 : C::KSTEPS;
         bf16x8 ka[C::NSUB][AHEAD];
 #pragma unroll
         for (int ks = 0; ks < AHEAD; ++ks)
 #pragma unroll
             for (int sub = 0; sub < C::NSUB; ++sub)
                 ka[sub][ks] = *reinterpret_cast<const bf16x8*>(Kb + koff[ks] + 32 * sub * D);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < C::KSTEPS; ++ks) {
 #pragma unroll
-            for (int sub = 0; sub < C::NSUB; ++sub) {
-                S[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][ks % AHEAD], qreg[ks], S[sub], 0, 0, 0);
-                if (ks + AHEAD < C::KSTEPS)
+            for (int sub = 0; sub < C::NSUB; ++sub)
+                if (ks == 0)
+                    S[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][0], qreg[0], zero16, 0, 0, 0);
+                else
+                    S[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][ks % AHEAD], qreg[ks], S[sub], 0, 0, 0);
+            if (ks + AHEAD < C::KSTEPS) {
+#pragma unroll
+                for (int sub = 0; sub < C::NSUB; ++sub)
                     ka[sub][ks % AHEAD] = *reinterpret_cast<const bf16x8*>(
                         Kb + koff[(ks + AHEAD) % C::KSTEPS] + 32 * sub * D);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
     } else {
 #pragma unroll
@@ -262,6 +319,7 @@ __device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&v
         bf16x8 va[2][C::DT];
 #pragma unroll
         for (int dt = 0; dt < C::DT; ++dt) va[0][dt] = read_v(0, dt);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int step = 0; step < NSTEP; ++step) {
             if (step + 1 < NSTEP) {
@@ -272,6 +330,7 @@ __device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&v
 #pragma unroll
             for (int dt = 0; dt < C::DT; ++dt)
                 O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[step & 1][dt], pb, O[dt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     } else {
 #pragma unroll
@@ -336,6 +395,16 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
                        4 * (i & 1);
     }
 
+    // per-lane byte offsets of the grouped direct loads (row inside the group, permuted piece)
+    unsigned goffk[C::IPW], goffv;
+    {
+        const int rl = lane / C::CPR, pc = lane % C::CPR;
+#pragma unroll
+        for (int i = 0; i < C::IPW; ++i)
+            goffk[i] = 2u * (rl * D + ((pc ^ (((w * C::IPW + i) * C::RPI + rl) % C::CPR)) * 8));
+        goffv = 2u * (rl * D + ((pc ^ ((4 * (rl % 4)) % C::CPR)) * 8));
+    }
+
     if (ntiles > 0) load_tile_async<D, NW, BN>(J, 0, nkeys, w, lane, Ks, Vt);
     wait_direct_loads();
     __syncthreads();
@@ -344,9 +413,32 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     // straight-line code, no per-wave decisions (this is where the time goes).  Blocks with
     // unused waves take the general loop for all their tiles.
     const int nfull = (J.q_rows == C::BM) ? min(ntiles, (min(J.causal_base, nkeys - 1) + 1) / BN) : 0;
+    // Leading tiles whose loads can stream with scalar pointers: whole slabs of range 0 per tile,
+    // or a contiguous range 1 when there is no range 0.
+    int nstream = 0;
+    long tile_stride = 0;
+    if (J.rows_grouped) {
+        if (J.n0 > 0) {
+            if (BN % J.slab == 0) { nstream = min(nfull, J.n0 / BN); tile_stride = (long)(BN / J.slab) * J.slab_stride; }
+        } else {
+            nstream = min(nfull, J.n1 / BN);
+            tile_stride = (long)BN * D;
+        }
+    }
+    const bf16_t *kptr[C::IPW], *vptr[C::IPW];
+#pragma unroll
+    for (int i = 0; i < C::IPW; ++i) {
+        const bf16_t *kp, *vp;
+        key_row<D>(J, min((w * C::IPW + i) * C::RPI, nkeys - 1), kp, vp);
+        kptr[i] = uniform_ptr(kp) + tile_stride;   // first streamed tile is tile 1
+        vptr[i] = uniform_ptr(vp) + tile_stride;
+    }
     for (int kt = 0; kt < nfull; ++kt) {
         const int buf = kt & 1;
-        if (kt + 1 < ntiles)
+        if (kt + 1 < nstream)
+            load_tile_async_stream<D, NW, BN>(kptr, vptr, tile_stride, w, goffk, goffv, Ks + (buf ^ 1) * C::KBUF,
+                                              Vt + (buf ^ 1) * C::VBUF);
+        else if (kt + 1 < ntiles)
             load_tile_async<D, NW, BN>(J, (kt + 1) * BN, nkeys, w, lane, Ks + (buf ^ 1) * C::KBUF,
                                        Vt + (buf ^ 1) * C::VBUF);
         f32x16 S[C::NSUB];
@@ -465,6 +557,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
     J.slab = 1; J.slab_magic = 0; J.slab_stride = 0;
     J.causal_base = NO_CAUSAL;
     J.k_self = J.v_self = nullptr;
+    J.rows_grouped = (sch.t % (64 / (D / 8))) == 0;
     J.q_rows = mj.rows;
     long qrow;
     if (mj.zone == ZONE_READ) {
@@ -512,6 +605,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
     J.k2 = P.k_mem + (long)bh * P.t * D;  J.v2 = P.v_mem + (long)bh * P.t * D;  J.n2 = P.t;
     J.causal_base = NO_CAUSAL;
     J.k_self = J.v_self = nullptr;
+    J.rows_grouped = (P.t % (64 / (D / 8))) == 0;
     J.q_rows = min(BM, P.t - o0);
     J.q = P.q_mem + ((long)bh * P.t + o0) * D;
     J.out = P.out + ((long)bh * P.t + o0) * D;
