@@ -52,10 +52,11 @@ struct FlashJob {
     const bf16_t *k_self, *v_self;  // rows aligned with q (repetition zone) or nullptr
 };
 
-template <int D, int NW, int BN>
+template <int D, int NW, int BN, int QT>
 struct Cfg {
     static constexpr int NT = 64 * NW;
-    static constexpr int BM = 32 * NW;
+    static constexpr int WROWS = 32 * QT;   // query rows per wave: QT tiles of 32
+    static constexpr int BM = WROWS * NW;
     static constexpr int CPR = D / 8;        // 16-byte pieces per row
     // Tiles are dense [BN][D] in LDS (the direct loads write 1 KB runs); instead of padding, the
     // 16-byte piece c of tile row r is stored at piece position c ^ swizzle(r):
@@ -124,10 +125,10 @@ __device__ __forceinline__ void direct_load_16B(const bf16_t* src, bf16_t* lds_d
 // belongs at its LDS position under the row's XOR permutation.  Keys past the end of the list
 // are clamped to the last key: their scores are masked and their probabilities are exactly 0,
 // so any finite row will do and no lane ever branches.
-template <int D, int NW, int BN>
+template <int D, int NW, int BN, int QT>
 __device__ __forceinline__ void load_tile_async(const FlashJob& J, int k0, int nkeys, int w, int lane,
                                                 bf16_t* Kb, bf16_t* Vb) {
-    using C = Cfg<D, NW, BN>;
+    using C = Cfg<D, NW, BN, QT>;
     const int p = lane % C::CPR;
 #pragma unroll
     for (int i = 0; i < C::IPW; ++i) {
@@ -155,13 +156,13 @@ __device__ __forceinline__ const bf16_t* uniform_ptr(const bf16_t* p) {
 // load and tile; every lane adds a loop-invariant offset.  No vector instruction is spent on
 // addresses.  (Possible when the range boundaries and the slab length are multiples of RPI --
 // the RPI rows of one load are then consecutive rows of one range -- and a tile covers whole slabs.)
-template <int D, int NW, int BN>
-__device__ __forceinline__ void load_tile_async_stream(const bf16_t* (&kptr)[Cfg<D, NW, BN>::IPW],
-                                                       const bf16_t* (&vptr)[Cfg<D, NW, BN>::IPW],
+template <int D, int NW, int BN, int QT>
+__device__ __forceinline__ void load_tile_async_stream(const bf16_t* (&kptr)[Cfg<D, NW, BN, QT>::IPW],
+                                                       const bf16_t* (&vptr)[Cfg<D, NW, BN, QT>::IPW],
                                                        long tile_stride, int w,
-                                                       const unsigned (&goffk)[Cfg<D, NW, BN>::IPW],
+                                                       const unsigned (&goffk)[Cfg<D, NW, BN, QT>::IPW],
                                                        unsigned goffv, bf16_t* Kb, bf16_t* Vb) {
-    using C = Cfg<D, NW, BN>;
+    using C = Cfg<D, NW, BN, QT>;
 #pragma unroll
     for (int i = 0; i < C::IPW; ++i) {
         const int rbase = (w * C::IPW + i) * C::RPI;   // wave-uniform
@@ -193,24 +194,26 @@ __device__ __forceinline__ s16x4 lds_read_tr(const bf16_t* p) {
 // One key tile for one wave: scores, online softmax, PV.  FULL = every key of the tile is visible
 // to every row of the wave (no mask, no sub-tile skipping): the hot path, written as straight-line
 // code with the LDS operand reads issued well ahead of the MFMAs that consume them.
-template <int D, int NW, int BN, bool FULL>
-__device__ __forceinline__ void score_phase(const bf16_t* Kb, const int (&koff)[Cfg<D, NW, BN>::KSTEPS],
-                                            const bf16x8 (&qreg)[Cfg<D, NW, BN>::KSTEPS],
-                                            f32x16 (&S)[Cfg<D, NW, BN>::NSUB],
-                                            int k0, int nsub, int my_lim, int lane) {
-    using C = Cfg<D, NW, BN>;
+template <int D, int NW, int BN, int QT, bool FULL>
+__device__ __forceinline__ void score_phase(const bf16_t* Kb, const int (&koff)[Cfg<D, NW, BN, QT>::KSTEPS],
+                                            const bf16x8 (&qreg)[QT][Cfg<D, NW, BN, QT>::KSTEPS],
+                                            f32x16 (&S)[QT][Cfg<D, NW, BN, QT>::NSUB],
+                                            int k0, int nsub, const int (&my_lim)[QT], int lane) {
+    using C = Cfg<D, NW, BN, QT>;
     const int g = lane >> 5;
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if constexpr (!FULL) {
 #pragma unroll
-        for (int sub = 0; sub < C::NSUB; ++sub)
+        for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) S[sub][i] = 0.f;
+            for (int sub = 0; sub < C::NSUB; ++sub)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) S[qt][sub][i] = 0.f;
     }
 
-    // ---- S^T = K Q^T -------------------------------------------------------------------------
+    // ---- S^T = K Q^T: one K operand read from LDS feeds the MFMAs of all QT query tiles ----------
     if constexpr (FULL) {
-        // K operands are read AHEAD k-steps before the MFMA that uses them; the scheduling
+        // K operands are read AHEAD k-steps before the MFMAs that use them; the scheduling
         // barriers keep the compiler from sinking the reads back next to their uses.
         constexpr int AHEAD = (C::KSTEPS >= 4) ? 4 : C::KSTEPS;
         bf16x8 ka[C::NSUB][AHEAD];
@@ -224,10 +227,14 @@ __device__ __forceinline__ void score_phase(const bf16_t* Kb, const int (&koff)[
         for (int ks = 0; ks < C::KSTEPS; ++ks) {
 #pragma unroll
             for (int sub = 0; sub < C::NSUB; ++sub)
-                if (ks == 0)
-                    S[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][0], qreg[0], zero16, 0, 0, 0);
-                else
-                    S[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][ks % AHEAD], qreg[ks], S[sub], 0, 0, 0);
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) {
+                    if (ks == 0)
+                        S[qt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][0], qreg[qt][0], zero16, 0, 0, 0);
+                    else
+                        S[qt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][ks % AHEAD], qreg[qt][ks],
+                                                                             S[qt][sub], 0, 0, 0);
+                }
             if (ks + AHEAD < C::KSTEPS) {
 #pragma unroll
                 for (int sub = 0; sub < C::NSUB; ++sub)
@@ -243,61 +250,66 @@ __device__ __forceinline__ void score_phase(const bf16_t* Kb, const int (&koff)[
 #pragma unroll
                 for (int ks = 0; ks < C::KSTEPS; ++ks) {
                     const bf16x8 a = *reinterpret_cast<const bf16x8*>(Kb + koff[ks] + 32 * sub * D);
-                    S[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], S[sub], 0, 0, 0);
+#pragma unroll
+                    for (int qt = 0; qt < QT; ++qt)
+                        S[qt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qt][ks], S[qt][sub], 0, 0, 0);
                 }
             }
         // accumulator i of lane (l32, g) is key 8*(i/4) + 4*g + i%4 of the sub-tile
 #pragma unroll
-        for (int sub = 0; sub < C::NSUB; ++sub)
+        for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int j = k0 + 32 * sub + 8 * (i >> 2) + 4 * g + (i & 3);
-                if (j > my_lim) S[sub][i] = -INFINITY;
-            }
+            for (int sub = 0; sub < C::NSUB; ++sub)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int j = k0 + 32 * sub + 8 * (i >> 2) + 4 * g + (i & 3);
+                    if (j > my_lim[qt]) S[qt][sub][i] = -INFINITY;
+                }
     }
 }
 
-template <int D, int NW, int BN, bool FULL>
-__device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&voff)[Cfg<D, NW, BN>::DT],
-                                                 f32x16 (&S)[Cfg<D, NW, BN>::NSUB],
-                                                 f32x16 (&O)[Cfg<D, NW, BN>::DT], float& m, float& lsum,
-                                                 float sc, int nsub, int lane) {
-    using C = Cfg<D, NW, BN>;
+template <int D, int NW, int BN, int QT, bool FULL>
+__device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&voff)[Cfg<D, NW, BN, QT>::DT],
+                                                 f32x16 (&S)[QT][Cfg<D, NW, BN, QT>::NSUB],
+                                                 f32x16 (&O)[QT][Cfg<D, NW, BN, QT>::DT], float (&m)[QT],
+                                                 float (&lsum)[QT], float sc, int nsub, int lane) {
+    using C = Cfg<D, NW, BN, QT>;
     // ---- online softmax (per query: lanes l and l^32) ---------------------------------------------
-    float mx = m;
 #pragma unroll
-    for (int sub = 0; sub < C::NSUB; ++sub)
-        if (FULL || sub < nsub) {
+    for (int qt = 0; qt < QT; ++qt) {
+        float mx = m[qt];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[sub][i]);
-        }
-    mx = pair_max(mx);
-    // rescale by exp2((m_old - m_new) * sc): exactly 1 for the rows whose maximum did not move.
-    // (Unconditional on purpose: a branch around it makes the compiler keep two copies of O.)
-    {
-        const float alpha = __builtin_amdgcn_exp2f((m - mx) * sc);
-        lsum *= alpha;
+        for (int sub = 0; sub < C::NSUB; ++sub)
+            if (FULL || sub < nsub) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[qt][sub][i]);
+            }
+        mx = pair_max(mx);
+        // rescale by exp2((m_old - m_new) * sc): exactly 1 for the rows whose maximum did not move.
+        // (Unconditional on purpose: a branch around it makes the compiler keep two copies of O.)
+        const float alpha = __builtin_amdgcn_exp2f((m[qt] - mx) * sc);
+        lsum[qt] *= alpha;
 #pragma unroll
         for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) O[dt][i] *= alpha;
-        m = mx;
-    }
-    const float mc = m * sc;
-    float ps = 0.f;
+            for (int i = 0; i < 16; ++i) O[qt][dt][i] *= alpha;
+        m[qt] = mx;
+        const float mc = mx * sc;
+        float ps = 0.f;
 #pragma unroll
-    for (int sub = 0; sub < C::NSUB; ++sub)
-        if (FULL || sub < nsub) {
+        for (int sub = 0; sub < C::NSUB; ++sub)
+            if (FULL || sub < nsub) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float p = __builtin_amdgcn_exp2f(S[sub][i] * sc - mc);
-                ps += p;
-                S[sub][i] = p;
+                for (int i = 0; i < 16; ++i) {
+                    const float p = __builtin_amdgcn_exp2f(S[qt][sub][i] * sc - mc);
+                    ps += p;
+                    S[qt][sub][i] = p;
+                }
             }
-        }
-    lsum += ps;
+        lsum[qt] += ps;
+    }
 
-    // ---- O^T += V^T P^T ------------------------------------------------------------------------------
+    // ---- O^T += V^T P^T: one V^T operand read feeds the MFMAs of all QT query tiles --------------------
     // V^T operand: lane (d = 32*dt + l32, half g) needs keys 16*step + 8*a + 4*g + 0..3, a = 0,1
     auto read_v = [&](int step, int dt) -> bf16x8 {
         const bf16_t* vp = Vb + voff[dt] + 16 * step * D;
@@ -305,13 +317,13 @@ __device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&v
         const s16x4 hi = lds_read_tr(vp + 8 * D);
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    auto pack_p = [&](int step) -> bf16x8 {
+    auto pack_p = [&](int qt, int step) -> bf16x8 {
         const int sub = step >> 1, jj = step & 1;
         uint4 pw;
-        pw.x = pack_bf16(S[sub][8 * jj + 0], S[sub][8 * jj + 1]);
-        pw.y = pack_bf16(S[sub][8 * jj + 2], S[sub][8 * jj + 3]);
-        pw.z = pack_bf16(S[sub][8 * jj + 4], S[sub][8 * jj + 5]);
-        pw.w = pack_bf16(S[sub][8 * jj + 6], S[sub][8 * jj + 7]);
+        pw.x = pack_bf16(S[qt][sub][8 * jj + 0], S[qt][sub][8 * jj + 1]);
+        pw.y = pack_bf16(S[qt][sub][8 * jj + 2], S[qt][sub][8 * jj + 3]);
+        pw.z = pack_bf16(S[qt][sub][8 * jj + 4], S[qt][sub][8 * jj + 5]);
+        pw.w = pack_bf16(S[qt][sub][8 * jj + 6], S[qt][sub][8 * jj + 7]);
         return __builtin_bit_cast(bf16x8, pw);
     };
     constexpr int NSTEP = 2 * C::NSUB;
@@ -326,27 +338,135 @@ __device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&v
 #pragma unroll
                 for (int dt = 0; dt < C::DT; ++dt) va[(step + 1) & 1][dt] = read_v(step + 1, dt);
             }
-            const bf16x8 pb = pack_p(step);
+            bf16x8 pb[QT];
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) pb[qt] = pack_p(qt, step);
 #pragma unroll
             for (int dt = 0; dt < C::DT; ++dt)
-                O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[step & 1][dt], pb, O[dt], 0, 0, 0);
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt)
+                    O[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[step & 1][dt], pb[qt], O[qt][dt], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     } else {
 #pragma unroll
         for (int step = 0; step < NSTEP; ++step)
             if ((step >> 1) < nsub) {
-                const bf16x8 pb = pack_p(step);
+                bf16x8 pb[QT];
 #pragma unroll
-                for (int dt = 0; dt < C::DT; ++dt)
-                    O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v(step, dt), pb, O[dt], 0, 0, 0);
+                for (int qt = 0; qt < QT; ++qt) pb[qt] = pack_p(qt, step);
+#pragma unroll
+                for (int dt = 0; dt < C::DT; ++dt) {
+                    const bf16x8 a = read_v(step, dt);
+#pragma unroll
+                    for (int qt = 0; qt < QT; ++qt)
+                        O[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt], O[qt][dt], 0, 0, 0);
+                }
             }
     }
 }
 
-template <int D, int NW, int BN>
+// The query row's own K and V rows, in the register layouts of the Q operand (K) and of the O
+// accumulators (V): lane (row l32, half g) holds head-dim 16*ks + 8*g.. of K and 32*dt + 8*i4 + 4*g.. of V.
+template <int D, int NW, int BN, int QT>
+__device__ __forceinline__ void load_self_rows(const FlashJob& J, int r, int g,
+                                               bf16x8 (&kself)[Cfg<D, NW, BN, QT>::KSTEPS],
+                                               uint2 (&vself)[Cfg<D, NW, BN, QT>::DT][4]) {
+    using C = Cfg<D, NW, BN, QT>;
+    const int rc = min(r, J.q_rows - 1);   // lanes past the block replay its last row (never stored)
+    const bf16_t* kp = J.k_self + (long)rc * D + 8 * g;
+    const bf16_t* vp = J.v_self + (long)rc * D + 4 * g;
+#pragma unroll
+    for (int ks = 0; ks < C::KSTEPS; ++ks)
+        kself[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kp + 16 * ks));
+#pragma unroll
+    for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) vself[dt][i4] = *reinterpret_cast<const uint2*>(vp + 32 * dt + 8 * i4);
+}
+
+// One more key for every query, its own (identity block of Eq. 1, second term of Eq. 9): a dot
+// product and an axpy per row on the vector ALU -- a diagonal is no MFMA tile.
+template <int D, int NW, int BN, int QT>
+__device__ __forceinline__ void self_term(const bf16x8 (&qreg)[Cfg<D, NW, BN, QT>::KSTEPS],
+                                          const bf16x8 (&kself)[Cfg<D, NW, BN, QT>::KSTEPS],
+                                          const uint2 (&vself)[Cfg<D, NW, BN, QT>::DT][4],
+                                          f32x16 (&O)[Cfg<D, NW, BN, QT>::DT], float& m, float& lsum, float sc, int g) {
+    using C = Cfg<D, NW, BN, QT>;
+    float part = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < C::KSTEPS; ++ks) {
+        const bf16x8 kk = kself[ks], qq = qreg[ks];
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const bf16x2 a = {qq[e], qq[e + 1]};
+            const bf16x2 b = {kk[e], kk[e + 1]};
+            part = __builtin_amdgcn_fdot2_f32_bf16(a, b, part, false);
+        }
+    }
+    const float sself = pair_sum(part);
+    const float mx = fmaxf(m, sself);
+    const float alpha = __builtin_amdgcn_exp2f((m - mx) * sc);
+    const float p = __builtin_amdgcn_exp2f((sself - mx) * sc);
+    lsum = lsum * alpha + (g == 0 ? p : 0.f);
+    m = mx;
+#pragma unroll
+    for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            const uint2 x = vself[dt][i4];
+            O[dt][4 * i4 + 0] = O[dt][4 * i4 + 0] * alpha + p * bf16_lo(x.x);
+            O[dt][4 * i4 + 1] = O[dt][4 * i4 + 1] * alpha + p * bf16_hi(x.x);
+            O[dt][4 * i4 + 2] = O[dt][4 * i4 + 2] * alpha + p * bf16_lo(x.y);
+            O[dt][4 * i4 + 3] = O[dt][4 * i4 + 3] * alpha + p * bf16_hi(x.y);
+        }
+}
+
+// Normalise, transpose through LDS (the tile buffers are free by now), store rows as 16-byte
+// pieces; one query tile at a time through the wave's own 32-row staging area.
+template <int D, int NW, int BN, int QT>
+__device__ __forceinline__ void store_rows(const FlashJob& J, f32x16 (&O)[QT][Cfg<D, NW, BN, QT>::DT],
+                                           const float (&m)[QT], const float (&lsum)[QT], float sc, bf16_t* smem,
+                                           int w, int lane, int row0, bool has_rows) {
+    using C = Cfg<D, NW, BN, QT>;
+    const int g = lane >> 5, l32 = lane & 31;
+    bf16_t* Os = smem + w * 32 * C::OSTR;
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const int rbase = row0 + 32 * qt;
+        const float ltot = pair_sum(lsum[qt]);
+        const float inv = 1.f / ltot;
+        if (has_rows) {
+#pragma unroll
+            for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    uint2 x;
+                    x.x = pack_bf16(O[qt][dt][4 * i4 + 0] * inv, O[qt][dt][4 * i4 + 1] * inv);
+                    x.y = pack_bf16(O[qt][dt][4 * i4 + 2] * inv, O[qt][dt][4 * i4 + 3] * inv);
+                    *reinterpret_cast<uint2*>(Os + l32 * C::OSTR + 32 * dt + 8 * i4 + 4 * g) = x;
+                }
+            if (J.lse != nullptr && g == 0 && rbase + l32 < J.q_rows)
+                J.lse[rbase + l32] = (m[qt] * sc + __builtin_amdgcn_logf(ltot)) * LN2;
+        }
+        __syncthreads();
+        if (has_rows) {
+#pragma unroll
+            for (int it = 0; it < 32 * C::CPR / 64; ++it) {
+                const int idx = it * 64 + lane;
+                const int r = idx / C::CPR, ch = idx % C::CPR;
+                if (rbase + r < J.q_rows)
+                    *reinterpret_cast<uint4*>(J.out + (long)(rbase + r) * D + ch * 8) =
+                        *reinterpret_cast<const uint4*>(Os + r * C::OSTR + ch * 8);
+            }
+        }
+        if (qt + 1 < QT) __syncthreads();
+    }
+}
+
+template <int D, int NW, int BN, int QT>
 __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* smem) {
-    using C = Cfg<D, NW, BN>;
+    using C = Cfg<D, NW, BN, QT>;
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, kept in a scalar register
     const int g = lane >> 5, l32 = lane & 31;
@@ -356,32 +476,37 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     const int nkeys = J.n0 + J.n1 + J.n2;
     const int kend_wg = min(nkeys, J.causal_base + J.q_rows);
     const int ntiles = (kend_wg + BN - 1) / BN;
-    const int row0 = 32 * w;                       // first block row of this wave
+    const int row0 = C::WROWS * w;                        // first block row of this wave
     const bool has_rows = row0 < J.q_rows;
-    const int row_hi = min(row0 + 32, J.q_rows);   // exclusive
+    const int row_hi = min(row0 + C::WROWS, J.q_rows);    // exclusive
     const int kend_w = has_rows ? min(nkeys, J.causal_base + row_hi) : 0;
-    const int my_row = min(row0 + l32, J.q_rows - 1);          // padded lanes replay the last row
-    const int my_lim = min(J.causal_base + my_row, nkeys - 1);  // last key this lane's query sees
+    int my_lim[QT];                                       // last key each of this lane's queries sees
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt)                       // padded lanes replay the last row
+        my_lim[qt] = min(J.causal_base + min(row0 + 32 * qt + l32, J.q_rows - 1), nkeys - 1);
 
     // Q^T as the B operand: lane (query l32, half g) holds head-dim 16*ks + 8*g .. +7
-    bf16x8 qreg[C::KSTEPS];
-    {
-        const bool ok = row0 + l32 < J.q_rows;
-        const bf16_t* qp = J.q + (long)(row0 + l32) * D + 8 * g;
+    bf16x8 qreg[QT][C::KSTEPS];
 #pragma unroll
-        for (int ks = 0; ks < C::KSTEPS; ++ks) {
-            uint4 x = make_uint4(0, 0, 0, 0);
-            if (ok) x = *reinterpret_cast<const uint4*>(qp + 16 * ks);
-            qreg[ks] = __builtin_bit_cast(bf16x8, x);
-        }
+    for (int qt = 0; qt < QT; ++qt) {
+        const int r = min(row0 + 32 * qt + l32, J.q_rows - 1);   // lanes past the block replay its last row
+        const bf16_t* qp = J.q + (long)r * D + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < C::KSTEPS; ++ks)
+            qreg[qt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * ks));
     }
 
-    f32x16 O[C::DT];
+    f32x16 O[QT][C::DT];
+    float m[QT], lsum[QT];
 #pragma unroll
-    for (int dt = 0; dt < C::DT; ++dt)
+    for (int qt = 0; qt < QT; ++qt) {
+        m[qt] = -INFINITY;
+        lsum[qt] = 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) O[dt][i] = 0.f;
-    float m = -INFINITY, lsum = 0.f;
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[qt][dt][i] = 0.f;
+    }
 
     // per-lane LDS offsets (elements) of the operand reads, under the tiles' XOR permutations
     int koff[C::KSTEPS], voff[C::DT];
@@ -395,7 +520,7 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
                        4 * (i & 1);
     }
 
-    // per-lane byte offsets of the grouped direct loads (row inside the group, permuted piece)
+    // per-lane byte offsets of the streamed direct loads (row inside the group, permuted piece)
     unsigned goffk[C::IPW], goffv;
     {
         const int rl = lane / C::CPR, pc = lane % C::CPR;
@@ -405,14 +530,14 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
         goffv = 2u * (rl * D + ((pc ^ ((4 * (rl % 4)) % C::CPR)) * 8));
     }
 
-    if (ntiles > 0) load_tile_async<D, NW, BN>(J, 0, nkeys, w, lane, Ks, Vt);
+    if (ntiles > 0) load_tile_async<D, NW, BN, QT>(J, 0, nkeys, w, lane, Ks, Vt);
     wait_direct_loads();
     __syncthreads();
 
     // Tiles that every row of the block sees in full come first and run in a loop of their own:
-    // straight-line code, no per-wave decisions (this is where the time goes).  Blocks with
-    // unused waves take the general loop for all their tiles.
-    const int nfull = (J.q_rows == C::BM) ? min(ntiles, (min(J.causal_base, nkeys - 1) + 1) / BN) : 0;
+    // straight-line code, no per-wave decisions except that a wave without rows (a block shorter
+    // than BM) only helps with the loads.  This is where the time goes.
+    const int nfull = min(ntiles, (min(J.causal_base, nkeys - 1) + 1) / BN);
     // Leading tiles whose loads can stream with scalar pointers: whole slabs of range 0 per tile,
     // or a contiguous range 1 when there is no range 0.
     int nstream = 0;
@@ -436,14 +561,16 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     for (int kt = 0; kt < nfull; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < nstream)
-            load_tile_async_stream<D, NW, BN>(kptr, vptr, tile_stride, w, goffk, goffv, Ks + (buf ^ 1) * C::KBUF,
-                                              Vt + (buf ^ 1) * C::VBUF);
+            load_tile_async_stream<D, NW, BN, QT>(kptr, vptr, tile_stride, w, goffk, goffv, Ks + (buf ^ 1) * C::KBUF,
+                                                  Vt + (buf ^ 1) * C::VBUF);
         else if (kt + 1 < ntiles)
-            load_tile_async<D, NW, BN>(J, (kt + 1) * BN, nkeys, w, lane, Ks + (buf ^ 1) * C::KBUF,
-                                       Vt + (buf ^ 1) * C::VBUF);
-        f32x16 S[C::NSUB];
-        score_phase<D, NW, BN, true>(Ks + buf * C::KBUF, koff, qreg, S, kt * BN, C::NSUB, my_lim, lane);
-        softmax_pv_phase<D, NW, BN, true>(Vt + buf * C::VBUF, voff, S, O, m, lsum, sc, C::NSUB, lane);
+            load_tile_async<D, NW, BN, QT>(J, (kt + 1) * BN, nkeys, w, lane, Ks + (buf ^ 1) * C::KBUF,
+                                           Vt + (buf ^ 1) * C::VBUF);
+        if (has_rows) {
+            f32x16 S[QT][C::NSUB];
+            score_phase<D, NW, BN, QT, true>(Ks + buf * C::KBUF, koff, qreg, S, kt * BN, C::NSUB, my_lim, lane);
+            softmax_pv_phase<D, NW, BN, QT, true>(Vt + buf * C::VBUF, voff, S, O, m, lsum, sc, C::NSUB, lane);
+        }
         wait_direct_loads();
         __syncthreads();
     }
@@ -453,13 +580,13 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
         const int buf = kt & 1;
         const int k0 = kt * BN;
         if (kt + 1 < ntiles)
-            load_tile_async<D, NW, BN>(J, (kt + 1) * BN, nkeys, w, lane, Ks + (buf ^ 1) * C::KBUF,
-                                       Vt + (buf ^ 1) * C::VBUF);
+            load_tile_async<D, NW, BN, QT>(J, (kt + 1) * BN, nkeys, w, lane, Ks + (buf ^ 1) * C::KBUF,
+                                           Vt + (buf ^ 1) * C::VBUF);
         if (k0 < kend_w) {
             const int nsub = min(C::NSUB, (kend_w - k0 + 31) >> 5);
-            f32x16 S[C::NSUB];
-            score_phase<D, NW, BN, false>(Ks + buf * C::KBUF, koff, qreg, S, k0, nsub, my_lim, lane);
-            softmax_pv_phase<D, NW, BN, false>(Vt + buf * C::VBUF, voff, S, O, m, lsum, sc, nsub, lane);
+            f32x16 S[QT][C::NSUB];
+            score_phase<D, NW, BN, QT, false>(Ks + buf * C::KBUF, koff, qreg, S, k0, nsub, my_lim, lane);
+            softmax_pv_phase<D, NW, BN, QT, false>(Vt + buf * C::VBUF, voff, S, O, m, lsum, sc, nsub, lane);
         }
         wait_direct_loads();
         __syncthreads();
@@ -467,70 +594,76 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
 
     // the row's own key (identity block of Eq. 1, second term of Eq. 9), on the vector ALU
     if (J.k_self != nullptr && has_rows) {
-        const bool ok = row0 + l32 < J.q_rows;
-        const bf16_t* kp = J.k_self + (long)(row0 + l32) * D + 8 * g;
-        float part = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < C::KSTEPS; ++ks) {
-            uint4 x = make_uint4(0, 0, 0, 0);
-            if (ok) x = *reinterpret_cast<const uint4*>(kp + 16 * ks);
-            const bf16x8 kk = __builtin_bit_cast(bf16x8, x);
-            const bf16x8 qq = qreg[ks];
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                const bf16x2 a = {qq[e], qq[e + 1]};
-                const bf16x2 b = {kk[e], kk[e + 1]};
-                part = __builtin_amdgcn_fdot2_f32_bf16(a, b, part, false);
-            }
+        for (int qt = 0; qt < QT; ++qt) {
+            bf16x8 kself[C::KSTEPS];
+            uint2 vself[C::DT][4];
+            load_self_rows<D, NW, BN, QT>(J, row0 + 32 * qt + l32, g, kself, vself);
+            self_term<D, NW, BN, QT>(qreg[qt], kself, vself, O[qt], m[qt], lsum[qt], sc, g);
         }
-        const float sself = pair_sum(part);
-        const float mx = fmaxf(m, sself);
-        const float alpha = __builtin_amdgcn_exp2f((m - mx) * sc);
-        const float p = __builtin_amdgcn_exp2f((sself - mx) * sc);
-        lsum = lsum * alpha + (g == 0 ? p : 0.f);
-        m = mx;
-        const bf16_t* vp = J.v_self + (long)(row0 + l32) * D + 4 * g;
-#pragma unroll
-        for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                uint2 x = make_uint2(0, 0);
-                if (ok) x = *reinterpret_cast<const uint2*>(vp + 32 * dt + 8 * i4);
-                O[dt][4 * i4 + 0] = O[dt][4 * i4 + 0] * alpha + p * bf16_lo(x.x);
-                O[dt][4 * i4 + 1] = O[dt][4 * i4 + 1] * alpha + p * bf16_hi(x.x);
-                O[dt][4 * i4 + 2] = O[dt][4 * i4 + 2] * alpha + p * bf16_lo(x.y);
-                O[dt][4 * i4 + 3] = O[dt][4 * i4 + 3] * alpha + p * bf16_hi(x.y);
-            }
     }
+    store_rows<D, NW, BN, QT>(J, O, m, lsum, sc, smem, w, lane, row0, has_rows);
+}
 
-    // normalise, transpose through LDS (the K buffers are free now), store rows coalesced
-    const float ltot = pair_sum(lsum);
-    const float inv = 1.f / ltot;
-    bf16_t* Os = smem + w * 32 * C::OSTR;
-    if (has_rows) {
+// Repetition rows when the memory zone fits one tile: t memory keys plus the row's own key
+// (Eq. 1 row 3, Eq. 9).  Everything the block needs is requested up front -- Q and the rows' own K
+// and V into registers, the memory-zone tile by direct loads -- so the block pays ONE memory round
+// trip instead of one per step.  (Repetition rows are nearly half of all rows and almost pure
+// HBM traffic: q, k, v in, out written, a few dozen keys of math.)
+template <int D, int NW, int BN>
+__device__ __forceinline__ void rep_job(const FlashJob& J, float sc, bf16_t* smem) {
+    constexpr int QT = 1;
+    using C = Cfg<D, NW, BN, QT>;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 5, l32 = lane & 31;
+    bf16_t* Ks = smem;
+    bf16_t* Vt = smem + 2 * C::KBUF;
+    const int nkeys = J.n1;                     // <= BN
+    const int row0 = 32 * w;
+    const bool has_rows = row0 < J.q_rows;
+
+    load_tile_async<D, NW, BN, QT>(J, 0, nkeys, w, lane, Ks, Vt);
+    bf16x8 qreg[QT][C::KSTEPS], kself[C::KSTEPS];
+    uint2 vself[C::DT][4];
+    {
+        const int r = min(row0 + l32, J.q_rows - 1);
+        const bf16_t* qp = J.q + (long)r * D + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < C::KSTEPS; ++ks)
+            qreg[0][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * ks));
+        load_self_rows<D, NW, BN, QT>(J, r, g, kself, vself);
+    }
+    __builtin_amdgcn_sched_barrier(0);   // all requests are out before anything waits
+    int koff[C::KSTEPS], voff[C::DT];
+#pragma unroll
+    for (int ks = 0; ks < C::KSTEPS; ++ks) koff[ks] = l32 * D + (((2 * ks + g) ^ (l32 % C::CPR)) * 8);
+    {
+        const int i = lane & 15, q = i >> 2;
 #pragma unroll
         for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                uint2 x;
-                x.x = pack_bf16(O[dt][4 * i4 + 0] * inv, O[dt][4 * i4 + 1] * inv);
-                x.y = pack_bf16(O[dt][4 * i4 + 2] * inv, O[dt][4 * i4 + 3] * inv);
-                *reinterpret_cast<uint2*>(Os + l32 * C::OSTR + 32 * dt + 8 * i4 + 4 * g) = x;
-            }
-        if (J.lse != nullptr && g == 0 && row0 + l32 < J.q_rows)
-            J.lse[row0 + l32] = (m * sc + __builtin_amdgcn_logf(ltot)) * LN2;
+            voff[dt] = (4 * g + q) * D + (4 * (dt ^ (q % (C::CPR / 4))) + 2 * ((lane >> 4) & 1) + ((i & 3) >> 1)) * 8 +
+                       4 * (i & 1);
     }
+    f32x16 O[QT][C::DT];
+    float m[QT] = {-INFINITY}, lsum[QT] = {0.f};
+#pragma unroll
+    for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[0][dt][i] = 0.f;
+
+    wait_direct_loads();
     __syncthreads();
     if (has_rows) {
-#pragma unroll
-        for (int it = 0; it < 32 * C::CPR / 64; ++it) {
-            const int idx = it * 64 + lane;
-            const int r = idx / C::CPR, ch = idx % C::CPR;
-            if (row0 + r < J.q_rows)
-                *reinterpret_cast<uint4*>(J.out + (long)(row0 + r) * D + ch * 8) =
-                    *reinterpret_cast<const uint4*>(Os + r * C::OSTR + ch * 8);
-        }
+        const int my_lim[QT] = {nkeys - 1};
+        const int nsub = min(C::NSUB, (nkeys + 31) >> 5);
+        f32x16 S[QT][C::NSUB];
+        score_phase<D, NW, BN, QT, false>(Ks, koff, qreg, S, 0, nsub, my_lim, lane);
+        softmax_pv_phase<D, NW, BN, QT, false>(Vt, voff, S, O, m, lsum, sc, nsub, lane);
+        self_term<D, NW, BN, QT>(qreg[0], kself, vself, O[0], m[0], lsum[0], sc, g);
     }
+    __syncthreads();   // every wave is done with the tile before the staging area overwrites it
+    store_rows<D, NW, BN, QT>(J, O, m, lsum, sc, smem, w, lane, row0, has_rows);
 }
 
 // ---- mask pass -------------------------------------------------------------------------------
@@ -543,8 +676,9 @@ struct MaskParams {
     float sc;             // scale * log2(e)
 };
 
-template <int D, int NW, int BN>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void mask_attn_kernel(MaskParams P) {
+template <int D, int NW, int BN, int QT>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(QT == 1 ? 2 : 1))) void mask_attn_kernel(
+    MaskParams P) {
     extern __shared__ __align__(16) bf16_t smem[];
     const MaskSchedule& sch = P.sched;
     const MaskJob mj = sch.decode(blockIdx.x);
@@ -580,7 +714,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
     J.q = P.q + qrow * D;
     J.out = P.out + qrow * D;
     J.lse = P.lse ? P.lse + qrow : nullptr;
-    flash_job<D, NW, BN>(J, P.sc, smem);
+    if (QT == 1 && mj.zone == ZONE_REP && sch.t <= BN)
+        rep_job<D, NW, BN>(J, P.sc, smem);
+    else
+        flash_job<D, NW, BN, QT>(J, P.sc, smem);
 }
 
 // ---- compression pass ----------------------------------------------------------------------------
@@ -595,6 +732,7 @@ struct CompressParams {
 
 template <int D, int NW, int BN>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void compress_kernel(CompressParams P) {
+    constexpr int QT = 1;
     extern __shared__ __align__(16) bf16_t smem[];
     constexpr int BM = 32 * NW;
     const int bh = blockIdx.x / P.nblk, blk = blockIdx.x % P.nblk;
@@ -610,7 +748,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
     J.q = P.q_mem + ((long)bh * P.t + o0) * D;
     J.out = P.out + ((long)bh * P.t + o0) * D;
     J.lse = nullptr;
-    flash_job<D, NW, BN>(J, P.sc, smem);
+    flash_job<D, NW, BN, QT>(J, P.sc, smem);
     // splice: the t new memory KVs join the compressed cache (Sec. 3.1 step 3)
     if (blk == 0) {
         const int pieces = P.t * D / 8;
@@ -636,23 +774,23 @@ int launch(K kernel, long long grid, int threads, int smem_bytes, const P& param
 template <int D>
 int launch_mask_d(const MaskParams& P, int bm, hipStream_t st) {
     const long long grid = P.sched.size();
-    if (bm == 128) return launch(mask_attn_kernel<D, 4, 64>, grid, 256, Cfg<D, 4, 64>::SMEM_BYTES, P, st);
-    if (bm == 64) return launch(mask_attn_kernel<D, 2, 32>, grid, 128, Cfg<D, 2, 32>::SMEM_BYTES, P, st);
-    return launch(mask_attn_kernel<D, 1, 32>, grid, 64, Cfg<D, 1, 32>::SMEM_BYTES, P, st);
+    if (bm == 128) return launch(mask_attn_kernel<D, 4, 64, 1>, grid, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, P, st);
+    if (bm == 64) return launch(mask_attn_kernel<D, 2, 32, 1>, grid, 128, Cfg<D, 2, 32, 1>::SMEM_BYTES, P, st);
+    return launch(mask_attn_kernel<D, 1, 32, 1>, grid, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, P, st);
 }
 
 template <int D>
 int launch_compress_d(CompressParams& P, int nbh, hipStream_t st) {
     if (P.t > 64) {
         P.nblk = (P.t + 127) / 128;
-        return launch(compress_kernel<D, 4, 64>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64>::SMEM_BYTES, P, st);
+        return launch(compress_kernel<D, 4, 64>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, P, st);
     }
     if (P.t > 32) {
         P.nblk = 1;
-        return launch(compress_kernel<D, 2, 32>, nbh, 128, Cfg<D, 2, 32>::SMEM_BYTES, P, st);
+        return launch(compress_kernel<D, 2, 32>, nbh, 128, Cfg<D, 2, 32, 1>::SMEM_BYTES, P, st);
     }
     P.nblk = 1;
-    return launch(compress_kernel<D, 1, 32>, nbh, 64, Cfg<D, 1, 32>::SMEM_BYTES, P, st);
+    return launch(compress_kernel<D, 1, 32>, nbh, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, P, st);
 }
 
 }  // namespace
