@@ -65,7 +65,9 @@ struct Cfg {
     //                                   once) fall into 8 different 32-byte groups
     static constexpr int KBUF = BN * D;
     static constexpr int VBUF = BN * D;
-    static constexpr int SMEM_BYTES = 2 * (KBUF + VBUF) * 2;
+    // tile stages in flight: the loads run NS-1 tiles ahead of the math
+    static constexpr int NS = 2;
+    static constexpr int SMEM_BYTES = NS * (KBUF + VBUF) * 2;
     static constexpr int OSTR = D + 8;                   // row stride of the output staging area
     static constexpr int RPI = 64 / CPR;                 // tile rows one wave-wide direct load covers
     static constexpr int IPW = BN / RPI / NW;            // direct loads per wave, per tensor, per tile
@@ -74,7 +76,7 @@ struct Cfg {
     static constexpr int DT = D / 32;
     static_assert(BN % 32 == 0 && D % 32 == 0, "tile shape");
     static_assert(BN % (RPI * NW) == 0, "tile rows must split evenly over the waves");
-    static_assert(2 * (KBUF + VBUF) >= NW * 32 * OSTR, "output staging must fit in the tile buffers");
+    static_assert(NS * (KBUF + VBUF) >= NW * 32 * OSTR, "output staging must fit in the tile buffers");
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -181,6 +183,19 @@ __device__ __forceinline__ void load_tile_async_stream(const bf16_t* (&kptr)[Cfg
 
 // all direct loads of this wave have landed in LDS (vmcnt(0); the other counters untouched)
 __device__ __forceinline__ void wait_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// all but the newest N vector-memory operations of this wave are complete
+template <int N>
+__device__ __forceinline__ void wait_direct_loads_but() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+// the tile after the current one has landed although `ahead` younger tiles (LPT loads each) are still in flight
+template <int LPT, int MAXAHEAD>
+__device__ __forceinline__ void wait_next_tile(int ahead) {
+    if (MAXAHEAD >= 2 && ahead >= 2) wait_direct_loads_but<2 * LPT>();
+    else if (MAXAHEAD >= 1 && ahead == 1) wait_direct_loads_but<LPT>();
+    else wait_direct_loads();
+}
 
 // Transposing LDS read: the 16 lanes of a group each point at 8 bytes; lane i of the group
 // receives element (i % 4) of the lanes 4e + i/4, e = 0..3.  With lane i pointing at row i/4,
@@ -471,7 +486,7 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, kept in a scalar register
     const int g = lane >> 5, l32 = lane & 31;
     bf16_t* Ks = smem;
-    bf16_t* Vt = smem + 2 * C::KBUF;
+    bf16_t* Vt = smem + C::NS * C::KBUF;
 
     const int nkeys = J.n0 + J.n1 + J.n2;
     const int kend_wg = min(nkeys, J.causal_base + J.q_rows);
@@ -530,10 +545,6 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
         goffv = 2u * (rl * D + ((pc ^ ((4 * (rl % 4)) % C::CPR)) * 8));
     }
 
-    if (ntiles > 0) load_tile_async<D, NW, BN, QT>(J, 0, nkeys, w, lane, Ks, Vt);
-    wait_direct_loads();
-    __syncthreads();
-
     // Tiles that every row of the block sees in full come first and run in a loop of their own:
     // straight-line code, no per-wave decisions except that a wave without rows (a block shorter
     // than BM) only helps with the loads.  This is where the time goes.
@@ -550,45 +561,55 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
             tile_stride = (long)BN * D;
         }
     }
+    constexpr int AHEAD = C::NS - 1;          // tiles requested ahead of the one being multiplied
+    constexpr int LPT = 2 * C::IPW;           // direct loads per wave and tile
     const bf16_t *kptr[C::IPW], *vptr[C::IPW];
 #pragma unroll
     for (int i = 0; i < C::IPW; ++i) {
         const bf16_t *kp, *vp;
         key_row<D>(J, min((w * C::IPW + i) * C::RPI, nkeys - 1), kp, vp);
-        kptr[i] = uniform_ptr(kp) + tile_stride;   // first streamed tile is tile 1
-        vptr[i] = uniform_ptr(vp) + tile_stride;
+        kptr[i] = uniform_ptr(kp) + AHEAD * tile_stride;   // the first streamed tile is tile AHEAD
+        vptr[i] = uniform_ptr(vp) + AHEAD * tile_stride;
     }
+    // request tile `t` into its stage (streamed with scalar pointers when it qualifies)
+    auto request_tile = [&](int t) {
+        bf16_t* Kd = Ks + (t % C::NS) * C::KBUF;
+        bf16_t* Vd = Vt + (t % C::NS) * C::VBUF;
+        if (t >= AHEAD && t < nstream)
+            load_tile_async_stream<D, NW, BN, QT>(kptr, vptr, tile_stride, w, goffk, goffv, Kd, Vd);
+        else
+            load_tile_async<D, NW, BN, QT>(J, t * BN, nkeys, w, lane, Kd, Vd);
+    };
+#pragma unroll
+    for (int t = 0; t < AHEAD; ++t)
+        if (t < ntiles) request_tile(t);
+    wait_next_tile<LPT, AHEAD - 1>(min(AHEAD, ntiles) - 1);   // tile 0 is in
+    __syncthreads();
+
     for (int kt = 0; kt < nfull; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nstream)
-            load_tile_async_stream<D, NW, BN, QT>(kptr, vptr, tile_stride, w, goffk, goffv, Ks + (buf ^ 1) * C::KBUF,
-                                                  Vt + (buf ^ 1) * C::VBUF);
-        else if (kt + 1 < ntiles)
-            load_tile_async<D, NW, BN, QT>(J, (kt + 1) * BN, nkeys, w, lane, Ks + (buf ^ 1) * C::KBUF,
-                                           Vt + (buf ^ 1) * C::VBUF);
+        const int st = kt % C::NS;
+        if (kt + AHEAD < ntiles) request_tile(kt + AHEAD);
         if (has_rows) {
             f32x16 S[QT][C::NSUB];
-            score_phase<D, NW, BN, QT, true>(Ks + buf * C::KBUF, koff, qreg, S, kt * BN, C::NSUB, my_lim, lane);
-            softmax_pv_phase<D, NW, BN, QT, true>(Vt + buf * C::VBUF, voff, S, O, m, lsum, sc, C::NSUB, lane);
+            score_phase<D, NW, BN, QT, true>(Ks + st * C::KBUF, koff, qreg, S, kt * BN, C::NSUB, my_lim, lane);
+            softmax_pv_phase<D, NW, BN, QT, true>(Vt + st * C::VBUF, voff, S, O, m, lsum, sc, C::NSUB, lane);
         }
-        wait_direct_loads();
+        wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
         __syncthreads();
     }
     // The remaining tiles: cut by the causal diagonal or by the end of the key list, differently
     // for every wave (a wave past its last visible key only helps with the loads).
     for (int kt = nfull; kt < ntiles; ++kt) {
-        const int buf = kt & 1;
+        const int st = kt % C::NS;
         const int k0 = kt * BN;
-        if (kt + 1 < ntiles)
-            load_tile_async<D, NW, BN, QT>(J, (kt + 1) * BN, nkeys, w, lane, Ks + (buf ^ 1) * C::KBUF,
-                                           Vt + (buf ^ 1) * C::VBUF);
+        if (kt + AHEAD < ntiles) request_tile(kt + AHEAD);
         if (k0 < kend_w) {
             const int nsub = min(C::NSUB, (kend_w - k0 + 31) >> 5);
             f32x16 S[QT][C::NSUB];
-            score_phase<D, NW, BN, QT, false>(Ks + buf * C::KBUF, koff, qreg, S, k0, nsub, my_lim, lane);
-            softmax_pv_phase<D, NW, BN, QT, false>(Vt + buf * C::VBUF, voff, S, O, m, lsum, sc, nsub, lane);
+            score_phase<D, NW, BN, QT, false>(Ks + st * C::KBUF, koff, qreg, S, k0, nsub, my_lim, lane);
+            softmax_pv_phase<D, NW, BN, QT, false>(Vt + st * C::VBUF, voff, S, O, m, lsum, sc, nsub, lane);
         }
-        wait_direct_loads();
+        wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
         __syncthreads();
     }
 
@@ -618,7 +639,7 @@ __device__ __forceinline__ void rep_job(const FlashJob& J, float sc, bf16_t* sme
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, l32 = lane & 31;
     bf16_t* Ks = smem;
-    bf16_t* Vt = smem + 2 * C::KBUF;
+    bf16_t* Vt = smem + C::NS * C::KBUF;
     const int nkeys = J.n1;                     // <= BN
     const int row0 = 32 * w;
     const bool has_rows = row0 < J.q_rows;
@@ -677,7 +698,7 @@ struct MaskParams {
 };
 
 template <int D, int NW, int BN, int QT>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(QT == 1 ? 2 : 1))) void mask_attn_kernel(
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(QT == 2 ? 1 : 2))) void mask_attn_kernel(
     MaskParams P) {
     extern __shared__ __align__(16) bf16_t smem[];
     const MaskSchedule& sch = P.sched;
