@@ -12,7 +12,9 @@ previous layer):
 `value` is the useful TFLOP/s of the mask leg (unmasked pairs only); the decode leg's
 GB/s is reported next to it.  Each leg is bracketed by HIP events on the launch stream.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers 32] [--no-extra] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers 32] [--no-extra] [--no-high-ratio] [--no-cpu]
+    python bench.py --copy-calibration     three plain 1 GiB device copies and nothing else: the known
+                                           traffic the FETCH_SIZE / WRITE_SIZE counters are scaled by
 """
 from __future__ import annotations
 
@@ -27,6 +29,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_BF16_PEAK_TF = 2500.0  # MI355X dense bf16
+# HBM bytes per launch from rocprofv3 counter runs over this script (2.000 x FETCH_SIZE + 1.000 x WRITE_SIZE KiB,
+# the factors being what the same counters read for 1 GiB device copies: --copy-calibration).  Counters cannot be
+# read from inside a timed run, so these are the figures of the committed profile, not of this process.
+TRAFFIC_BYTES = {"decode": (2.0 * 68783.6 + 192) * 1024, "mask": (2.0 * 115952 + 64512) * 1024,
+                 "long_context_mask": (2.0 * 506947 + 261120) * 1024}
 
 
 def parse():
@@ -36,7 +43,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--no-extra", action="store_true", help="skip the long-context and high-ratio configurations")
+    ap.add_argument("--no-high-ratio", action="store_true", help="skip the high-ratio decode configuration (about 35 GB of state)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration", action="store_true", help="run three 1 GiB device copies and exit")
     return ap.parse_args()
 
 
@@ -115,6 +124,14 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read_per_copy": 1 << 30, "bytes_written_per_copy": 1 << 30, "copies": 3}}))
+        return
     gen = torch.Generator(device="cuda")
     gen.manual_seed(wl.SEED_BASE)
     L = args.layers
@@ -204,11 +221,13 @@ def main():
         "compress": {"us_per_call": comp_ms * 1e3, "algorithmic_GBps": comp_bytes / (comp_ms * 1e-3) / 1e9,
                      "useful_tflops": comp_flops / (comp_ms * 1e-3) / 1e12},
         # dominant kernel of the step by time: the split-K decode kernel (HBM-bound)
-        "roofline": {"kernel": "decode_split_kernel<128> (+ combine)", "bound": "hbm", "achieved": dec_gbs,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dec_gbs / HBM_PEAK_GBS, "traffic": None},
+        "roofline": {"kernel": "decode_split_kernel<128, 16>", "bound": "hbm", "achieved": dec_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dec_gbs / HBM_PEAK_GBS,
+                     "traffic": TRAFFIC_BYTES["decode"]},
         # the mask-pass kernel at this shape is HBM-bound too (63 flop/byte)
-        "roofline_mask": {"kernel": "mask_attn_kernel<128,2,32>", "bound": "hbm", "achieved": mask_gbs,
-                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": mask_gbs / HBM_PEAK_GBS, "traffic": None},
+        "roofline_mask": {"kernel": "mask_attn_kernel<128, 2, 32, 1>", "bound": "hbm", "achieved": mask_gbs,
+                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": mask_gbs / HBM_PEAK_GBS,
+                          "traffic": TRAFFIC_BYTES["mask"]},
     }
 
     # ---- the other single-GPU configurations, timed on their own ---------------------------------
@@ -224,11 +243,12 @@ def main():
         result["long_context_mask"] = {"workload": c4.name, "us_per_call": ms * 1e3, "useful_tflops": fl / (ms * 1e-3) / 1e12,
                                        "frac_of_mfma_peak": fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF,
                                        "algorithmic_GBps": wl.mask_pass_bytes(c4) / (ms * 1e-3) / 1e9}
-        result["roofline_long_context_mask"] = {"kernel": "mask_attn_kernel<128,4,64>", "bound": "mfma",
+        result["roofline_long_context_mask"] = {"kernel": "mask_attn_kernel<128, 4, 64, 1>", "bound": "mfma",
                                                 "achieved": fl / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TF,
                                                 "unit": "TFLOP/s", "frac": fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF,
-                                                "traffic": None}
+                                                "traffic": TRAFFIC_BYTES["long_context_mask"]}
         del sets
+    if not args.no_extra and not args.no_high_ratio:
         del gen_layers
         torch.cuda.empty_cache()
         c5 = wl.CONFIGS[4]
