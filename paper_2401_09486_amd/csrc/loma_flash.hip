@@ -67,7 +67,11 @@ struct Cfg {
     static constexpr int VBUF = BN * D;
     // tile stages in flight: the loads run NS-1 tiles ahead of the math
     static constexpr int NS = 2;
-    static constexpr int SMEM_BYTES = NS * (KBUF + VBUF) * 2;
+    static constexpr int RING_BYTES = NS * (KBUF + VBUF) * 2;
+    // repetition rows leave through an fp32 staging area (one per wave: 32 rows, padded, plus 32 row factors)
+    static constexpr int FSTR = D + 4;
+    static constexpr int REP_STAGE_BYTES = NW * (32 * FSTR + 32) * 4;
+    static constexpr int SMEM_BYTES = RING_BYTES > REP_STAGE_BYTES ? RING_BYTES : REP_STAGE_BYTES;
     static constexpr int OSTR = D + 8;                   // row stride of the output staging area
     static constexpr int RPI = 64 / CPR;                 // tile rows one wave-wide direct load covers
     static constexpr int IPW = BN / RPI / NW;            // direct loads per wave, per tensor, per tile
@@ -76,6 +80,7 @@ struct Cfg {
     static constexpr int DT = D / 32;
     static_assert(BN % 32 == 0 && D % 32 == 0, "tile shape");
     static_assert(BN % (RPI * NW) == 0, "tile rows must split evenly over the waves");
+    static_assert(NW <= 2 * (BN / 32), "the second ring stage must hold the block's queries");
     static_assert(NS * (KBUF + VBUF) >= NW * 32 * OSTR, "output staging must fit in the tile buffers");
 };
 
@@ -97,6 +102,22 @@ __device__ __forceinline__ float pair_max(float x) {
 __device__ __forceinline__ float pair_sum(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// sum over the CPR consecutive lanes (8 or 16) that hold one row; every lane gets the total
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+    const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false);
+    return x + __int_as_float(y);
+}
+template <int CPR>
+__device__ __forceinline__ float row_sum(float x) {
+    static_assert(CPR == 8 || CPR == 16, "lanes per row");
+    x = dpp_add<0xB1>(x);   // quad_perm [1,0,3,2]
+    x = dpp_add<0x4E>(x);   // quad_perm [2,3,0,1]
+    x = dpp_add<0x141>(x);  // row_half_mirror
+    if (CPR == 16) x = dpp_add<0x140>(x);  // row_mirror
+    return x;
 }
 
 // Global row of key j of the job's key list, written with selects only.  (Takes the job by
@@ -142,6 +163,31 @@ __device__ __forceinline__ void load_tile_async(const FlashJob& J, int k0, int n
         const int cv = p ^ ((4 * (r % 4)) % C::CPR);
         direct_load_16B(kp + ck * 8, Kb + rbase * D);
         direct_load_16B(vp + cv * 8, Vb + rbase * D);
+    }
+}
+
+// Where wave w keeps its 32 query rows in LDS: the second stage of the tile ring (free until the
+// first tile request inside the loop), laid out like a key tile, so the B-operand reads use the
+// same per-lane offsets as the K reads.
+template <int D, int NW, int BN, int QT>
+__device__ __forceinline__ bf16_t* query_stage(bf16_t* smem, int w) {
+    using C = Cfg<D, NW, BN, QT>;
+    static_assert(C::NS == 2, "the queries borrow ring stage 1");
+    bf16_t* Ks = smem;
+    bf16_t* Vt = smem + C::NS * C::KBUF;
+    return w < C::NSUB ? Ks + C::KBUF + w * 32 * D : Vt + C::VBUF + (w - C::NSUB) * 32 * D;
+}
+// Direct HBM -> LDS copy of the wave's 32 query rows: whole 1 KB runs per instruction instead of
+// 32 scattered 32-byte pieces (rows past the block replay its last row, never stored).
+template <int D, int NW, int BN, int QT>
+__device__ __forceinline__ void load_queries_async(const FlashJob& J, int row0, int lane, bf16_t* Qs) {
+    using C = Cfg<D, NW, BN, QT>;
+    const int p = lane % C::CPR;
+#pragma unroll
+    for (int i = 0; i < 32 / C::RPI; ++i) {
+        const int r = i * C::RPI + lane / C::CPR;
+        const int src = min(row0 + r, J.q_rows - 1);
+        direct_load_16B(J.q + (long)src * D + (p ^ (r % C::CPR)) * 8, Qs + i * C::RPI * D);
     }
 }
 
@@ -500,16 +546,11 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     for (int qt = 0; qt < QT; ++qt)                       // padded lanes replay the last row
         my_lim[qt] = min(J.causal_base + min(row0 + 32 * qt + l32, J.q_rows - 1), nkeys - 1);
 
-    // Q^T as the B operand: lane (query l32, half g) holds head-dim 16*ks + 8*g .. +7
+    // Q^T as the B operand: lane (query l32, half g) holds head-dim 16*ks + 8*g .. +7; it arrives through LDS
+    static_assert(QT == 1, "one 32-row query tile per wave");
     bf16x8 qreg[QT][C::KSTEPS];
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        const int r = min(row0 + 32 * qt + l32, J.q_rows - 1);   // lanes past the block replay its last row
-        const bf16_t* qp = J.q + (long)r * D + 8 * g;
-#pragma unroll
-        for (int ks = 0; ks < C::KSTEPS; ++ks)
-            qreg[qt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * ks));
-    }
+    bf16_t* Qs = query_stage<D, NW, BN, QT>(smem, w);
+    load_queries_async<D, NW, BN, QT>(J, row0, lane, Qs);
 
     f32x16 O[QT][C::DT];
     float m[QT], lsum[QT];
@@ -583,8 +624,11 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
 #pragma unroll
     for (int t = 0; t < AHEAD; ++t)
         if (t < ntiles) request_tile(t);
-    wait_next_tile<LPT, AHEAD - 1>(min(AHEAD, ntiles) - 1);   // tile 0 is in
+    wait_next_tile<LPT, AHEAD - 1>(min(AHEAD, ntiles) - 1);   // tile 0 and the queries are in
     __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < C::KSTEPS; ++ks) qreg[0][ks] = *reinterpret_cast<const bf16x8*>(Qs + koff[ks]);
+    __syncthreads();   // ring stage 1 belongs to the tiles from here on
 
     for (int kt = 0; kt < nfull; ++kt) {
         const int st = kt % C::NS;
@@ -627,14 +671,19 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
 }
 
 // Repetition rows when the memory zone fits one tile: t memory keys plus the row's own key
-// (Eq. 1 row 3, Eq. 9).  Everything the block needs is requested up front -- Q and the rows' own K
-// and V into registers, the memory-zone tile by direct loads -- so the block pays ONE memory round
-// trip instead of one per step.  (Repetition rows are nearly half of all rows and almost pure
-// HBM traffic: q, k, v in, out written, a few dozen keys of math.)
+// (Eq. 1 row 3, Eq. 9).  Repetition rows are nearly half of all rows and almost pure HBM traffic
+// (q, k, v in, out written, a few dozen keys of math), so everything the block reads is
+// requested up front -- ONE memory round trip -- and every request covers whole 1 KB runs:
+// the queries and the memory-zone tile go straight to LDS, the rows' own K and V go to
+// registers in the layout of the row-wise store (lane = 16-byte piece of a row).  The own key's
+// score is a dot product in that layout (q read back from LDS the same way) summed over the
+// lanes of a row; its V term is added when the rows leave through an fp32 staging area, so the
+// output is rounded once.
 template <int D, int NW, int BN>
 __device__ __forceinline__ void rep_job(const FlashJob& J, float sc, bf16_t* smem) {
     constexpr int QT = 1;
     using C = Cfg<D, NW, BN, QT>;
+    constexpr int NR = 32 / C::RPI;             // wave-wide row-layout accesses that cover 32 rows
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, l32 = lane & 31;
@@ -643,17 +692,17 @@ __device__ __forceinline__ void rep_job(const FlashJob& J, float sc, bf16_t* sme
     const int nkeys = J.n1;                     // <= BN
     const int row0 = 32 * w;
     const bool has_rows = row0 < J.q_rows;
+    const int rl = lane / C::CPR, pc = lane % C::CPR;   // row-layout role: row rl of each group of RPI rows, piece pc
 
+    bf16_t* Qs = query_stage<D, NW, BN, QT>(smem, w);
+    load_queries_async<D, NW, BN, QT>(J, row0, lane, Qs);
     load_tile_async<D, NW, BN, QT>(J, 0, nkeys, w, lane, Ks, Vt);
-    bf16x8 qreg[QT][C::KSTEPS], kself[C::KSTEPS];
-    uint2 vself[C::DT][4];
-    {
-        const int r = min(row0 + l32, J.q_rows - 1);
-        const bf16_t* qp = J.q + (long)r * D + 8 * g;
+    u32x4 kc[NR], vc[NR];
 #pragma unroll
-        for (int ks = 0; ks < C::KSTEPS; ++ks)
-            qreg[0][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * ks));
-        load_self_rows<D, NW, BN, QT>(J, r, g, kself, vself);
+    for (int i = 0; i < NR; ++i) {
+        const long src = (long)min(row0 + i * C::RPI + rl, J.q_rows - 1) * D + pc * 8;
+        kc[i] = *reinterpret_cast<const u32x4*>(J.k_self + src);
+        vc[i] = *reinterpret_cast<const u32x4*>(J.v_self + src);
     }
     __builtin_amdgcn_sched_barrier(0);   // all requests are out before anything waits
     int koff[C::KSTEPS], voff[C::DT];
@@ -675,16 +724,87 @@ __device__ __forceinline__ void rep_job(const FlashJob& J, float sc, bf16_t* sme
 
     wait_direct_loads();
     __syncthreads();
+    float inv = 0.f;
     if (has_rows) {
+        bf16x8 qreg[QT][C::KSTEPS];
+#pragma unroll
+        for (int ks = 0; ks < C::KSTEPS; ++ks) qreg[0][ks] = *reinterpret_cast<const bf16x8*>(Qs + koff[ks]);
+        // the own key's score: q . k in the row layout, summed over the lanes of a row
+        float ss[NR];
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            const int r = i * C::RPI + rl;
+            const u32x4 qq = *reinterpret_cast<const u32x4*>(Qs + r * D + ((pc ^ (r % C::CPR)) * 8));
+            const uint32_t k0 = kc[i].x, k1 = kc[i].y, k2 = kc[i].z, k3 = kc[i].w;
+            const uint32_t q0 = qq.x, q1 = qq.y, q2 = qq.z, q3 = qq.w;
+            float a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q0), __builtin_bit_cast(bf16x2, k0), 0.f, false);
+            a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q1), __builtin_bit_cast(bf16x2, k1), a, false);
+            a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q2), __builtin_bit_cast(bf16x2, k2), a, false);
+            a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q3), __builtin_bit_cast(bf16x2, k3), a, false);
+            ss[i] = row_sum<C::CPR>(a);
+        }
+        // hand each row's score to the lanes that own the row in the accumulator layout (through the
+        // wave's own query area, which has been read by now)
+        float* xs = reinterpret_cast<float*>(Qs);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (pc == 0) {
+#pragma unroll
+            for (int i = 0; i < NR; ++i) xs[i * C::RPI + rl] = ss[i];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        const float sself = xs[l32];
+
         const int my_lim[QT] = {nkeys - 1};
         const int nsub = min(C::NSUB, (nkeys + 31) >> 5);
         f32x16 S[QT][C::NSUB];
         score_phase<D, NW, BN, QT, false>(Ks, koff, qreg, S, 0, nsub, my_lim, lane);
         softmax_pv_phase<D, NW, BN, QT, false>(Vt, voff, S, O, m, lsum, sc, nsub, lane);
-        self_term<D, NW, BN, QT>(qreg[0], kself, vself, O[0], m[0], lsum[0], sc, g);
+        // one more key: the row itself
+        const float mx = fmaxf(m[0], sself);
+        const float alpha = __builtin_amdgcn_exp2f((m[0] - mx) * sc);
+        const float p = __builtin_amdgcn_exp2f((sself - mx) * sc);
+        lsum[0] = lsum[0] * alpha + (g == 0 ? p : 0.f);
+        m[0] = mx;
+        const float ltot = pair_sum(lsum[0]);
+        inv = 1.f / ltot;
+        const float oscale = alpha * inv;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[0][dt][i] *= oscale;
+        if (J.lse != nullptr && g == 0 && row0 + l32 < J.q_rows)
+            J.lse[row0 + l32] = (mx * sc + __builtin_amdgcn_logf(ltot)) * LN2;
+        inv *= p;   // weight of the row's own V in the output
     }
-    __syncthreads();   // every wave is done with the tile before the staging area overwrites it
-    store_rows<D, NW, BN, QT>(J, O, m, lsum, sc, smem, w, lane, row0, has_rows);
+    __syncthreads();   // every wave is done with the tile and the queries before the staging areas overwrite them
+    if (has_rows) {
+        float* Of = reinterpret_cast<float*>(smem) + w * (32 * C::FSTR + 32);
+        float* wf = Of + 32 * C::FSTR;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                float4 x;
+                x.x = O[0][dt][4 * i4 + 0]; x.y = O[0][dt][4 * i4 + 1]; x.z = O[0][dt][4 * i4 + 2]; x.w = O[0][dt][4 * i4 + 3];
+                *reinterpret_cast<float4*>(Of + l32 * C::FSTR + 32 * dt + 8 * i4 + 4 * g) = x;
+            }
+        if (g == 0) wf[l32] = inv;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            const int r = i * C::RPI + rl;
+            const float4 a = *reinterpret_cast<const float4*>(Of + r * C::FSTR + pc * 8);
+            const float4 b = *reinterpret_cast<const float4*>(Of + r * C::FSTR + pc * 8 + 4);
+            const float wv = wf[r];
+            const uint32_t v0 = vc[i].x, v1 = vc[i].y, v2 = vc[i].z, v3 = vc[i].w;
+            uint4 o;
+            o.x = pack_bf16(a.x + wv * bf16_lo(v0), a.y + wv * bf16_hi(v0));
+            o.y = pack_bf16(a.z + wv * bf16_lo(v1), a.w + wv * bf16_hi(v1));
+            o.z = pack_bf16(b.x + wv * bf16_lo(v2), b.y + wv * bf16_hi(v2));
+            o.w = pack_bf16(b.z + wv * bf16_lo(v3), b.w + wv * bf16_hi(v3));
+            if (row0 + r < J.q_rows) *reinterpret_cast<uint4*>(J.out + (long)(row0 + r) * D + pc * 8) = o;
+        }
+    }
 }
 
 // ---- mask pass -------------------------------------------------------------------------------
