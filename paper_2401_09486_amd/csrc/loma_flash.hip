@@ -34,6 +34,7 @@ typedef uint16_t bf16_t;  // storage type of bf16 tensors
 
 constexpr int NO_CAUSAL = 1 << 29;
 constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LAZY_TAU = 8.f;   // a softmax reference may lag the running maximum by this much (exp2 units)
 constexpr float LN2 = 0.6931471805599453f;
 
 struct FlashJob {
@@ -329,32 +330,59 @@ __device__ __forceinline__ void score_phase(const bf16_t* Kb, const int (&koff)[
     }
 }
 
-template <int D, int NW, int BN, int QT, bool FULL>
+// Largest score of every query over one fully visible tile, joined with the running reference m.
+template <int D, int NW, int BN, int QT>
+__device__ __forceinline__ void tile_row_max(const f32x16 (&S)[QT][Cfg<D, NW, BN, QT>::NSUB], const float (&m)[QT],
+                                             float (&mx)[QT]) {
+    using C = Cfg<D, NW, BN, QT>;
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        float x = m[qt];
+#pragma unroll
+        for (int sub = 0; sub < C::NSUB; ++sub)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) x = fmaxf(x, S[qt][sub][i]);
+        mx[qt] = pair_max(x);
+    }
+}
+
+// RESCALE = false: the caller has checked that no query's maximum exceeds its reference m by more
+// than LAZY_TAU (in exp2 units), so m, and with it the scale of O and of the running sum, stay as
+// they are: probabilities are at most 2^LAZY_TAU, harmless in fp32 and in bf16, and the 64
+// multiplies of O are saved.  The final normalisation divides by a sum taken in the same scale.
+template <int D, int NW, int BN, int QT, bool FULL, bool RESCALE = true, bool HAVE_MAX = false>
 __device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&voff)[Cfg<D, NW, BN, QT>::DT],
                                                  f32x16 (&S)[QT][Cfg<D, NW, BN, QT>::NSUB],
                                                  f32x16 (&O)[QT][Cfg<D, NW, BN, QT>::DT], float (&m)[QT],
-                                                 float (&lsum)[QT], float sc, int nsub, int lane) {
+                                                 float (&lsum)[QT], float sc, int nsub, int lane,
+                                                 const float* mx_in = nullptr) {
     using C = Cfg<D, NW, BN, QT>;
     // ---- online softmax (per query: lanes l and l^32) ---------------------------------------------
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
         float mx = m[qt];
+        if constexpr (RESCALE) {
+            if constexpr (HAVE_MAX) {
+                mx = mx_in[qt];
+            } else {
 #pragma unroll
-        for (int sub = 0; sub < C::NSUB; ++sub)
-            if (FULL || sub < nsub) {
+                for (int sub = 0; sub < C::NSUB; ++sub)
+                    if (FULL || sub < nsub) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[qt][sub][i]);
+                        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[qt][sub][i]);
+                    }
+                mx = pair_max(mx);
             }
-        mx = pair_max(mx);
-        // rescale by exp2((m_old - m_new) * sc): exactly 1 for the rows whose maximum did not move.
-        // (Unconditional on purpose: a branch around it makes the compiler keep two copies of O.)
-        const float alpha = __builtin_amdgcn_exp2f((m[qt] - mx) * sc);
-        lsum[qt] *= alpha;
+            // rescale by exp2((m_old - m_new) * sc): exactly 1 for the rows whose maximum did not move.
+            // (No branch around it here: a branch makes the compiler keep two copies of O.)
+            const float alpha = __builtin_amdgcn_exp2f((m[qt] - mx) * sc);
+            lsum[qt] *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < C::DT; ++dt)
+            for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) O[qt][dt][i] *= alpha;
-        m[qt] = mx;
+                for (int i = 0; i < 16; ++i) O[qt][dt][i] *= alpha;
+            m[qt] = mx;
+        }
         const float mc = mx * sc;
         float ps = 0.f;
 #pragma unroll
@@ -630,16 +658,35 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     for (int ks = 0; ks < C::KSTEPS; ++ks) qreg[0][ks] = *reinterpret_cast<const bf16x8*>(Qs + koff[ks]);
     __syncthreads();   // ring stage 1 belongs to the tiles from here on
 
-    for (int kt = 0; kt < nfull; ++kt) {
-        const int st = kt % C::NS;
-        if (kt + AHEAD < ntiles) request_tile(kt + AHEAD);
-        if (has_rows) {
+    // The fast loop keeps the softmax reference m (and so the scale of O) while no query's maximum
+    // moves up by more than LAZY_TAU; when one does, the wave leaves the loop with the scores in
+    // hand, finishes that tile with a rescale and comes back.  Every path passes one barrier per tile.
+    {
+        int kt = 0;
+        while (kt < nfull) {
             f32x16 S[QT][C::NSUB];
-            score_phase<D, NW, BN, QT, true>(Ks + st * C::KBUF, koff, qreg, S, kt * BN, C::NSUB, my_lim, lane);
-            softmax_pv_phase<D, NW, BN, QT, true>(Vt + st * C::VBUF, voff, S, O, m, lsum, sc, C::NSUB, lane);
+            float mx[QT];
+            bool moved = false;
+            for (; kt < nfull; ++kt) {
+                const int st = kt % C::NS;
+                if (kt + AHEAD < ntiles) request_tile(kt + AHEAD);
+                if (has_rows) {
+                    score_phase<D, NW, BN, QT, true>(Ks + st * C::KBUF, koff, qreg, S, kt * BN, C::NSUB, my_lim, lane);
+                    tile_row_max<D, NW, BN, QT>(S, m, mx);
+                    if (__builtin_amdgcn_ballot_w64((mx[0] - m[0]) * sc > LAZY_TAU) != 0) { moved = true; break; }
+                    softmax_pv_phase<D, NW, BN, QT, true, false>(Vt + st * C::VBUF, voff, S, O, m, lsum, sc, C::NSUB, lane);
+                }
+                wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
+                __syncthreads();
+            }
+            if (moved) {
+                softmax_pv_phase<D, NW, BN, QT, true, true, true>(Vt + (kt % C::NS) * C::VBUF, voff, S, O, m, lsum, sc,
+                                                                   C::NSUB, lane, mx);
+                wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
+                __syncthreads();
+                ++kt;
+            }
         }
-        wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
-        __syncthreads();
     }
     // The remaining tiles: cut by the causal diagonal or by the end of the key list, differently
     // for every wave (a wave past its last visible key only helps with the loads).

@@ -61,6 +61,27 @@ def test_mask_pass_mfma_small(loma, c_oracle, cfg):
     run_mask(loma, c_oracle, cfg, want_lse=True)
 
 
+@pytest.mark.parametrize("shape", [(32, 8, 10), (16, 4, 12), (8, 4, 9)], ids=["t32c8_4wave", "t16c4_2wave", "t8c4_1wave"])
+@pytest.mark.parametrize("scale", [0.25, 1.0, 4.0])
+def test_mask_pass_moving_maximum(loma, c_oracle, shape, scale):
+    """A sharp softmax over keys whose norm keeps growing along the sequence: between some tiles a
+    row's running maximum moves by far more than the threshold up to which the kernel keeps its
+    softmax reference, between others by less, so both the kept-reference and the rescale path run
+    (with the default 1/sqrt(d) scale and unit-variance data the maximum settles in the first tile)."""
+    t, c, n = shape
+    cfg = small(f"moving_max_t{t}c{c}", 1, 2, 128, t, c, n)
+    print(f"[case] moving maximum {cfg} scale={scale}", flush=True)
+    q, k, v = wl.mask_inputs(cfg)
+    ramp = (0.25 + 1.75 * np.arange(cfg.S, dtype=np.float32) / cfg.S)[None, None, :, None]
+    k = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(k) * ramp)
+    lse = torch.empty((cfg.B, cfg.H, cfg.S), dtype=torch.float32, device="cuda")
+    out = loma.loma_mask_attn_fwd(to_dev(q), to_dev(k), to_dev(v), t, c, n, scale, lse=lse)
+    torch.cuda.synchronize()
+    ref, ref_lse = c_oracle.mask_attn(q, k, v, t, c, n, scale, return_lse=True)
+    check(to_host_f64(out), ref, cfg.dtype, cfg.name)
+    assert np.abs(lse.cpu().numpy().astype(np.float64) - ref_lse).max() <= 2e-2 * max(1.0, scale * 8)
+
+
 @pytest.mark.parametrize("cfg", [
     small("f32_d128_t16c2", 1, 2, 128, 16, 2, 3, dtype="f32", scale=1.0),
     small("f32_d40_t3c3", 2, 1, 40, 3, 3, 4, dtype="f32", scale=1.0),
