@@ -32,8 +32,8 @@ MFMA_BF16_PEAK_TF = 2500.0  # MI355X dense bf16
 # HBM bytes per launch from rocprofv3 counter runs over this script (2.000 x FETCH_SIZE + 1.000 x WRITE_SIZE KiB,
 # the factors being what the same counters read for 1 GiB device copies: --copy-calibration).  Counters cannot be
 # read from inside a timed run, so these are the figures of the committed profile, not of this process.
-TRAFFIC_BYTES = {"decode": (2.0 * 68783.6 + 192) * 1024, "mask": (2.0 * 115952 + 64512) * 1024,
-                 "long_context_mask": (2.0 * 506947 + 261120) * 1024}
+TRAFFIC_BYTES = {"decode": (2.0 * 68783.5 + 192) * 1024, "mask": (2.0 * 114529 + 64512) * 1024,
+                 "long_context_mask": (2.0 * 508406 + 261120) * 1024}
 
 
 def parse():
