@@ -230,6 +230,23 @@ def main():
                           "traffic": TRAFFIC_BYTES["mask"]},
     }
 
+    # ---- prompt form on the generation shape: a whole reading zone of new tokens per call --------------
+    if not args.no_extra:
+        pre = [tuple(randn_bf16((gc.B, gc.H, gc.R, gc.d), gen) for _ in range(3)) + (torch.empty((gc.B, gc.H, gc.R, gc.d), dtype=torch.bfloat16, device="cuda"),)
+               for _ in range(min(L, 8))]
+        pms = time_calls(lambda i: loma.loma_prefill_attn(pre[i % len(pre)][0], pre[i % len(pre)][1], pre[i % len(pre)][2],
+                                                          gen_layers[i % L]["k_mem"], gen_layers[i % L]["v_mem"],
+                                                          gen_layers[i % L]["k_read"], gen_layers[i % L]["v_read"],
+                                                          gc.t, gc.c, gc.prior_chunks + 1, 0, gc.scale, out=pre[i % len(pre)][3]), 4 * L)
+        nbh = gc.B * gc.H
+        pbytes = nbh * (2 * n_mem_keys * gc.d + 6 * gc.R * gc.d) * 2   # cache read once; q, k, v in, out and the appended K/V out
+        pflops = 4.0 * gc.d * nbh * (gc.R * n_mem_keys + gc.R * (gc.R + 1) / 2)
+        result["prefill"] = {"workload": f"{gc.name}: {gc.R} new tokens per sequence over {n_mem_keys} memory KVs",
+                             "us_per_call": pms * 1e3, "algorithmic_GBps": pbytes / (pms * 1e-3) / 1e9,
+                             "frac_of_hbm_peak": pbytes / (pms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             "useful_tflops": pflops / (pms * 1e-3) / 1e12,
+                             "vs_token_by_token": gc.R * dec_ms / pms}   # time of the same tokens through loma_decode_attn / this
+
     # ---- the other single-GPU configurations, timed on their own ---------------------------------
     if not args.no_extra:
         del mask_layers

@@ -124,6 +124,29 @@ int loma_decode_attn(const void* q, const void* k_new, const void* v_new,
                      void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Generation form, several new tokens per sequence at once: a prompt or a piece of one
+ * (Appendix A: add_token_ids / inference_input with more than one input token, whose
+ * mask is the lower triangle shifted by the cache length; the cost model T_infer(l, k)
+ * of Sec. 3.1).  Same state and same arguments as loma_decode_attn, with n_new rows:
+ *
+ *   q, k_new, v_new, out: [B, H, n_new, head_dim]   (k_new, v_new required)
+ * New token i (0 <= i < n_new) attends over all n_mem_chunks*t memory keys, the
+ * read_fill live reading-zone rows and new tokens 0..i (itself included): exactly what
+ * n_new successive loma_decode_attn calls would give.  k_new/v_new are written to
+ * reading-zone rows [read_fill, read_fill + n_new); the caller then sets
+ * read_fill += n_new and calls loma_compress_step when the zone is full.
+ * Requires 1 <= n_new and read_fill + n_new <= t*c (a longer prompt is fed in pieces
+ * with compression steps in between, as the appendix's driver loop does).
+ * lse (optional, may be NULL): [B, H, n_new] float.  No workspace; deterministic.
+ */
+int loma_prefill_attn(const void* q, const void* k_new, const void* v_new,
+                      const void* k_memcache, const void* v_memcache,
+                      void* k_read, void* v_read, void* out, float* lse,
+                      int B, int H, int head_dim, int t, int c,
+                      int n_mem_chunks, int mem_capacity, int read_fill, int n_new,
+                      float scale, int dtype, void* stream);
+
+/*
  * Bytes of workspace loma_decode_attn needs for this shape at ANY read_fill in [0, R]
  * (with or without k_new).  0 on invalid arguments.  Host-only arithmetic.
  */

@@ -139,6 +139,15 @@ class GenerationCache:
         return attend_segments(q, self.k_mem, self.v_mem, self.n_mem_chunks * self.t,
                                self.k_read, self.v_read, self.read_fill, self.scale, bh_list)
 
+    def prefill(self, q, k_new, v_new, bh_list=None):
+        """l tokens at once (Appendix A, several input tokens): token i sees the cache and new tokens
+        0..i -- written out as l single-token steps, the plain meaning of the shifted lower triangle."""
+        l = q.shape[2]
+        if l < 1 or self.read_fill + l > self.R:
+            raise ValueError("the new tokens must fit the reading zone")
+        outs = [self.decode(q[:, :, i:i + 1], k_new[:, :, i:i + 1], v_new[:, :, i:i + 1], bh_list) for i in range(l)]
+        return np.concatenate(outs, axis=2)
+
     def compress(self, q_m, k_m, v_m, bh_list=None):
         """t <m> queries over [reading zone || own K/V]; then splice the t new KVs into the memory."""
         if self.read_fill != self.R:

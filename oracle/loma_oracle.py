@@ -209,6 +209,29 @@ class GenerationCache:
         v = np.concatenate([self.v_mem, self.v_read], axis=2)
         return self._attend(np.asarray(q, dtype=np.float64), k, v)
 
+    def prefill(self, q, k_new, v_new):
+        """q, k_new, v_new: [B, H, l, d] -- l tokens fed at once (Appendix A, inference_input with
+        several input tokens).  The l rows are appended to the reading zone; the mask over
+        [memory || reading zone incl. the new rows] is the lower triangle shifted by the
+        number of cached rows: new token i sees every cached row and new tokens 0..i."""
+        q = np.asarray(q, dtype=np.float64)
+        l = q.shape[2]
+        if l < 1 or self.read_fill + l > self.R:
+            raise ValueError("the new tokens must fit the reading zone (feed a longer prompt in pieces)")
+        cached = self.k_mem.shape[2] + self.read_fill
+        self.k_read = np.concatenate([self.k_read, np.asarray(k_new, dtype=np.float64)], axis=2)
+        self.v_read = np.concatenate([self.v_read, np.asarray(v_new, dtype=np.float64)], axis=2)
+        k = np.concatenate([self.k_mem, self.k_read], axis=2)
+        v = np.concatenate([self.v_mem, self.v_read], axis=2)
+        mask = np.tril(np.ones((l, cached + l), dtype=np.uint8), k=cached)
+        out = np.empty(q.shape, dtype=np.float64)
+        lse = np.empty(q.shape[:3], dtype=np.float64)
+        for b in range(self.B):
+            for h in range(self.H):
+                out[b, h], lse[b, h], _ = masked_softmax_attention(q[b, h], k[b, h], v[b, h], mask, self.scale)
+        self.last_lse = lse
+        return out
+
     def compress(self, q_m, k_m, v_m):
         """q_m, k_m, v_m: [B, H, t, d] -- the t <m> tokens."""
         if self.read_fill != self.R:

@@ -123,6 +123,31 @@ int loma_decode_attn(const void* q, const void* k_new, const void* v_new,
                                        head_dim, R, (int)n_mem_keys, mem_capacity, read_fill, scale, dtype, st);
 }
 
+int loma_prefill_attn(const void* q, const void* k_new, const void* v_new,
+                      const void* k_memcache, const void* v_memcache,
+                      void* k_read, void* v_read, void* out, float* lse,
+                      int B, int H, int head_dim, int t, int c,
+                      int n_mem_chunks, int mem_capacity, int read_fill, int n_new,
+                      float scale, int dtype, void* stream) {
+    if (int rc = check_common(B, H, head_dim, t, c, scale, dtype)) return rc;
+    const int R = t * c;
+    if (n_mem_chunks < 0 || mem_capacity < 0 || read_fill < 0 || n_new < 1) return LOMA_ERR_INVALID_ARG;
+    const long long n_mem_keys = (long long)n_mem_chunks * t;
+    if (n_mem_keys > mem_capacity || n_mem_keys > 0x3fffffffLL) return LOMA_ERR_INVALID_ARG;
+    if ((long long)read_fill + n_new > R) return LOMA_ERR_INVALID_ARG;
+    if (!good_ptr(q) || !good_ptr(k_new) || !good_ptr(v_new) || !good_ptr(out) || !good_ptr(k_read) || !good_ptr(v_read))
+        return LOMA_ERR_INVALID_ARG;
+    if (n_mem_chunks > 0 && (!good_ptr(k_memcache) || !good_ptr(v_memcache))) return LOMA_ERR_INVALID_ARG;
+    if (lse != nullptr && (reinterpret_cast<uintptr_t>(lse) & 3u)) return LOMA_ERR_INVALID_ARG;
+    const int nbh = B * H;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (loma::use_mfma_path(dtype, head_dim))
+        return loma::launch_prefill_mfma(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, lse, nbh,
+                                         head_dim, R, (int)n_mem_keys, mem_capacity, read_fill, n_new, scale, st);
+    return loma::launch_prefill_generic(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, lse, nbh,
+                                        head_dim, R, (int)n_mem_keys, mem_capacity, read_fill, n_new, scale, dtype, st);
+}
+
 long long loma_mask_schedule_size(int B, int H, int head_dim, int t, int c, int n_chunks, int dtype) {
     if (check_common(B, H, head_dim, t, c, 1.f, dtype) != LOMA_OK || n_chunks < 1) return 0;
     if (!loma::use_mfma_path(dtype, head_dim)) return 0;

@@ -948,6 +948,54 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
     }
 }
 
+// ---- several new tokens against the cache (Appendix A, more than one input token) ----------------------
+struct PrefillParams {
+    const bf16_t *q, *k_new, *v_new, *k_cache, *v_cache;
+    bf16_t *k_read, *v_read, *out;
+    float* lse;
+    int n_new, R, nblk;     // nblk = row blocks per (b,h)
+    int n_mem_keys, read_fill;
+    long cache_rows;        // mem_capacity
+    float sc;
+};
+
+// Keys of a block of new tokens: the memory cache (contiguous), the live reading-zone rows, then the
+// new tokens themselves up to the block's last row, read from k_new/v_new and cut by the causal
+// diagonal -- a reading-zone block of the mask pass whose earlier memory zones sit in one piece.
+template <int D, int NW, int BN>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void prefill_kernel(PrefillParams P) {
+    constexpr int QT = 1;
+    extern __shared__ __align__(16) bf16_t smem[];
+    constexpr int BM = 32 * NW;
+    const int bh = blockIdx.x / P.nblk;
+    const int blk = P.nblk - 1 - blockIdx.x % P.nblk;   // last rows (most keys) first
+    const int o0 = blk * BM;
+    const int rows = min(BM, P.n_new - o0);
+    const long new0 = (long)bh * P.n_new;
+    FlashJob J;
+    J.k0 = P.k_cache + (long)bh * P.cache_rows * D; J.v0 = P.v_cache + (long)bh * P.cache_rows * D;
+    J.n0 = P.n_mem_keys; J.slab = 1; J.slab_magic = 0; J.slab_stride = D;
+    J.k1 = P.k_read + (long)bh * P.R * D; J.v1 = P.v_read + (long)bh * P.R * D; J.n1 = P.read_fill;
+    J.k2 = P.k_new + new0 * D; J.v2 = P.v_new + new0 * D; J.n2 = o0 + rows;
+    J.causal_base = P.n_mem_keys + P.read_fill + o0;
+    J.k_self = J.v_self = nullptr;
+    J.rows_grouped = (P.n_mem_keys % (64 / (D / 8))) == 0 && (P.n_mem_keys > 0 || P.read_fill % (64 / (D / 8)) == 0);
+    J.q_rows = rows;
+    J.q = P.q + (new0 + o0) * D;
+    J.out = P.out + (new0 + o0) * D;
+    J.lse = P.lse ? P.lse + new0 + o0 : nullptr;
+    flash_job<D, NW, BN, QT>(J, P.sc, smem);
+    // the new tokens join the reading zone (rows no block of this launch reads)
+    if (blk == 0) {
+        const int pieces = P.n_new * D / 8;
+        const uint4* ks = reinterpret_cast<const uint4*>(J.k2);
+        const uint4* vs = reinterpret_cast<const uint4*>(J.v2);
+        uint4* kd = reinterpret_cast<uint4*>(P.k_read + ((long)bh * P.R + P.read_fill) * D);
+        uint4* vd = reinterpret_cast<uint4*>(P.v_read + ((long)bh * P.R + P.read_fill) * D);
+        for (int i = threadIdx.x; i < pieces; i += 64 * NW) { kd[i] = ks[i]; vd[i] = vs[i]; }
+    }
+}
+
 template <typename K, typename P>
 int launch(K kernel, long long grid, int threads, int smem_bytes, const P& params, hipStream_t st) {
     if (grid <= 0) return LOMA_OK;
@@ -981,7 +1029,35 @@ int launch_compress_d(CompressParams& P, int nbh, hipStream_t st) {
     return launch(compress_kernel<D, 1, 32>, nbh, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, P, st);
 }
 
+template <int D>
+int launch_prefill_d(PrefillParams& P, int nbh, hipStream_t st) {
+    if (P.n_new > 64) {
+        P.nblk = (P.n_new + 127) / 128;
+        return launch(prefill_kernel<D, 4, 64>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, P, st);
+    }
+    P.nblk = 1;
+    // one workgroup walks the whole cache of its (b,h): 64-key tiles halve the number of dependent steps
+    if (P.n_new > 32) return launch(prefill_kernel<D, 2, 64>, nbh, 128, Cfg<D, 2, 64, 1>::SMEM_BYTES, P, st);
+    return launch(prefill_kernel<D, 1, 32>, nbh, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, P, st);
+}
+
 }  // namespace
+
+int launch_prefill_mfma(const void* q, const void* k_new, const void* v_new,
+                        const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
+                        void* out, float* lse, int nbh, int D, int R, int n_mem_keys, int mem_capacity,
+                        int read_fill, int n_new, float scale, hipStream_t st) {
+    PrefillParams P;
+    P.q = static_cast<const bf16_t*>(q); P.k_new = static_cast<const bf16_t*>(k_new);
+    P.v_new = static_cast<const bf16_t*>(v_new);
+    P.k_cache = static_cast<const bf16_t*>(k_memcache); P.v_cache = static_cast<const bf16_t*>(v_memcache);
+    P.k_read = static_cast<bf16_t*>(k_read); P.v_read = static_cast<bf16_t*>(v_read);
+    P.out = static_cast<bf16_t*>(out); P.lse = lse;
+    P.n_new = n_new; P.R = R; P.nblk = 1; P.n_mem_keys = n_mem_keys; P.read_fill = read_fill;
+    P.cache_rows = mem_capacity;
+    P.sc = scale * LOG2E;
+    return D == 128 ? launch_prefill_d<128>(P, nbh, st) : launch_prefill_d<64>(P, nbh, st);
+}
 
 int launch_mask_attn_mfma(const void* q, const void* k, const void* v, void* out, float* lse,
                           int nbh, int D, const Geometry& g, float scale, hipStream_t st) {

@@ -171,6 +171,30 @@ __global__ __launch_bounds__(64) void decode_rows_kernel(const T* q, const T* k_
     }
 }
 
+// one wave per new token: memory keys, live reading rows, new tokens 0..i (read from k_new/v_new);
+// the wave also appends its token to the reading zone (rows nobody reads in this launch)
+template <typename T>
+__global__ __launch_bounds__(64) void prefill_rows_kernel(const T* q, const T* k_new, const T* v_new,
+                                                          const T* k_cache, const T* v_cache, T* k_read, T* v_read,
+                                                          T* out, float* lse, int D, int R, int n_mem_keys,
+                                                          long cache_rows, int read_fill, int n_new, float scale) {
+    const long bh = blockIdx.x / n_new;
+    const int i = blockIdx.x % n_new;
+    RowSegs sg;
+    sg.k0 = k_cache ? k_cache + bh * cache_rows * D : nullptr;
+    sg.v0 = v_cache ? v_cache + bh * cache_rows * D : nullptr;
+    sg.n0 = n_mem_keys; sg.slab = 1 << 30; sg.slab_stride = 0;
+    sg.k1 = k_read + bh * R * D; sg.v1 = v_read + bh * R * D; sg.n1 = read_fill;
+    sg.k2 = k_new + bh * n_new * D; sg.v2 = v_new + bh * n_new * D; sg.n2 = i + 1;
+    const long row = bh * n_new + i;
+    wave_attend<T>(q + row * D, sg, D, scale, out + row * D, lse ? lse + row : nullptr);
+    const long dst = (bh * R + read_fill + i) * D;
+    for (int e = threadIdx.x; e < D; e += 64) {
+        k_read[dst + e] = k_new[row * D + e];
+        v_read[dst + e] = v_new[row * D + e];
+    }
+}
+
 inline int check_launch(long long grid) {
     return grid > 0x7fffffffLL ? LOMA_ERR_UNSUPPORTED : LOMA_OK;
 }
@@ -228,6 +252,26 @@ int launch_decode_generic(const void* q, const void* k_new, const void* v_new,
                            (const uint16_t*)q, (const uint16_t*)k_new, (const uint16_t*)v_new,
                            (const uint16_t*)k_memcache, (const uint16_t*)v_memcache, (uint16_t*)k_read,
                            (uint16_t*)v_read, (uint16_t*)out, D, R, n_mem_keys, (long)mem_capacity, read_fill, scale);
+    return after_launch();
+}
+
+int launch_prefill_generic(const void* q, const void* k_new, const void* v_new,
+                           const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
+                           void* out, float* lse, int nbh, int D, int R, int n_mem_keys, int mem_capacity,
+                           int read_fill, int n_new, float scale, int dtype, hipStream_t st) {
+    const long long grid = (long long)nbh * n_new;
+    if (int rc = check_launch(grid)) return rc;
+    if (dtype == LOMA_F32)
+        hipLaunchKernelGGL(prefill_rows_kernel<float>, dim3((unsigned)grid), dim3(64), 0, st,
+                           (const float*)q, (const float*)k_new, (const float*)v_new, (const float*)k_memcache,
+                           (const float*)v_memcache, (float*)k_read, (float*)v_read, (float*)out, lse,
+                           D, R, n_mem_keys, (long)mem_capacity, read_fill, n_new, scale);
+    else
+        hipLaunchKernelGGL(prefill_rows_kernel<uint16_t>, dim3((unsigned)grid), dim3(64), 0, st,
+                           (const uint16_t*)q, (const uint16_t*)k_new, (const uint16_t*)v_new,
+                           (const uint16_t*)k_memcache, (const uint16_t*)v_memcache, (uint16_t*)k_read,
+                           (uint16_t*)v_read, (uint16_t*)out, lse, D, R, n_mem_keys, (long)mem_capacity, read_fill,
+                           n_new, scale);
     return after_launch();
 }
 

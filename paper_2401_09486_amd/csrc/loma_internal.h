@@ -114,6 +114,16 @@ int launch_decode_generic(const void* q, const void* k_new, const void* v_new,
                           void* out, int nbh, int D, int R, int n_mem_keys, int mem_capacity, int read_fill,
                           float scale, int dtype, hipStream_t st);
 
+// Several new tokens against the cache: memory keys and live reading rows in full, new tokens causally.
+int launch_prefill_mfma(const void* q, const void* k_new, const void* v_new,
+                        const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
+                        void* out, float* lse, int nbh, int D, int R, int n_mem_keys, int mem_capacity,
+                        int read_fill, int n_new, float scale, hipStream_t st);
+int launch_prefill_generic(const void* q, const void* k_new, const void* v_new,
+                           const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
+                           void* out, float* lse, int nbh, int D, int R, int n_mem_keys, int mem_capacity,
+                           int read_fill, int n_new, float scale, int dtype, hipStream_t st);
+
 // Split-K decode over [memory cache || reading zone || new token].
 int decode_num_splits(int nbh, int n_keys);
 size_t decode_workspace_bytes(int nbh, int D, int n_keys_max);

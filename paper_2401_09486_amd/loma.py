@@ -42,6 +42,8 @@ def _load() -> ctypes.CDLL:
     lib.loma_compress_step.restype = I
     lib.loma_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, F, I, vp, Z, vp]
     lib.loma_decode_attn.restype = I
+    lib.loma_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, I, F, I, vp]
+    lib.loma_prefill_attn.restype = I
     lib.loma_decode_workspace_bytes.argtypes = [I, I, I, I, I, I, I]
     lib.loma_decode_workspace_bytes.restype = Z
     lib.loma_mask_schedule_size.argtypes = [I, I, I, I, I, I, I]
@@ -156,6 +158,27 @@ def loma_decode_attn(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, t,
                               pws, nws, _stream(stream))
     if rc != OK:
         raise LomaError(rc, "loma_decode_attn")
+    return out
+
+
+def loma_prefill_attn(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, t, c, n_mem_chunks, read_fill, scale,
+                      out=None, lse=None, stream=None):
+    """n_new tokens per sequence at once against [memory cache || reading zone], causal among themselves."""
+    B, H, n_new, d = q.shape
+    if out is None:
+        out = torch.empty_like(q)
+    dt = q.dtype
+    cap = 0 if k_memcache is None else k_memcache.shape[2]
+    pkm = None if k_memcache is None else _dev(k_memcache, "k_memcache", (B, H, cap, d), dt)
+    pvm = None if v_memcache is None else _dev(v_memcache, "v_memcache", (B, H, cap, d), dt)
+    plse = None if lse is None else _dev(lse, "lse", (B, H, n_new), torch.float32)
+    rc = lib.loma_prefill_attn(_dev(q, "q"), _dev(k_new, "k_new", q.shape, dt), _dev(v_new, "v_new", q.shape, dt),
+                               pkm, pvm, _dev(k_read, "k_read", (B, H, t * c, d), dt),
+                               _dev(v_read, "v_read", (B, H, t * c, d), dt), _dev(out, "out", q.shape, dt), plse,
+                               B, H, d, t, c, n_mem_chunks, cap, read_fill, n_new, float(scale), _dtype_code(q),
+                               _stream(stream))
+    if rc != OK:
+        raise LomaError(rc, "loma_prefill_attn")
     return out
 
 

@@ -119,6 +119,22 @@ def test_decode_rejects_bad_arguments(lib):
     assert decode_call(lib, B=1, H=8, wsb=need - 1) == EWS
 
 
+def test_prefill_rejects_bad_arguments(lib):
+    def call(q=P, kn=P, vn=P, km=P, vm=P, kr=P, vr=P, out=P, lse=None, B=2, H=4, d=128, t=16, c=4, nm=3, cap=64, fill=10,
+             n_new=20, scale=0.1, dtype=BF16):
+        return lib.loma_prefill_attn(q, kn, vn, km, vm, kr, vr, out, lse, B, H, d, t, c, nm, cap, fill, n_new, scale, dtype, None)
+    assert call(n_new=0) == EINVAL
+    assert call(fill=50, n_new=15) == EINVAL            # 65 > t*c = 64
+    assert call(fill=-1) == EINVAL
+    assert call(nm=5, cap=64) == EINVAL                 # 80 memory rows do not fit the cache
+    assert call(kn=None) == EINVAL and call(vn=None) == EINVAL
+    assert call(q=P + 8) == EINVAL                      # misaligned
+    assert call(km=None) == EINVAL and call(vm=None) == EINVAL
+    assert call(lse=P + 2) == EINVAL
+    assert call(d=100) == EUNSUP and call(dtype=7) == EUNSUP
+    assert call(scale=0.0) == EINVAL
+
+
 def test_decode_workspace_bytes(lib):
     f = lib.loma_decode_workspace_bytes
     assert f(0, 32, 128, 16, 4, 4, BF16) == 0

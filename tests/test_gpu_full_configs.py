@@ -6,7 +6,7 @@ import torch
 
 from gpu_util import check, host_bits, to_dev, to_host_f64
 from paper_2401_09486_amd import workloads as wl
-from test_gpu_parity import run_generation
+from test_gpu_parity import run_generation, run_prefill
 
 pytestmark = pytest.mark.gpu
 
@@ -50,6 +50,16 @@ def test_mask_pass_full_size(loma, c_oracle, idx, stride):
 def test_generation_config3_full(loma, c_oracle):
     worst = run_generation(loma, c_oracle, wl.CONFIGS[2])
     print(f"[result] config 3: all 256 steps, all (b,h): worst max abs {worst:.3e}", flush=True)
+
+
+def test_prefill_config3_shape_full(loma, c_oracle):
+    """The generation configuration with the prompt fed a reading zone at a time (64 tokens per call, the shape
+    bench.py times) and in uneven pieces; all (b,h), every new token."""
+    cfg = wl.CONFIGS[2]
+    run_prefill(loma, c_oracle, wl.GenConfig(cfg.index, "c3_prefill_whole_zone", cfg.B, cfg.H, cfg.d, cfg.t, cfg.c,
+                                             cfg.prior_chunks, 2 * cfg.R, cfg.dtype, cfg.kv_scale, cfg.q_scale), (cfg.R,))
+    run_prefill(loma, c_oracle, wl.GenConfig(cfg.index, "c3_prefill_pieces", cfg.B, cfg.H, cfg.d, cfg.t, cfg.c,
+                                             cfg.prior_chunks, cfg.R, cfg.dtype, cfg.kv_scale, cfg.q_scale), (7, 33, 24))
 
 
 def test_generation_config5_full(loma, c_oracle):

@@ -192,6 +192,73 @@ def test_generation_small(loma, c_oracle, cfg):
     run_generation(loma, c_oracle, cfg)
 
 
+# ---- several tokens at once (Appendix A, inference_input with more than one token) ---------------------
+def run_prefill(loma, c_oracle, cfg, pieces):
+    """Every reading zone is fed in pieces (token counts in `pieces`, summing to t*c) through
+    loma_prefill_attn, with compression steps in between; the oracle takes the same tokens one by one."""
+    print(f"[case] prefill {cfg} pieces={pieces}", flush=True)
+    assert sum(pieces) == cfg.R
+    st = wl.gen_initial_state(cfg)
+    dev = {k: to_dev(v) for k, v in st.items()}
+    orc = c_oracle.GenerationCache(st["k_mem"].copy(), st["v_mem"].copy(), cfg.prior_chunks,
+                                   st["k_read"].copy(), st["v_read"].copy(), cfg.R, cfg.t, cfg.c, cfg.scale)
+    n_mem, step = cfg.prior_chunks, 0
+    for event in range(cfg.n_compress):
+        qm, km, vm = wl.gen_compress_inputs(cfg, event)
+        loma.loma_compress_step(to_dev(qm), to_dev(km), to_dev(vm), dev["k_read"], dev["v_read"],
+                                dev["k_mem"], dev["v_mem"], cfg.t, cfg.c, n_mem, cfg.scale)
+        orc.compress(qm, km, vm)
+        n_mem, fill = n_mem + 1, 0
+        for l in pieces:
+            toks = [wl.gen_step_inputs(cfg, step + i) for i in range(l)]
+            q, kn, vn = (np.concatenate([tk[j] for tk in toks], axis=2) for j in range(3))
+            lse = torch.empty((cfg.B, cfg.H, l), dtype=torch.float32, device="cuda")
+            out = loma.loma_prefill_attn(to_dev(q), to_dev(kn), to_dev(vn), dev["k_mem"], dev["v_mem"],
+                                         dev["k_read"], dev["v_read"], cfg.t, cfg.c, n_mem, fill, cfg.scale, lse=lse)
+            torch.cuda.synchronize()
+            ref = orc.prefill(q, kn, vn).reshape(cfg.B, cfg.H, l, cfg.d)
+            check(to_host_f64(out), ref, cfg.dtype, f"prefill event {event} fill {fill} l {l}")
+            assert torch.isfinite(lse).all()
+            fill += l
+            step += l
+            # the new tokens sit in the reading zone, bit for bit, and nothing past them was touched
+            assert np.array_equal(host_bits(dev["k_read"][:, :, :fill]), orc.k_read[:, :, :fill])
+            assert np.array_equal(host_bits(dev["v_read"][:, :, :fill]), orc.v_read[:, :, :fill])
+
+
+@pytest.mark.parametrize("cfg,pieces", [
+    (gen_small("pre_bf16_t16c4", 2, 4, 128, 16, 4, 8, 128), (1, 31, 32)),         # 1-wave kernel (n_new 1, 31, 32)
+    (gen_small("pre_bf16_t16c4_whole", 1, 8, 128, 16, 4, 20, 64), (64,)),         # 2-wave kernel, whole reading zone
+    (gen_small("pre_bf16_t32c8", 1, 2, 128, 32, 8, 5, 512), (100, 156)),          # 4-wave kernel, 1 and 2 row blocks
+    (gen_small("pre_bf16_t32c8_whole", 1, 2, 128, 32, 8, 12, 256), (256,)),
+    (gen_small("pre_bf16_t4c3", 1, 2, 128, 4, 3, 40, 24), (5, 7)),                # nothing aligned
+    (gen_small("pre_bf16_d64", 1, 3, 64, 8, 4, 5, 32), (9, 23)),
+    (gen_small("pre_f32_generic", 1, 2, 64, 4, 4, 6, 32), (3, 13)),
+    (gen_small("pre_bf16_d96_generic", 1, 2, 96, 4, 4, 6, 16), (16,)),
+], ids=lambda x: x.name if hasattr(x, "name") else None)
+def test_prefill_small(loma, c_oracle, cfg, pieces):
+    run_prefill(loma, c_oracle, cfg, pieces)
+
+
+def test_prefill_into_an_empty_cache(loma):
+    """No memory yet, empty reading zone: plain causal attention over the new tokens (numpy oracle)."""
+    from oracle import loma_oracle as lo
+    B, H, d, t, c, l = 1, 2, 128, 16, 4, 40
+    rng = np.random.default_rng(9486 + 77)
+    q, kn, vn = (wl.f32_to_bf16_bits(rng.standard_normal((B, H, l, d)).astype(np.float32)) for _ in range(3))
+    k_read = torch.zeros((B, H, t * c, d), dtype=torch.bfloat16, device="cuda")
+    v_read = torch.zeros_like(k_read)
+    lse = torch.empty((B, H, l), dtype=torch.float32, device="cuda")
+    out = loma.loma_prefill_attn(to_dev(q), to_dev(kn), to_dev(vn), None, None, k_read, v_read, t, c, 0, 0, 1 / math.sqrt(d),
+                                 lse=lse)
+    gen = lo.GenerationCache(B, H, d, t, c, 1 / math.sqrt(d))
+    ref = gen.prefill(*(wl.bf16_bits_to_f32(x) for x in (q, kn, vn)))
+    check(to_host_f64(out), ref, "bf16", "empty cache")
+    assert np.abs(lse.cpu().numpy().astype(np.float64) - gen.last_lse).max() <= 2e-3
+    assert np.array_equal(host_bits(k_read[:, :, :l]), kn) and np.array_equal(host_bits(v_read[:, :, :l]), vn)
+    assert not k_read[:, :, l:].any() and not v_read[:, :, l:].any()
+
+
 def test_decode_without_new_token(loma, c_oracle):
     cfg = gen_small("nonew", 2, 2, 128, 16, 4, 4, 1)
     st = wl.gen_initial_state(cfg)

@@ -256,6 +256,59 @@ def test_generation_equals_mask_pass_rows(c_oracle, t, c, n, d):
         assert cg.n_mem_chunks == y + 1 and cg.read_fill == 0
 
 
+# ---- several tokens at once == the same tokens one by one == rows of the mask pass (Appendix A) --------
+@pytest.mark.parametrize("t,c,n,d,pieces", [(2, 2, 3, 8, (1, 3)), (4, 4, 3, 16, (5, 11)), (3, 2, 4, 4, (6,)), (2, 3, 2, 8, (2, 2, 2))])
+def test_prefill_equals_single_steps_and_mask_pass_rows(c_oracle, t, c, n, d, pieces):
+    """Each reading zone is fed in pieces (the sizes in `pieces`, summing to t*c).  Three routes must agree:
+    the explicit shifted-lower-triangle mask (numpy), single-token steps (C), and the reading rows of
+    the full mask pass, which is a separate routine working from the zone rules."""
+    R, s = t * c, t * (2 * c + 1)
+    assert sum(pieces) == R
+    S, B, H = n * s, 2, 2
+    rng = np.random.default_rng(16)
+    q, k, v = rand_qkv(rng, B, H, S, d)
+    scale = 1.0 / math.sqrt(d)
+    full = lo.mask_attn_fwd(q, k, v, t, c, n, scale, return_lse=True)
+    full_out, full_lse = full
+    gen = lo.GenerationCache(B, H, d, t, c, scale)
+    cg = c_oracle.GenerationCache(np.zeros((B, H, n * t, d), np.float32), np.zeros((B, H, n * t, d), np.float32), 0,
+                                  np.zeros((B, H, R, d), np.float32), np.zeros((B, H, R, d), np.float32), 0,
+                                  t, c, scale)
+    for y in range(n):
+        p = y * s
+        for l in pieces:
+            got = gen.prefill(q[:, :, p:p + l], k[:, :, p:p + l], v[:, :, p:p + l])
+            np.testing.assert_allclose(got, full_out[:, :, p:p + l], atol=1e-12)
+            np.testing.assert_allclose(gen.last_lse, full_lse[:, :, p:p + l], atol=1e-12)
+            got_c = cg.prefill(q[:, :, p:p + l].copy(), k[:, :, p:p + l].copy(), v[:, :, p:p + l].copy())
+            np.testing.assert_allclose(got_c.reshape(B, H, l, d), got, atol=1e-12)
+            p += l
+            assert gen.read_fill == cg.read_fill == p - y * s
+        m0, m1 = y * s + R, y * s + R + t
+        gen.compress(q[:, :, m0:m1], k[:, :, m0:m1], v[:, :, m0:m1])
+        cg.compress(q[:, :, m0:m1].copy(), k[:, :, m0:m1].copy(), v[:, :, m0:m1].copy())
+
+
+def test_prefill_mask_is_the_shifted_lower_triangle():
+    """Brute force on a tiny case: with Q = 0 every weight is uniform, so new token i returns the mean of the
+    cached V rows and of new V rows 0..i -- a closed form that a wrong diagonal shifts by one row."""
+    B, H, d, t, c = 1, 1, 3, 2, 3
+    gen = lo.GenerationCache(B, H, d, t, c, 0.7)
+    rng = np.random.default_rng(17)
+    km, vm = rng.standard_normal((B, H, 4, d)), rng.standard_normal((B, H, 4, d))
+    kr, vr = rng.standard_normal((B, H, 2, d)), rng.standard_normal((B, H, 2, d))
+    gen.load_state(km, vm, kr, vr)
+    kn, vn = rng.standard_normal((B, H, 3, d)), rng.standard_normal((B, H, 3, d))
+    out = gen.prefill(np.zeros((B, H, 3, d)), kn, vn)
+    cached = np.concatenate([vm, vr], axis=2)[0, 0]
+    for i in range(3):
+        want = np.concatenate([cached, vn[0, 0, :i + 1]]).mean(axis=0)
+        np.testing.assert_allclose(out[0, 0, i], want, atol=1e-13)
+    assert gen.read_fill == 5
+    with pytest.raises(ValueError):
+        gen.prefill(np.zeros((B, H, 2, d)), kn[:, :, :2], vn[:, :, :2])   # 5 + 2 > t*c
+
+
 def test_generation_state_machine_rejects_illegal_moves():
     gen = lo.GenerationCache(1, 1, 4, 2, 2, 0.5)
     z = np.zeros((1, 1, 1, 4))
