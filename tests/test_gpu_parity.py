@@ -192,6 +192,44 @@ def test_generation_small(loma, c_oracle, cfg):
     run_generation(loma, c_oracle, cfg)
 
 
+def random_shapes(seed, count):
+    """Seeded draw of small geometries that mixes every kernel variant: head_dim 64 / 128 (MFMA kernels),
+    reading zones below 32, between 32 and 64, 64..127 and 128 and more rows, memory zones from 1 to 70 rows
+    (the last needs two tiles for the repetition rows' keys), ragged everything."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        d = int(rng.choice([64, 128]))
+        t = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16, 20, 32, 33, 48, 70]))
+        c = int(rng.integers(1, 9))
+        while t * c > 300:
+            c = max(1, c // 2)
+        n = int(rng.integers(1, 6))
+        B, H = int(rng.integers(1, 3)), int(rng.choice([1, 2, 3, 4, 8]))
+        out.append((B, H, d, t, c, n))
+    # memory zones wider than one key tile of the kernel that takes them
+    return out + [(1, 2, 128, 48, 2, 3), (1, 1, 128, 70, 2, 2), (1, 2, 64, 33, 3, 2), (1, 1, 128, 70, 4, 2)]
+
+
+@pytest.mark.parametrize("shape", random_shapes(9486, 28), ids=lambda s: "B%d_H%d_d%d_t%d_c%d_n%d" % s)
+def test_mask_pass_random_shapes(loma, c_oracle, shape):
+    B, H, d, t, c, n = shape
+    run_mask(loma, c_oracle, small("rand_%d_%d_%d" % (t, c, n), B, H, d, t, c, n), want_lse=True)
+
+
+@pytest.mark.parametrize("shape", random_shapes(9487, 16), ids=lambda s: "B%d_H%d_d%d_t%d_c%d_n%d" % s)
+def test_generation_and_prefill_random_shapes(loma, c_oracle, shape):
+    """Token-by-token generation and the same reading zones fed in two or three random pieces."""
+    B, H, d, t, c, n = shape
+    R = t * c
+    prior = n * 3
+    run_generation(loma, c_oracle, gen_small("randgen", B, H, d, t, c, prior, min(2 * R + 1, 70)))
+    rng = np.random.default_rng(t * 1000 + c)
+    cuts = sorted(set(int(x) for x in rng.integers(1, R, size=2))) if R > 1 else []
+    pieces = tuple(b - a for a, b in zip([0] + cuts, cuts + [R]))
+    run_prefill(loma, c_oracle, gen_small("randpre", B, H, d, t, c, prior, 2 * R), pieces)
+
+
 # ---- several tokens at once (Appendix A, inference_input with more than one token) ---------------------
 def run_prefill(loma, c_oracle, cfg, pieces):
     """Every reading zone is fed in pieces (token counts in `pieces`, summing to t*c) through
