@@ -80,9 +80,11 @@ struct Cfg {
     static constexpr int KSTEPS = D / 16;
     static constexpr int DT = D / 32;
     static_assert(BN % 32 == 0 && D % 32 == 0, "tile shape");
-    static_assert(BN % (RPI * NW) == 0, "tile rows must split evenly over the waves");
-    static_assert(NW <= 2 * (BN / 32), "the second ring stage must hold the block's queries");
-    static_assert(NS * (KBUF + VBUF) >= NW * 32 * OSTR, "output staging must fit in the tile buffers");
+    // what a kernel needs of the configuration it LOADS tiles with (a configuration may also just describe
+    // the part of a tile one wave works on)
+    static constexpr bool LOADABLE = BN % (RPI * NW) == 0 &&        // tile rows split evenly over the waves
+                                     NW <= 2 * (BN / 32) &&          // a ring stage holds the block's queries
+                                     NS * (KBUF + VBUF) >= NW * 32 * OSTR;   // output staging fits in the tile buffers
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -167,16 +169,16 @@ __device__ __forceinline__ void load_tile_async(const FlashJob& J, int k0, int n
     }
 }
 
-// Where wave w keeps its 32 query rows in LDS: the second stage of the tile ring (free until the
+// Where wave w keeps its 32 query rows in LDS: the last stage of the tile ring (free until the
 // first tile request inside the loop), laid out like a key tile, so the B-operand reads use the
 // same per-lane offsets as the K reads.
-template <int D, int NW, int BN, int QT>
+template <int D, int NW, int BN, int QT, int NS = 2>
 __device__ __forceinline__ bf16_t* query_stage(bf16_t* smem, int w) {
     using C = Cfg<D, NW, BN, QT>;
-    static_assert(C::NS == 2, "the queries borrow ring stage 1");
+    static_assert(C::LOADABLE, "tile configuration");
     bf16_t* Ks = smem;
-    bf16_t* Vt = smem + C::NS * C::KBUF;
-    return w < C::NSUB ? Ks + C::KBUF + w * 32 * D : Vt + C::VBUF + (w - C::NSUB) * 32 * D;
+    bf16_t* Vt = smem + NS * C::KBUF;
+    return w < C::NSUB ? Ks + (NS - 1) * C::KBUF + w * 32 * D : Vt + (NS - 1) * C::VBUF + (w - C::NSUB) * 32 * D;
 }
 // Direct HBM -> LDS copy of the wave's 32 query rows: whole 1 KB runs per instruction instead of
 // 32 scattered 32-byte pieces (rows past the block replay its last row, never stored).
@@ -239,7 +241,9 @@ __device__ __forceinline__ void wait_direct_loads_but() {
 // the tile after the current one has landed although `ahead` younger tiles (LPT loads each) are still in flight
 template <int LPT, int MAXAHEAD>
 __device__ __forceinline__ void wait_next_tile(int ahead) {
-    if (MAXAHEAD >= 2 && ahead >= 2) wait_direct_loads_but<2 * LPT>();
+    static_assert(MAXAHEAD <= 3 && MAXAHEAD * LPT < 64, "wait depth");
+    if (MAXAHEAD >= 3 && ahead >= 3) wait_direct_loads_but<(MAXAHEAD >= 3 ? 3 : 0) * LPT>();
+    else if (MAXAHEAD >= 2 && ahead == 2) wait_direct_loads_but<(MAXAHEAD >= 2 ? 2 : 0) * LPT>();
     else if (MAXAHEAD >= 1 && ahead == 1) wait_direct_loads_but<LPT>();
     else wait_direct_loads();
 }
@@ -375,13 +379,18 @@ __device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&v
             }
             // rescale by exp2((m_old - m_new) * sc): exactly 1 for the rows whose maximum did not move.
             // (No branch around it here: a branch makes the compiler keep two copies of O.)
-            const float alpha = __builtin_amdgcn_exp2f((m[qt] - mx) * sc);
+            // A row that has seen no key yet and sees none in a cut tile (possible when the keys of a tile are
+            // split over wave groups) keeps m = -inf; the arithmetic then runs against 0 instead: factor 0 on
+            // an O that is 0, probabilities exp2(-inf) = 0.
+            const float mref = (!FULL && mx == -INFINITY) ? 0.f : mx;
+            const float alpha = __builtin_amdgcn_exp2f((m[qt] - mref) * sc);
             lsum[qt] *= alpha;
 #pragma unroll
             for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) O[qt][dt][i] *= alpha;
             m[qt] = mx;
+            mx = mref;
         }
         const float mc = mx * sc;
         float ps = 0.f;
@@ -553,19 +562,30 @@ __device__ __forceinline__ void store_rows(const FlashJob& J, f32x16 (&O)[QT][Cf
     }
 }
 
-template <int D, int NW, int BN, int QT>
+// KS > 1 splits the KEYS of every tile over KS groups of waves (for launches with few workgroups, where
+// one workgroup walks a long key list alone): the block has 32 * NW / KS rows, wave w owns row group
+// w % (NW / KS) and, of every tile of BN keys, the BN / KS keys of key group w / (NW / KS).  All waves
+// share the loads; the groups' partial results (same register layout in every wave) meet in LDS at
+// the end.
+template <int D, int NW, int BN, int QT, int KS = 1, int NS = 2>
 __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* smem) {
-    using C = Cfg<D, NW, BN, QT>;
+    using C = Cfg<D, NW, BN, QT>;            // tiles as they are loaded (the ring has NS stages)
+    constexpr int BNC = BN / KS;             // keys of a tile one wave works on
+    using CC = Cfg<D, NW, BNC, QT>;
+    constexpr int RG = NW / KS;              // row groups
+    static_assert(NW % KS == 0 && BN % (32 * KS) == 0, "key split");
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, kept in a scalar register
+    const int kg = w / RG;                                      // key group of this wave
     const int g = lane >> 5, l32 = lane & 31;
     bf16_t* Ks = smem;
-    bf16_t* Vt = smem + C::NS * C::KBUF;
+    bf16_t* Vt = smem + NS * C::KBUF;
+    const int wk0 = kg * BNC;                                   // first key of the wave's part of a tile
 
     const int nkeys = J.n0 + J.n1 + J.n2;
     const int kend_wg = min(nkeys, J.causal_base + J.q_rows);
     const int ntiles = (kend_wg + BN - 1) / BN;
-    const int row0 = C::WROWS * w;                        // first block row of this wave
+    const int row0 = C::WROWS * (w % RG);                 // first block row of this wave
     const bool has_rows = row0 < J.q_rows;
     const int row_hi = min(row0 + C::WROWS, J.q_rows);    // exclusive
     const int kend_w = has_rows ? min(nkeys, J.causal_base + row_hi) : 0;
@@ -577,7 +597,7 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     // Q^T as the B operand: lane (query l32, half g) holds head-dim 16*ks + 8*g .. +7; it arrives through LDS
     static_assert(QT == 1, "one 32-row query tile per wave");
     bf16x8 qreg[QT][C::KSTEPS];
-    bf16_t* Qs = query_stage<D, NW, BN, QT>(smem, w);
+    bf16_t* Qs = query_stage<D, NW, BN, QT, NS>(smem, w);
     load_queries_async<D, NW, BN, QT>(J, row0, lane, Qs);
 
     f32x16 O[QT][C::DT];
@@ -630,7 +650,7 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
             tile_stride = (long)BN * D;
         }
     }
-    constexpr int AHEAD = C::NS - 1;          // tiles requested ahead of the one being multiplied
+    constexpr int AHEAD = NS - 1;          // tiles requested ahead of the one being multiplied
     constexpr int LPT = 2 * C::IPW;           // direct loads per wave and tile
     const bf16_t *kptr[C::IPW], *vptr[C::IPW];
 #pragma unroll
@@ -642,8 +662,8 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     }
     // request tile `t` into its stage (streamed with scalar pointers when it qualifies)
     auto request_tile = [&](int t) {
-        bf16_t* Kd = Ks + (t % C::NS) * C::KBUF;
-        bf16_t* Vd = Vt + (t % C::NS) * C::VBUF;
+        bf16_t* Kd = Ks + (t % NS) * C::KBUF;
+        bf16_t* Vd = Vt + (t % NS) * C::VBUF;
         if (t >= AHEAD && t < nstream)
             load_tile_async_stream<D, NW, BN, QT>(kptr, vptr, tile_stride, w, goffk, goffv, Kd, Vd);
         else
@@ -664,24 +684,26 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     {
         int kt = 0;
         while (kt < nfull) {
-            f32x16 S[QT][C::NSUB];
+            f32x16 S[QT][CC::NSUB];
             float mx[QT];
             bool moved = false;
             for (; kt < nfull; ++kt) {
-                const int st = kt % C::NS;
+                const int st = kt % NS;
                 if (kt + AHEAD < ntiles) request_tile(kt + AHEAD);
                 if (has_rows) {
-                    score_phase<D, NW, BN, QT, true>(Ks + st * C::KBUF, koff, qreg, S, kt * BN, C::NSUB, my_lim, lane);
-                    tile_row_max<D, NW, BN, QT>(S, m, mx);
+                    score_phase<D, NW, BNC, QT, true>(Ks + st * C::KBUF + wk0 * D, koff, qreg, S, kt * BN + wk0, CC::NSUB,
+                                                      my_lim, lane);
+                    tile_row_max<D, NW, BNC, QT>(S, m, mx);
                     if (__builtin_amdgcn_ballot_w64((mx[0] - m[0]) * sc > LAZY_TAU) != 0) { moved = true; break; }
-                    softmax_pv_phase<D, NW, BN, QT, true, false>(Vt + st * C::VBUF, voff, S, O, m, lsum, sc, C::NSUB, lane);
+                    softmax_pv_phase<D, NW, BNC, QT, true, false>(Vt + st * C::VBUF + wk0 * D, voff, S, O, m, lsum, sc,
+                                                                  CC::NSUB, lane);
                 }
                 wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
                 __syncthreads();
             }
             if (moved) {
-                softmax_pv_phase<D, NW, BN, QT, true, true, true>(Vt + (kt % C::NS) * C::VBUF, voff, S, O, m, lsum, sc,
-                                                                   C::NSUB, lane, mx);
+                softmax_pv_phase<D, NW, BNC, QT, true, true, true>(Vt + (kt % NS) * C::VBUF + wk0 * D, voff, S, O, m, lsum,
+                                                                    sc, CC::NSUB, lane, mx);
                 wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
                 __syncthreads();
                 ++kt;
@@ -691,21 +713,55 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     // The remaining tiles: cut by the causal diagonal or by the end of the key list, differently
     // for every wave (a wave past its last visible key only helps with the loads).
     for (int kt = nfull; kt < ntiles; ++kt) {
-        const int st = kt % C::NS;
-        const int k0 = kt * BN;
+        const int st = kt % NS;
+        const int k0 = kt * BN + wk0;    // first key of this wave's part of the tile
         if (kt + AHEAD < ntiles) request_tile(kt + AHEAD);
         if (k0 < kend_w) {
-            const int nsub = min(C::NSUB, (kend_w - k0 + 31) >> 5);
-            f32x16 S[QT][C::NSUB];
-            score_phase<D, NW, BN, QT, false>(Ks + st * C::KBUF, koff, qreg, S, k0, nsub, my_lim, lane);
-            softmax_pv_phase<D, NW, BN, QT, false>(Vt + st * C::VBUF, voff, S, O, m, lsum, sc, nsub, lane);
+            const int nsub = min(CC::NSUB, (kend_w - k0 + 31) >> 5);
+            f32x16 S[QT][CC::NSUB];
+            score_phase<D, NW, BNC, QT, false>(Ks + st * C::KBUF + wk0 * D, koff, qreg, S, k0, nsub, my_lim, lane);
+            softmax_pv_phase<D, NW, BNC, QT, false>(Vt + st * C::VBUF + wk0 * D, voff, S, O, m, lsum, sc, nsub, lane);
         }
         wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
         __syncthreads();
     }
 
+    // key groups 1.. hand their partial results to group 0 of the same rows: every wave holds O, m and the
+    // running sum in the same registers of the same lanes, so they cross LDS as plain [register][lane] arrays
+    if constexpr (KS > 1) {
+        float* xs = reinterpret_cast<float*>(smem);   // the ring is free: the loop's last barrier has been passed
+        constexpr int PER_WAVE = (16 * C::DT + 2) * 64;
+        if (kg > 0 && has_rows) {
+            float* dst = xs + (size_t)(w - RG) * PER_WAVE + lane;
+#pragma unroll
+            for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) dst[(16 * dt + i) * 64] = O[0][dt][i];
+            dst[16 * C::DT * 64] = m[0];
+            dst[(16 * C::DT + 1) * 64] = lsum[0];
+        }
+        __syncthreads();
+        if (kg == 0 && has_rows) {
+#pragma unroll
+            for (int k = 1; k < KS; ++k) {
+                const float* src = xs + (size_t)(w + (k - 1) * RG) * PER_WAVE + lane;
+                const float mb = src[16 * C::DT * 64], lb = src[(16 * C::DT + 1) * 64];
+                const float mx = fmaxf(m[0], mb);
+                // a group that saw no key has m = -inf, sum 0 and O = 0: its factor is exp2(-inf) = 0
+                const float fa = __builtin_amdgcn_exp2f((m[0] - mx) * sc), fb = __builtin_amdgcn_exp2f((mb - mx) * sc);
+                lsum[0] = lsum[0] * fa + lb * fb;
+                m[0] = mx;
+#pragma unroll
+                for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) O[0][dt][i] = O[0][dt][i] * fa + src[(16 * dt + i) * 64] * fb;
+            }
+        }
+        __syncthreads();   // the exchange area becomes the staging area of store_rows
+    }
+    const bool owns_rows = has_rows && kg == 0;
     // the row's own key (identity block of Eq. 1, second term of Eq. 9), on the vector ALU
-    if (J.k_self != nullptr && has_rows) {
+    if (J.k_self != nullptr && owns_rows) {
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
             bf16x8 kself[C::KSTEPS];
@@ -714,7 +770,7 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
             self_term<D, NW, BN, QT>(qreg[qt], kself, vself, O[qt], m[qt], lsum[qt], sc, g);
         }
     }
-    store_rows<D, NW, BN, QT>(J, O, m, lsum, sc, smem, w, lane, row0, has_rows);
+    store_rows<D, NW, BN, QT>(J, O, m, lsum, sc, smem, w, lane, row0, owns_rows);
 }
 
 // Repetition rows when the memory zone fits one tile: t memory keys plus the row's own key
@@ -962,11 +1018,11 @@ struct PrefillParams {
 // Keys of a block of new tokens: the memory cache (contiguous), the live reading-zone rows, then the
 // new tokens themselves up to the block's last row, read from k_new/v_new and cut by the causal
 // diagonal -- a reading-zone block of the mask pass whose earlier memory zones sit in one piece.
-template <int D, int NW, int BN>
+template <int D, int NW, int BN, int KS, int NS>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void prefill_kernel(PrefillParams P) {
     constexpr int QT = 1;
     extern __shared__ __align__(16) bf16_t smem[];
-    constexpr int BM = 32 * NW;
+    constexpr int BM = 32 * NW / KS;
     const int bh = blockIdx.x / P.nblk;
     const int blk = P.nblk - 1 - blockIdx.x % P.nblk;   // last rows (most keys) first
     const int o0 = blk * BM;
@@ -984,7 +1040,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
     J.q = P.q + (new0 + o0) * D;
     J.out = P.out + (new0 + o0) * D;
     J.lse = P.lse ? P.lse + new0 + o0 : nullptr;
-    flash_job<D, NW, BN, QT>(J, P.sc, smem);
+    flash_job<D, NW, BN, QT, KS, NS>(J, P.sc, smem);
     // the new tokens join the reading zone (rows no block of this launch reads)
     if (blk == 0) {
         const int pieces = P.n_new * D / 8;
@@ -1031,14 +1087,27 @@ int launch_compress_d(CompressParams& P, int nbh, hipStream_t st) {
 
 template <int D>
 int launch_prefill_d(PrefillParams& P, int nbh, hipStream_t st) {
+    // Few workgroups (a handful of sequences): one workgroup walks the whole cache of its (b,h) alone, so what
+    // counts is how many bytes it keeps in flight and how few dependent steps it takes: a ring of four stages
+    // (three tiles requested ahead) and the keys of every tile split over two groups of waves.
+    // Many workgroups: the plain variants, more of which fit a CU.
+    const bool few = (long long)nbh * ((P.n_new + 63) / 64) < 1024;
+    constexpr int RING4 = 2 * Cfg<D, 4, 64, 1>::RING_BYTES;   // 4 stages of 64 keys
+    if (few && P.n_new <= 32) {
+        P.nblk = 1;
+        return launch(prefill_kernel<D, 2, 64, 2, 4>, nbh, 128, RING4, P, st);
+    }
+    if (few) {
+        P.nblk = (P.n_new + 63) / 64;
+        return launch(prefill_kernel<D, 4, 64, 2, 4>, (long long)nbh * P.nblk, 256, RING4, P, st);
+    }
     if (P.n_new > 64) {
         P.nblk = (P.n_new + 127) / 128;
-        return launch(prefill_kernel<D, 4, 64>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, P, st);
+        return launch(prefill_kernel<D, 4, 64, 1, 2>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, P, st);
     }
     P.nblk = 1;
-    // one workgroup walks the whole cache of its (b,h): 64-key tiles halve the number of dependent steps
-    if (P.n_new > 32) return launch(prefill_kernel<D, 2, 64>, nbh, 128, Cfg<D, 2, 64, 1>::SMEM_BYTES, P, st);
-    return launch(prefill_kernel<D, 1, 32>, nbh, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, P, st);
+    if (P.n_new > 32) return launch(prefill_kernel<D, 2, 64, 1, 2>, nbh, 128, Cfg<D, 2, 64, 1>::SMEM_BYTES, P, st);
+    return launch(prefill_kernel<D, 1, 32, 1, 2>, nbh, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, P, st);
 }
 
 }  // namespace
