@@ -41,6 +41,8 @@ def _load():
         lib.loma_oracle_attend_segments.argtypes = [vp, I, vp, vp, L, I, vp, vp, L, I, dp,
                                                     I, I, I, D, I, ip, I, I]
         lib.loma_oracle_attend_segments.restype = I
+        lib.loma_oracle_mask_attn_bwd.argtypes = [vp, vp, vp, vp, dp, dp, dp, I, I, I, I, I, I, D, I, I]
+        lib.loma_oracle_mask_attn_bwd.restype = I
         lib.loma_oracle_num_threads.restype = I
         _lib = lib
     return _lib
@@ -83,6 +85,21 @@ def mask_attn(q, k, v, t, c, n_chunks, scale, rows=None, return_lse=False, nthre
     if rc != 0:
         raise RuntimeError("loma_oracle_mask_attn failed")
     return (out, lse) if return_lse else out
+
+
+def mask_attn_bwd(q, k, v, dout, t, c, n_chunks, scale, nthreads=0):
+    """Gradients (dq, dk, dv), fp64 [B, H, S, d], of the mask pass for the upstream gradient dout."""
+    q, k, v, dout = (np.ascontiguousarray(x) for x in (q, k, v, dout))
+    code = _dtype_code(q)
+    assert all(_dtype_code(x) == code and x.shape == q.shape for x in (k, v, dout))
+    B, H, S, d = q.shape
+    assert S == n_chunks * t * (2 * c + 1)
+    dq, dk, dv = (np.empty((B, H, S, d), dtype=np.float64) for _ in range(3))
+    rc = _load().loma_oracle_mask_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv),
+                                           B, H, d, t, c, n_chunks, float(scale), code, nthreads)
+    if rc != 0:
+        raise RuntimeError("loma_oracle_mask_attn_bwd failed")
+    return dq, dk, dv
 
 
 def attend_segments(q, k1, v1, n1, k2, v2, n2, scale, bh_list=None, nthreads=0):

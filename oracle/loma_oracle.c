@@ -140,6 +140,84 @@ int loma_oracle_mask_attn(const void* q, const void* k, const void* v, double* o
 }
 
 /*
+ * Gradients of the mask pass for an upstream gradient dout of the output (Sec. 4.4, Eq. 5-7
+ * differentiated; masked pairs have weight 0 and carry nothing).  Row by row, with the row's mask
+ * written out explicitly as in the forward routine: weights w_j = softmax over the visible keys,
+ * o = sum_j w_j v_j, delta = dout . o, and for every visible key j
+ *     da_j = w_j (dout . v_j - delta);  dq += scale da_j k_j;  dk_j += scale da_j q;  dv_j += w_j dout.
+ * One thread owns a (b, h) pair, so the sums into dk/dv need no atomics.
+ * q, k, v, dout: [B, H, S, d] (float32 or bf16 bits); dq, dk, dv: [B, H, S, d] fp64.
+ */
+int loma_oracle_mask_attn_bwd(const void* q, const void* k, const void* v, const void* dout,
+                              double* dq, double* dk, double* dv,
+                              int B, int H, int d, int t, int c, int n, double scale, int dtype, int nthreads) {
+    if (!q || !k || !v || !dout || !dq || !dk || !dv || B < 1 || H < 1 || d < 1 || t < 1 || c < 1 || n < 1) return -1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return -1;
+    const int R = t * c, s = 2 * R + t, S = n * s;
+    int* col_chunk = malloc(sizeof(int) * S);
+    int* col_zone = malloc(sizeof(int) * S);
+    int* col_off = malloc(sizeof(int) * S);
+    if (!col_chunk || !col_zone || !col_off) { free(col_chunk); free(col_zone); free(col_off); return -1; }
+    for (int x = 0; x < S; ++x) { col_chunk[x] = x / s; col_off[x] = x % s; col_zone[x] = zone_of(x % s, R, t); }
+    memset(dk, 0, sizeof(double) * (size_t)B * H * S * d);
+    memset(dv, 0, sizeof(double) * (size_t)B * H * S * d);
+    int failed = 0;
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#endif
+#pragma omp parallel
+    {
+        uint8_t* mask = malloc((size_t)S);
+        int* key_rows = malloc(sizeof(int) * S);
+        double* w = malloc(sizeof(double) * S);
+        double* qrow = malloc(sizeof(double) * d);
+        double* krow = malloc(sizeof(double) * d);
+        double* grow = malloc(sizeof(double) * d);
+        double* orow = malloc(sizeof(double) * d);
+        if (!mask || !key_rows || !w || !qrow || !krow || !grow || !orow) {
+#pragma omp atomic write
+            failed = 1;
+        } else {
+#pragma omp for schedule(dynamic, 1)
+            for (int bh = 0; bh < B * H; ++bh) {
+                const size_t base = (size_t)bh * S;
+                for (int p = 0; p < S; ++p) {
+                    build_mask_row(p, t, c, n, col_chunk, col_zone, col_off, mask);
+                    int nk = 0;
+                    for (int x = 0; x < S; ++x) if (mask[x]) key_rows[nk++] = x;
+                    widen_row(q, base + p, d, dtype, qrow);
+                    widen_row(dout, base + p, d, dtype, grow);
+                    attend_one(qrow, k, v, dtype, base, key_rows, nk, d, scale, w, krow, orow, NULL);
+                    /* attend_one leaves exp(score - max) in w; normalise to the weights */
+                    double den = 0.0;
+                    for (int j = 0; j < nk; ++j) den += w[j];
+                    double delta = 0.0;
+                    for (int e = 0; e < d; ++e) delta += grow[e] * orow[e];
+                    double* dqp = dq + (base + p) * (size_t)d;
+                    for (int e = 0; e < d; ++e) dqp[e] = 0.0;
+                    for (int j = 0; j < nk; ++j) {
+                        const size_t kr = base + (size_t)key_rows[j];
+                        const double wj = w[j] / den;
+                        widen_row(v, kr, d, dtype, krow);
+                        double dw = 0.0;
+                        for (int e = 0; e < d; ++e) dw += grow[e] * krow[e];
+                        double* dvp = dv + kr * (size_t)d;
+                        for (int e = 0; e < d; ++e) dvp[e] += wj * grow[e];
+                        const double da = wj * (dw - delta) * scale;
+                        widen_row(k, kr, d, dtype, krow);
+                        double* dkp = dk + kr * (size_t)d;
+                        for (int e = 0; e < d; ++e) { dqp[e] += da * krow[e]; dkp[e] += da * qrow[e]; }
+                    }
+                }
+            }
+        }
+        free(mask); free(key_rows); free(w); free(qrow); free(krow); free(grow); free(orow);
+    }
+    free(col_chunk); free(col_zone); free(col_off);
+    return failed ? -1 : 0;
+}
+
+/*
  * Generation form, attention of Lq queries over an explicit key list made of two
  * segments (all pairs visible: the appendix masks for one new token, and for the
  * <m> pass, are all ones).  Per (b, h):

@@ -151,6 +151,35 @@ def mask_attn_fwd(q, k, v, t, c, n_chunks, scale, return_lse=False):
     return (out, lse) if return_lse else out
 
 
+def mask_attn_bwd(q, k, v, dout, t, c, n_chunks, scale):
+    """Gradients of the mask pass (Sec. 4.4: O = softmax(A + log M) V, Eq. 5-7) for an upstream
+    gradient dout of O.  With W the attention weights (0 on masked pairs):
+        dV = W^T dO;   dW = dO V^T;   dA = W * (dW - rowsum(dO * O));   dQ = scale dA K;   dK = scale dA^T Q.
+    A masked pair has W = 0, so nothing flows through it: a repetition row sends gradient only to its
+    chunk's memory K/V and to its own K/V (the path that trains the memory tokens, Sec. 4.2).
+    Returns (dq, dk, dv), fp64, shaped like q."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    dout = np.asarray(dout, dtype=np.float64)
+    B, H, S, d = q.shape
+    if S != n_chunks * t * (2 * c + 1):
+        raise ValueError("sequence length is not n_chunks * t(2c+1)")
+    mask = mask_from_blocks(t, c, n_chunks)
+    dq, dk, dv = np.empty_like(q), np.empty_like(q), np.empty_like(q)
+    for b in range(B):
+        for h in range(H):
+            O, _, W = masked_softmax_attention(q[b, h], k[b, h], v[b, h], mask, scale)
+            dO = dout[b, h]
+            dv[b, h] = W.T @ dO
+            dW = dO @ v[b, h].T
+            delta = (dO * O).sum(axis=1, keepdims=True)
+            dA = W * (dW - delta)
+            dq[b, h] = float(scale) * (dA @ k[b, h])
+            dk[b, h] = float(scale) * (dA.T @ q[b, h])
+    return dq, dk, dv
+
+
 # --------------------------------------------------------------------------
 # Generation form: Sec. 3.1 steps 1-3, Appendix A
 # --------------------------------------------------------------------------

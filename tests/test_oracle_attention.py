@@ -341,3 +341,77 @@ def test_workload_generation_schedule():
     assert (c3.n_compress, c3.mem_capacity) == (4, 1088)
     assert (c5.n_compress, c5.mem_capacity) == (1, 8208)
     assert wl.CONFIGS[1].S == 4032 and wl.CONFIGS[3].S == 32640 and wl.CONFIGS[0].S == 144
+
+
+# ---- backward of the mask pass (Sec. 4.4 differentiated) ------------------------------------------------
+def _loss(q, k, v, g, t, c, n, scale):
+    return float((lo.mask_attn_fwd(q, k, v, t, c, n, scale) * g).sum())
+
+
+@pytest.mark.parametrize("t,c,n,d", [(2, 2, 2, 4), (1, 3, 3, 3), (3, 1, 2, 5)])
+def test_backward_matches_finite_differences_of_the_forward_oracle(c_oracle, t, c, n, d):
+    """Central differences of L = sum(O * G) through the (separately pinned) forward routine, in every
+    coordinate of q, k and v of a tiny case: a dropped term, a wrong sign or a transposed operand in any of
+    the three gradients fails this."""
+    S, B, H = n * t * (2 * c + 1), 1, 2
+    rng = np.random.default_rng(21)
+    q, k, v = (x.astype(np.float64) for x in rand_qkv(rng, B, H, S, d))    # fp64, so the steps below are exact
+    g = rng.standard_normal(q.shape)
+    scale = 0.9 / math.sqrt(d)
+    dq, dk, dv = lo.mask_attn_bwd(q, k, v, g, t, c, n, scale)
+    eps = 1e-6
+    for name, x, grad in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        num = np.zeros_like(x)
+        it = np.nditer(x, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = x[idx]
+            x[idx] = old + eps
+            up = _loss(q, k, v, g, t, c, n, scale)
+            x[idx] = old - eps
+            dn = _loss(q, k, v, g, t, c, n, scale)
+            x[idx] = old
+            num[idx] = (up - dn) / (2 * eps)
+        np.testing.assert_allclose(grad, num, rtol=2e-6, atol=2e-8, err_msg=f"d{name}")
+    # the C routine (row by row, explicit mask rows) agrees with the numpy one (block-matrix mask)
+    cq, ck, cv = c_oracle.mask_attn_bwd(q.astype(np.float32), k.astype(np.float32), v.astype(np.float32),
+                                        g.astype(np.float32), t, c, n, scale)
+    fq, fk, fv = lo.mask_attn_bwd(q.astype(np.float32), k.astype(np.float32), v.astype(np.float32),
+                                  g.astype(np.float32), t, c, n, scale)
+    for a, b in ((cq, fq), (ck, fk), (cv, fv)):
+        np.testing.assert_allclose(a, b, atol=1e-12)
+    # ... also on bf16 bit patterns (the C routine widens them exactly)
+    bits = [wl.f32_to_bf16_bits(x.astype(np.float32)) for x in (q, k, v, g)]
+    wide = [wl.bf16_bits_to_f32(x) for x in bits]
+    for a, b in zip(c_oracle.mask_attn_bwd(*bits, t, c, n, scale), lo.mask_attn_bwd(*wide, t, c, n, scale)):
+        np.testing.assert_allclose(a, b, atol=1e-12)
+
+
+def test_backward_invariants(c_oracle):
+    """What the mask fixes about the gradients, whatever the numbers: a repetition token's K/V receive
+    gradient from its own row only (dV_p = w_pp dO_p exactly); reading-zone K/V of a chunk receive nothing
+    from other chunks; rows of the score gradient sum to zero, so dQ vanishes when all visible keys are equal."""
+    t, c, n, d = 2, 2, 3, 6
+    R, s = t * c, t * (2 * c + 1)
+    S = n * s
+    rng = np.random.default_rng(22)
+    q, k, v = rand_qkv(rng, 1, 1, S, d)
+    g = rng.standard_normal(q.shape)
+    scale = 0.5
+    dq, dk, dv = lo.mask_attn_bwd(q, k, v, g, t, c, n, scale)
+    mask = lo.mask_from_blocks(t, c, n)
+    _, _, W = lo.masked_softmax_attention(q[0, 0], k[0, 0], v[0, 0], mask, scale)
+    for y in range(n):
+        for o in range(R + t, s):
+            p = y * s + o
+            np.testing.assert_allclose(dv[0, 0, p], W[p, p] * g[0, 0, p], atol=1e-14)
+    # gradients from chunk 1's rows alone never reach chunk 0's reading-zone K/V
+    g1 = np.zeros_like(g)
+    g1[:, :, s:2 * s] = g[:, :, s:2 * s]
+    _, dk1, dv1 = lo.mask_attn_bwd(q, k, v, g1, t, c, n, scale)
+    assert not dk1[0, 0, :R].any() and not dv1[0, 0, :R].any()
+    assert dk1[0, 0, R:R + t].any() and dv1[0, 0, R:R + t].any()       # ... but they do reach its memory zone
+    # equal keys: softmax is flat in q, so dQ = 0
+    k2 = np.broadcast_to(k[:, :, :1], k.shape).copy()
+    dq2, _, _ = lo.mask_attn_bwd(q, k2, v, g, t, c, n, scale)
+    np.testing.assert_allclose(dq2, 0.0, atol=1e-13)
