@@ -44,7 +44,7 @@ extern "C" {
 #define LOMA_OK 0
 #define LOMA_ERR_INVALID_ARG (-1) /* null/misaligned pointer, non-positive size, state the method forbids */
 #define LOMA_ERR_UNSUPPORTED (-2) /* well-formed but outside what the kernels handle (dtype, head_dim, size) */
-#define LOMA_ERR_WORKSPACE (-3)   /* workspace missing or smaller than loma_decode_workspace_bytes() */
+#define LOMA_ERR_WORKSPACE (-3)   /* workspace missing or smaller than the matching *_workspace_bytes() */
 #define LOMA_ERR_LAUNCH (-4)      /* the HIP runtime refused a kernel launch */
 
 #define LOMA_F32 0
@@ -72,6 +72,36 @@ int loma_abi_version(void);
 int loma_mask_attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
                        int B, int H, int head_dim, int t, int c, int n_chunks,
                        float scale, int dtype, void* stream);
+
+/*
+ * Gradients of the training form: what fine-tuning under the mask needs from this operation
+ * (Sec. 4.2: the loss L = L_LM + L_Repeat is back-propagated through the attention of Sec. 4.3-4.4;
+ * the repetition rows reach the text only through their chunk's memory-zone K/V, so the
+ * gradient that trains the memory tokens flows through exactly this operator).
+ *
+ *   q, k, v, out, dout, dq, dk, dv: [B, H, S, head_dim] in `dtype`, S = n_chunks * t * (2c + 1)
+ *   lse: [B, H, S] float, as written by loma_mask_attn_fwd for the same q, k, scale (required)
+ *   out: the forward output for the same inputs;  dout: gradient of the loss w.r.t. out.
+ * With W_ij = exp(scale q_i.k_j - lse_i) on visible pairs and 0 on masked ones, and
+ * delta_i = dout_i . out_i:
+ *   dv_j = sum_i W_ij dout_i
+ *   dq_i = scale sum_j W_ij (dout_i . v_j - delta_i) k_j
+ *   dk_j = scale sum_i W_ij (dout_i . v_j - delta_i) q_i
+ * Sums run over visible pairs only; masked tiles are never loaded.  Arithmetic as in the forward
+ * pass: bf16 products on the matrix cores with fp32 accumulation (W and dA rounded to bf16 before
+ * their products), fp32 throughout for f32 data.  dq, dk, dv are fully overwritten; they must not
+ * alias an input.  Deterministic: every output row is summed by one owner, no atomics.
+ * workspace: device scratch of at least loma_mask_attn_bwd_workspace_bytes(...) bytes (the per-row
+ * delta), 16-byte aligned; contents are don't-care on entry and exit.
+ */
+int loma_mask_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                       const void* dout, void* dq, void* dk, void* dv,
+                       int B, int H, int head_dim, int t, int c, int n_chunks,
+                       float scale, int dtype,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace loma_mask_attn_bwd needs for this shape.  0 on invalid arguments.  Host-only. */
+size_t loma_mask_attn_bwd_workspace_bytes(int B, int H, int head_dim, int t, int c, int n_chunks, int dtype);
 
 /*
  * Generation form, compression boundary (Sec. 3.1 step 2-3; Appendix A, compress_last_chunk).

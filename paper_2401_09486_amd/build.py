@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libloma.so")
-SOURCES = ("loma_api.hip", "loma_flash.hip", "loma_generic.hip", "loma_decode.hip")
+SOURCES = ("loma_api.hip", "loma_flash.hip", "loma_generic.hip", "loma_decode.hip", "loma_bwd_generic.hip")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",

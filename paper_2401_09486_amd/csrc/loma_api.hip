@@ -59,6 +59,41 @@ int loma_mask_attn_fwd(const void* q, const void* k, const void* v, void* out, f
     return loma::launch_mask_attn_generic(q, k, v, out, lse, nbh, head_dim, g, scale, dtype, st);
 }
 
+size_t loma_mask_attn_bwd_workspace_bytes(int B, int H, int head_dim, int t, int c, int n_chunks, int dtype) {
+    if (check_common(B, H, head_dim, t, c, 1.f, dtype) != LOMA_OK || n_chunks < 1) return 0;
+    const long long S = (long long)n_chunks * t * (2 * c + 1);
+    if (S > (1LL << 30)) return 0;
+    return (size_t)B * H * (size_t)S * sizeof(float);
+}
+
+int loma_mask_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                       const void* dout, void* dq, void* dk, void* dv,
+                       int B, int H, int head_dim, int t, int c, int n_chunks,
+                       float scale, int dtype,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+    if (int rc = check_common(B, H, head_dim, t, c, scale, dtype)) return rc;
+    if (n_chunks < 1) return LOMA_ERR_INVALID_ARG;
+    if (!good_ptr(q) || !good_ptr(k) || !good_ptr(v) || !good_ptr(out) || !good_ptr(dout) || !good_ptr(dq) ||
+        !good_ptr(dk) || !good_ptr(dv))
+        return LOMA_ERR_INVALID_ARG;
+    if (lse == nullptr || (reinterpret_cast<uintptr_t>(lse) & 3u)) return LOMA_ERR_INVALID_ARG;
+    for (const void* o : {(const void*)dq, (const void*)dk, (const void*)dv}) {
+        for (const void* i : {q, k, v, out, dout}) if (o == i) return LOMA_ERR_INVALID_ARG;
+    }
+    if (dq == dk || dq == dv || dk == dv) return LOMA_ERR_INVALID_ARG;
+    Geometry g;
+    g.t = t; g.c = c; g.n = n_chunks; g.R = t * c; g.s = t * (2 * c + 1);
+    const long long S = (long long)n_chunks * g.s;
+    if (S > (1LL << 30)) return LOMA_ERR_UNSUPPORTED;
+    g.S = (int)S;
+    const size_t need = loma_mask_attn_bwd_workspace_bytes(B, H, head_dim, t, c, n_chunks, dtype);
+    if (workspace == nullptr || workspace_bytes < need || !aligned16(workspace)) return LOMA_ERR_WORKSPACE;
+    const int nbh = B * H;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return loma::launch_mask_attn_bwd_generic(q, k, v, out, lse, dout, dq, dk, dv, static_cast<float*>(workspace),
+                                              nbh, head_dim, g, scale, dtype, st);
+}
+
 int loma_compress_step(const void* q_mem, const void* k_mem, const void* v_mem,
                        const void* k_read, const void* v_read,
                        void* k_memcache, void* v_memcache, void* out,

@@ -114,6 +114,11 @@ int launch_decode_generic(const void* q, const void* k_new, const void* v_new,
                           void* out, int nbh, int D, int R, int n_mem_keys, int mem_capacity, int read_fill,
                           float scale, int dtype, hipStream_t st);
 
+// Gradients of the mask pass; `delta` is the caller's workspace, nbh*S floats.
+int launch_mask_attn_bwd_generic(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                                 const void* dout, void* dq, void* dk, void* dv, float* delta,
+                                 int nbh, int D, const Geometry& g, float scale, int dtype, hipStream_t st);
+
 // Several new tokens against the cache: memory keys and live reading rows in full, new tokens causally.
 int launch_prefill_mfma(const void* q, const void* k_new, const void* v_new,
                         const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,

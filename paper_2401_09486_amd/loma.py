@@ -38,6 +38,10 @@ def _load() -> ctypes.CDLL:
     lib.loma_abi_version.restype = I
     lib.loma_mask_attn_fwd.argtypes = [vp, vp, vp, vp, vp, I, I, I, I, I, I, F, I, vp]
     lib.loma_mask_attn_fwd.restype = I
+    lib.loma_mask_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, F, I, vp, Z, vp]
+    lib.loma_mask_attn_bwd.restype = I
+    lib.loma_mask_attn_bwd_workspace_bytes.argtypes = [I, I, I, I, I, I, I]
+    lib.loma_mask_attn_bwd_workspace_bytes.restype = Z
     lib.loma_compress_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, F, I, vp]
     lib.loma_compress_step.restype = I
     lib.loma_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, F, I, vp, Z, vp]
@@ -106,6 +110,36 @@ def loma_mask_attn_fwd(q, k, v, t, c, n_chunks, scale, out=None, lse=None, strea
     if rc != OK:
         raise LomaError(rc, "loma_mask_attn_fwd")
     return out
+
+
+def loma_mask_attn_bwd_workspace_bytes(B, H, d, t, c, n_chunks, dtype=torch.bfloat16) -> int:
+    code = F32 if dtype == torch.float32 else BF16
+    return int(lib.loma_mask_attn_bwd_workspace_bytes(B, H, d, t, c, n_chunks, code))
+
+
+def loma_mask_attn_bwd(q, k, v, out, lse, dout, t, c, n_chunks, scale, dq=None, dk=None, dv=None, workspace=None,
+                       stream=None):
+    """Gradients of the training form for the upstream gradient dout; out and lse come from
+    loma_mask_attn_fwd on the same inputs.  Returns (dq, dk, dv)."""
+    B, H, S, d = q.shape
+    if S != n_chunks * t * (2 * c + 1):
+        raise ValueError("sequence length must be n_chunks * t * (2c + 1)")
+    dt = q.dtype
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(q) if dk is None else dk
+    dv = torch.empty_like(q) if dv is None else dv
+    if workspace is None:
+        need = loma_mask_attn_bwd_workspace_bytes(B, H, d, t, c, n_chunks, dt)
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    ptrs = [_dev(q, "q")] + [_dev(x, n, q.shape, dt) for x, n in ((k, "k"), (v, "v"), (out, "out"))]
+    ptrs.append(_dev(lse, "lse", (B, H, S), torch.float32))
+    ptrs += [_dev(x, n, q.shape, dt) for x, n in ((dout, "dout"), (dq, "dq"), (dk, "dk"), (dv, "dv"))]
+    rc = lib.loma_mask_attn_bwd(*ptrs, B, H, d, t, c, n_chunks, float(scale), _dtype_code(q),
+                                _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                _stream(stream))
+    if rc != OK:
+        raise LomaError(rc, "loma_mask_attn_bwd")
+    return dq, dk, dv
 
 
 def loma_compress_step(q_mem, k_mem, v_mem, k_read, v_read, k_memcache, v_memcache, t, c, n_mem_chunks, scale,

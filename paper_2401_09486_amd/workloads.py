@@ -137,6 +137,13 @@ def mask_inputs(cfg: MaskConfig):
     return tuple(_draw(rng, shape, cfg.value_scale, cfg.dtype) for _ in range(3))
 
 
+def mask_grad_input(cfg: MaskConfig):
+    """Upstream gradient of the mask pass's output, [B, H, S, d], unit normal, in the config's dtype
+    (a stream of its own, so q, k, v of mask_inputs are unchanged by drawing it)."""
+    rng = np.random.default_rng(cfg.seed + 500_000)
+    return _draw(rng, (cfg.B, cfg.H, cfg.S, cfg.d), 1.0, cfg.dtype)
+
+
 # ---- generation inputs ---------------------------------------------------------
 def gen_initial_state(cfg: GenConfig):
     """Cache at the start of the run: prior_chunks*t memory rows in buffers of

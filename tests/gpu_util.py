@@ -41,3 +41,22 @@ def check(got: np.ndarray, want: np.ndarray, dtype: str, what: str = ""):
         assert mx <= BF16_MAX, f"{what}: max abs err {mx:.3e} > {BF16_MAX}"
         assert mean <= BF16_MEAN, f"{what}: mean abs err {mean:.3e} > {BF16_MEAN}"
     return mx, mean
+
+
+def check_grad(got: np.ndarray, want: np.ndarray, dtype: str, what: str = ""):
+    """Gradients are sums over many rows and are not bounded by the value range as the outputs are, so
+    the bar scales with the value: fp32 data |err| <= 1e-5 (1 + |want|); bf16 data
+    |err| <= 2e-2 (1 + |want|) and mean |err| <= 2e-3 (1 + mean |want|) -- the output bar at magnitude
+    <= 1, and a few bf16 roundings (2^-9 each: weights, score gradients, result) above it."""
+    assert got.shape == want.shape, (got.shape, want.shape)
+    assert np.isfinite(got).all(), f"{what}: non-finite gradient"
+    err = np.abs(got - want)
+    mag = np.abs(want)
+    rel = float((err / (1.0 + mag)).max())
+    if dtype == "f32":
+        assert rel <= F32_MAX, f"{what}: scaled max err {rel:.3e} > {F32_MAX}"
+    else:
+        assert rel <= BF16_MAX, f"{what}: scaled max err {rel:.3e} > {BF16_MAX}"
+        mean, bar = float(err.mean()), BF16_MEAN * (1.0 + float(mag.mean()))
+        assert mean <= bar, f"{what}: mean abs err {mean:.3e} > {bar:.3e}"
+    return rel

@@ -135,6 +135,31 @@ def test_prefill_rejects_bad_arguments(lib):
     assert call(scale=0.0) == EINVAL
 
 
+def test_mask_bwd_rejects_bad_arguments(lib):
+    # distinct fake addresses: the outputs may not alias an input or each other
+    A = [P + 0x1000 * i for i in range(9)]
+
+    def call(q=A[0], k=A[1], v=A[2], out=A[3], lse=A[4], dout=A[5], dq=A[6], dk=A[7], dv=A[8], B=1, H=2, d=128, t=16,
+             c=4, n=2, scale=0.1, dtype=BF16, ws=P, wsb=0):
+        return lib.loma_mask_attn_bwd(q, k, v, out, lse, dout, dq, dk, dv, B, H, d, t, c, n, scale, dtype, ws, wsb, None)
+    need = lib.loma_mask_attn_bwd_workspace_bytes(1, 2, 128, 16, 4, 2, BF16)
+    assert need == 4 * 2 * 2 * 16 * 9
+    # every call below keeps the workspace too small, so even a call with good pointers stops at the host
+    assert call(wsb=need - 1) == EWS
+    assert call(ws=None, wsb=need) == EWS
+    assert call(lse=None, wsb=need) == EINVAL
+    assert call(dout=None, wsb=need) == EINVAL
+    assert call(dq=A[0], wsb=need) == EINVAL            # aliases q
+    assert call(dk=A[8], wsb=need) == EINVAL            # aliases dv
+    assert call(dv=A[5], wsb=need) == EINVAL            # aliases dout
+    assert call(k=A[1] + 2, wsb=need) == EINVAL
+    assert call(n=0, wsb=need) == EINVAL
+    assert call(scale=-1.0, wsb=need) == EINVAL
+    assert call(d=100, wsb=need) == EUNSUP and call(dtype=3, wsb=need) == EUNSUP
+    assert lib.loma_mask_attn_bwd_workspace_bytes(1, 2, 128, 16, 4, 0, BF16) == 0
+    assert lib.loma_mask_attn_bwd_workspace_bytes(1, 2, 100, 16, 4, 2, BF16) == 0
+
+
 def test_decode_workspace_bytes(lib):
     f = lib.loma_decode_workspace_bytes
     assert f(0, 32, 128, 16, 4, 4, BF16) == 0

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import check, host_bits, to_dev, to_host_f64
+from gpu_util import check, check_grad, host_bits, to_dev, to_host_f64
 from paper_2401_09486_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -347,4 +347,54 @@ def test_binding_reports_errors(loma):
         loma.loma_mask_attn_fwd(q, q, q, 4, 4, 5, 0.125)        # S != n*s
     with pytest.raises(loma.LomaError) as e:
         loma.loma_mask_attn_fwd(q, q, q, 4, 4, 4, -1.0)
+    assert e.value.status == loma.ERR_INVALID_ARG
+
+
+# ---- gradients of the mask pass ---------------------------------------------------------------------------
+def run_mask_bwd(loma, c_oracle, cfg):
+    """Forward (out, lse) and backward both through the C ABI; the oracle differentiates its own forward."""
+    print(f"[case] mask pass gradients {cfg}", flush=True)
+    q, k, v = wl.mask_inputs(cfg)
+    g = wl.mask_grad_input(cfg)
+    tq, tk, tv, tg = (to_dev(x) for x in (q, k, v, g))
+    lse = torch.empty((cfg.B, cfg.H, cfg.S), dtype=torch.float32, device="cuda")
+    out = loma.loma_mask_attn_fwd(tq, tk, tv, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, lse=lse)
+    keep = [x.clone() for x in (tq, tk, tv, out, tg)]
+    dq, dk, dv = loma.loma_mask_attn_bwd(tq, tk, tv, out, lse, tg, cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
+    torch.cuda.synchronize()
+    for a, b in zip(keep, (tq, tk, tv, out, tg)):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16)), "the backward pass wrote to an input"
+    rq, rk, rv = c_oracle.mask_attn_bwd(q, k, v, g, cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
+    for name, got, want in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+        check_grad(to_host_f64(got), want, cfg.dtype, f"{cfg.name} {name}")
+    return dq, dk, dv
+
+
+@pytest.mark.parametrize("cfg", [
+    wl.CONFIGS[0],
+    small("bwd_f32_d128_t16c2", 1, 2, 128, 16, 2, 3, dtype="f32", scale=1.0),
+    small("bwd_f32_d40_t3c3", 2, 1, 40, 3, 3, 4, dtype="f32", scale=1.0),
+    small("bwd_f32_t1c1", 1, 1, 64, 1, 1, 5, dtype="f32", scale=1.0),
+    small("bwd_bf16_d96", 1, 2, 96, 8, 2, 3),
+    small("bwd_bf16_d256", 1, 1, 256, 4, 3, 2),
+    small("bwd_f32_long_rows", 1, 1, 64, 40, 3, 3, dtype="f32", scale=1.0),   # more than 64 rows per key and keys per row
+], ids=lambda c: c.name)
+def test_mask_pass_gradients_generic_small(loma, c_oracle, cfg):
+    run_mask_bwd(loma, c_oracle, cfg)
+
+
+def test_mask_pass_gradients_need_their_workspace(loma):
+    cfg = small("bwd_ws", 1, 1, 64, 4, 2, 2, dtype="f32")
+    q, k, v = (to_dev(x) for x in wl.mask_inputs(cfg))
+    g = to_dev(wl.mask_grad_input(cfg))
+    lse = torch.empty((1, 1, cfg.S), dtype=torch.float32, device="cuda")
+    out = loma.loma_mask_attn_fwd(q, k, v, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, lse=lse)
+    need = loma.loma_mask_attn_bwd_workspace_bytes(1, 1, 64, cfg.t, cfg.c, cfg.n_chunks, torch.float32)
+    assert need == 4 * cfg.S
+    small_ws = torch.empty(need - 4, dtype=torch.uint8, device="cuda")
+    with pytest.raises(loma.LomaError) as e:
+        loma.loma_mask_attn_bwd(q, k, v, out, lse, g, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, workspace=small_ws)
+    assert e.value.status == loma.ERR_WORKSPACE
+    with pytest.raises(loma.LomaError) as e:      # an output that aliases an input
+        loma.loma_mask_attn_bwd(q, k, v, out, lse, g, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, dq=q)
     assert e.value.status == loma.ERR_INVALID_ARG
