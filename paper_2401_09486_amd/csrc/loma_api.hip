@@ -90,6 +90,9 @@ int loma_mask_attn_bwd(const void* q, const void* k, const void* v, const void* 
     if (workspace == nullptr || workspace_bytes < need || !aligned16(workspace)) return LOMA_ERR_WORKSPACE;
     const int nbh = B * H;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (loma::use_mfma_path(dtype, head_dim) && loma::mask_attn_bwd_mfma_fits(g))
+        return loma::launch_mask_attn_bwd_mfma(q, k, v, out, lse, dout, dq, dk, dv, static_cast<float*>(workspace),
+                                               nbh, head_dim, g, scale, st);
     return loma::launch_mask_attn_bwd_generic(q, k, v, out, lse, dout, dq, dk, dv, static_cast<float*>(workspace),
                                               nbh, head_dim, g, scale, dtype, st);
 }

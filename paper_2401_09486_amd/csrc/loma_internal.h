@@ -119,6 +119,11 @@ int launch_mask_attn_bwd_generic(const void* q, const void* k, const void* v, co
                                  const void* dout, void* dq, void* dk, void* dv, float* delta,
                                  int nbh, int D, const Geometry& g, float scale, int dtype, hipStream_t st);
 
+bool mask_attn_bwd_mfma_fits(const Geometry& g);
+int launch_mask_attn_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                              const void* dout, void* dq, void* dk, void* dv, float* delta,
+                              int nbh, int D, const Geometry& g, float scale, hipStream_t st);
+
 // Several new tokens against the cache: memory keys and live reading rows in full, new tokens causally.
 int launch_prefill_mfma(const void* q, const void* k_new, const void* v_new,
                         const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,

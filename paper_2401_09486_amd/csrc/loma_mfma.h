@@ -1,0 +1,102 @@
+// Device helpers shared by the MFMA kernels of libloma (gfx950): vector types, bf16 packing, the
+// half-wave and row reductions, direct HBM -> LDS loads with hand-placed waits, the transposing
+// LDS read.  Not part of the ABI.
+#pragma once
+#include "loma_internal.h"
+
+namespace loma {
+namespace mfma {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef uint16_t bf16_t;  // storage type of bf16 tensors
+
+constexpr int NO_CAUSAL = 1 << 29;
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// two floats -> packed bf16 pair, round to nearest even
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    f32x2 f = {a, b};
+    bf16x2 h = __builtin_convertvector(f, bf16x2);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+// value held by the other half-wave's lane (l ^ 32) and own value: returns max / sum over the pair
+__device__ __forceinline__ float pair_max(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pair_sum(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// sum over the CPR consecutive lanes (8 or 16) that hold one row; every lane gets the total
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+    const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false);
+    return x + __int_as_float(y);
+}
+template <int CPR>
+__device__ __forceinline__ float row_sum(float x) {
+    static_assert(CPR == 8 || CPR == 16, "lanes per row");
+    x = dpp_add<0xB1>(x);   // quad_perm [1,0,3,2]
+    x = dpp_add<0x4E>(x);   // quad_perm [2,3,0,1]
+    x = dpp_add<0x141>(x);  // row_half_mirror
+    if (CPR == 16) x = dpp_add<0x140>(x);  // row_mirror
+    return x;
+}
+
+// One wave-wide direct load: lane l's 16 bytes at `src` land at LDS byte 16*l past `lds_dst`
+// (wave-uniform).  Written as inline assembly so that the compiler does not order later LDS
+// reads of the OTHER tile buffer behind it; the waits are placed by hand (wait_direct_loads).
+__device__ __forceinline__ void direct_load_16B(const bf16_t* src, bf16_t* lds_dst) {
+    const unsigned dst = __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)(__attribute__((address_space(3))) bf16_t*)lds_dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory", "m0");
+}
+
+// a pointer every lane agrees on, moved to scalar registers
+__device__ __forceinline__ const bf16_t* uniform_ptr(const bf16_t* p) {
+    const uint64_t x = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+    return reinterpret_cast<const bf16_t*>(((uint64_t)hi << 32) | lo);
+}
+
+// all direct loads of this wave have landed in LDS (vmcnt(0); the other counters untouched)
+__device__ __forceinline__ void wait_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// all but the newest N vector-memory operations of this wave are complete
+template <int N>
+__device__ __forceinline__ void wait_direct_loads_but() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+// the tile after the current one has landed although `ahead` younger tiles (LPT loads each) are still in flight
+template <int LPT, int MAXAHEAD>
+__device__ __forceinline__ void wait_next_tile(int ahead) {
+    static_assert(MAXAHEAD <= 3 && MAXAHEAD * LPT < 64, "wait depth");
+    if (MAXAHEAD >= 3 && ahead >= 3) wait_direct_loads_but<(MAXAHEAD >= 3 ? 3 : 0) * LPT>();
+    else if (MAXAHEAD >= 2 && ahead == 2) wait_direct_loads_but<(MAXAHEAD >= 2 ? 2 : 0) * LPT>();
+    else if (MAXAHEAD >= 1 && ahead == 1) wait_direct_loads_but<LPT>();
+    else wait_direct_loads();
+}
+
+// Transposing LDS read: the 16 lanes of a group each point at 8 bytes; lane i of the group
+// receives element (i % 4) of the lanes 4e + i/4, e = 0..3.  With lane i pointing at row i/4,
+// columns 4*(i%4).., lane i ends up with column i of four consecutive rows.
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+__device__ __forceinline__ s16x4 lds_read_tr(const bf16_t* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(const_cast<bf16_t*>(p)));
+}
+
+}  // namespace mfma
+}  // namespace loma

@@ -383,6 +383,36 @@ def test_mask_pass_gradients_generic_small(loma, c_oracle, cfg):
     run_mask_bwd(loma, c_oracle, cfg)
 
 
+@pytest.mark.parametrize("cfg", [
+    small("bwd_bf16_t16c4_bm64", 1, 2, 128, 16, 4, 3),          # 2 waves: memory-key block spans 4 chunks > 3
+    small("bwd_bf16_t16c4_n9", 1, 1, 128, 16, 4, 9),            # three memory-key blocks, later chunks see all of a block
+    small("bwd_bf16_t32c8_bm128", 1, 2, 128, 32, 8, 6),         # 4 waves, one chunk's memory zone per wave
+    small("bwd_bf16_t4c4_bm32", 2, 1, 128, 4, 4, 11),           # 1 wave, 8 chunks per memory-key block
+    small("bwd_bf16_t5c7_ragged", 1, 3, 128, 5, 7, 8),          # R = 35, t = 5: nothing aligned
+    small("bwd_bf16_t24c6_ragged128", 1, 1, 128, 24, 6, 3),     # R = 144
+    small("bwd_bf16_t40c1", 1, 2, 128, 40, 1, 4),               # memory zone longer than a wave's 32 keys
+    small("bwd_bf16_t1c1", 1, 1, 128, 1, 1, 5),                 # degenerate: every zone one token
+    small("bwd_bf16_d64_t16c4", 1, 2, 64, 16, 4, 5),
+    small("bwd_bf16_d64_t32c8", 1, 1, 64, 32, 8, 3),
+    small("bwd_bf16_nbh8_xcd", 1, 8, 128, 16, 2, 6),            # B*H multiple of 8
+], ids=lambda c: c.name)
+def test_mask_pass_gradients_mfma_small(loma, c_oracle, cfg):
+    run_mask_bwd(loma, c_oracle, cfg)
+
+
+def test_mask_pass_gradients_are_deterministic(loma):
+    cfg = small("bwd_det", 1, 4, 128, 32, 4, 4)
+    q, k, v = (to_dev(x) for x in wl.mask_inputs(cfg))
+    g = to_dev(wl.mask_grad_input(cfg))
+    lse = torch.empty((cfg.B, cfg.H, cfg.S), dtype=torch.float32, device="cuda")
+    out = loma.loma_mask_attn_fwd(q, k, v, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, lse=lse)
+    a = loma.loma_mask_attn_bwd(q, k, v, out, lse, g, cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
+    b = loma.loma_mask_attn_bwd(q, k, v, out, lse, g, cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+
+
 def test_mask_pass_gradients_need_their_workspace(loma):
     cfg = small("bwd_ws", 1, 1, 64, 4, 2, 2, dtype="f32")
     q, k, v = (to_dev(x) for x in wl.mask_inputs(cfg))
