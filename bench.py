@@ -247,6 +247,25 @@ def main():
                              "useful_tflops": pflops / (pms * 1e-3) / 1e12,
                              "vs_token_by_token": gc.R * dec_ms / pms}   # time of the same tokens through loma_decode_attn / this
 
+    # ---- gradients of the mask pass (forward output and lse kept, as a training step would) --------------
+    def time_backward(cfg, q, k, v, o):
+        lse = torch.empty((cfg.B, cfg.H, cfg.S), dtype=torch.float32, device="cuda")
+        loma.loma_mask_attn_fwd(q, k, v, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, out=o, lse=lse)
+        g = randn_bf16(tuple(q.shape), gen)
+        grads = [torch.empty_like(q) for _ in range(3)]
+        wsb = torch.empty(loma.loma_mask_attn_bwd_workspace_bytes(cfg.B, cfg.H, cfg.d, cfg.t, cfg.c, cfg.n_chunks),
+                          dtype=torch.uint8, device="cuda")
+        ms = time_calls(lambda i: loma.loma_mask_attn_bwd(q, k, v, o, lse, g, cfg.t, cfg.c, cfg.n_chunks, cfg.scale,
+                                                          dq=grads[0], dk=grads[1], dv=grads[2], workspace=wsb), 10)
+        fl = 2.5 * wl.mask_pass_useful_flops(cfg)      # five products per visible pair against the forward's two
+        by = 2.0 * wl.mask_pass_bytes(cfg)             # q, k, v, out, dout in; dq, dk, dv out
+        return {"workload": cfg.name, "us_per_call": ms * 1e3, "useful_tflops": fl / (ms * 1e-3) / 1e12,
+                "frac_of_mfma_peak": fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, "useful_flops": fl,
+                "algorithmic_GBps": by / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+    if not args.no_extra:
+        result["mask_bwd"] = time_backward(mc, *mask_layers[0])
+
     # ---- the other single-GPU configurations, timed on their own ---------------------------------
     if not args.no_extra:
         del mask_layers
@@ -264,6 +283,7 @@ def main():
                                                 "achieved": fl / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TF,
                                                 "unit": "TFLOP/s", "frac": fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF,
                                                 "traffic": TRAFFIC_BYTES["long_context_mask"]}
+        result["long_context_mask_bwd"] = time_backward(c4, *sets[0])
         del sets
     if not args.no_extra and not args.no_high_ratio:
         del gen_layers

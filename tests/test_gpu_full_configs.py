@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import check, host_bits, to_dev, to_host_f64
+from gpu_util import check, check_grad, host_bits, to_dev, to_host_f64
 from paper_2401_09486_amd import workloads as wl
 from test_gpu_parity import run_generation, run_prefill
 
@@ -45,6 +45,32 @@ def test_mask_pass_full_size(loma, c_oracle, idx, stride):
     print(f"[result] {cfg.name}: {rows.size} rows x {cfg.B * cfg.H} (b,h): max abs {mx:.3e} mean abs {mean:.3e}", flush=True)
     # every output element finite, also outside the sample
     assert torch.isfinite(out.float()).all()
+
+
+@pytest.mark.parametrize("idx,npairs", [(1, 8), (3, 4)], ids=["config2_llama7b_mask", "config4_long_mask"])
+def test_mask_pass_gradients_full_size(loma, c_oracle, idx, npairs):
+    """Forward and backward at full size through the C ABI; the oracle differentiates whole (b,h) pairs
+    (a pair's gradients depend on that pair alone), sampled across the batch and the XCD interleave."""
+    cfg = wl.CONFIGS[idx]
+    print(f"[case] full-size mask pass gradients {cfg}", flush=True)
+    q, k, v = wl.mask_inputs(cfg)
+    g = wl.mask_grad_input(cfg)
+    tq, tk, tv, tg = (to_dev(x) for x in (q, k, v, g))
+    lse = torch.empty((cfg.B, cfg.H, cfg.S), dtype=torch.float32, device="cuda")
+    out = loma.loma_mask_attn_fwd(tq, tk, tv, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, lse=lse)
+    dq, dk, dv = loma.loma_mask_attn_bwd(tq, tk, tv, out, lse, tg, cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
+    torch.cuda.synchronize()
+    nbh = cfg.B * cfg.H
+    sel = sorted(set(np.linspace(0, nbh - 1, npairs).astype(int).tolist() + [1]))
+
+    def pick(x):   # [B, H, S, d] -> [1, nsel, S, d]
+        return np.ascontiguousarray(x.reshape(nbh, cfg.S, cfg.d)[sel])[None]
+
+    rq, rk, rv = c_oracle.mask_attn_bwd(pick(q), pick(k), pick(v), pick(g), cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
+    for name, got, want in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+        rel = check_grad(pick(to_host_f64(got)), want, cfg.dtype, f"{cfg.name} {name}")
+        print(f"[result] {cfg.name} {name}: {len(sel)} (b,h) pairs, all rows: scaled max err {rel:.3e}", flush=True)
+        assert torch.isfinite(got.float()).all()
 
 
 def test_generation_config3_full(loma, c_oracle):

@@ -400,6 +400,12 @@ def test_mask_pass_gradients_mfma_small(loma, c_oracle, cfg):
     run_mask_bwd(loma, c_oracle, cfg)
 
 
+@pytest.mark.parametrize("shape", random_shapes(9488, 24), ids=lambda s: "B%d_H%d_d%d_t%d_c%d_n%d" % s)
+def test_mask_pass_gradients_random_shapes(loma, c_oracle, shape):
+    B, H, d, t, c, n = shape
+    run_mask_bwd(loma, c_oracle, small("bwd_rand_%d_%d_%d" % (t, c, n), B, H, d, t, c, n + 3))
+
+
 def test_mask_pass_gradients_are_deterministic(loma):
     cfg = small("bwd_det", 1, 4, 128, 32, 4, 4)
     q, k, v = (to_dev(x) for x in wl.mask_inputs(cfg))
