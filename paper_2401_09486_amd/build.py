@@ -14,21 +14,20 @@ CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libloma.so")
 SOURCES = ("loma_api.hip", "loma_flash.hip", "loma_generic.hip", "loma_decode.hip", "loma_bwd_generic.hip",
-           "loma_flash_bwd.hip")
+           "loma_bwd_dq.hip", "loma_bwd_dkv.hip")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA accumulators stay in ordinary VGPRs (no AGPR copies around the softmax arithmetic)
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
 ]
-# forward kernels: MFMA accumulators stay in ordinary VGPRs (no AGPR copies around the softmax arithmetic).
-# The backward kernels hold more accumulators than there are VGPRs and leave the choice to the compiler.
-EXTRA_FLAGS = {src: ["-mllvm", "-amdgpu-mfma-vgpr-form=1"] for src in SOURCES if src != "loma_flash_bwd.hip"}
 
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJDIR, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(ln for ln in res.stderr.splitlines() if noise not in ln)

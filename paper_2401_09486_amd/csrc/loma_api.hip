@@ -63,7 +63,7 @@ size_t loma_mask_attn_bwd_workspace_bytes(int B, int H, int head_dim, int t, int
     if (check_common(B, H, head_dim, t, c, 1.f, dtype) != LOMA_OK || n_chunks < 1) return 0;
     const long long S = (long long)n_chunks * t * (2 * c + 1);
     if (S > (1LL << 30)) return 0;
-    return (size_t)B * H * (size_t)S * sizeof(float);
+    return (size_t)B * H * (size_t)S * 2 * sizeof(float);   // per row: dout . out and -lse * log2(e)
 }
 
 int loma_mask_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,

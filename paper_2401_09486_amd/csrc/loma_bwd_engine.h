@@ -23,9 +23,30 @@
 // free of bank conflicts.  Repetition rows see their own key only through the diagonal: that
 // term (for dQ, and the whole of dK/dV of repetition-zone keys) is added on the vector ALU when
 // the dQ rows of a repetition block leave.  Every output row has one owner: no atomics.
+#pragma once
+#include <type_traits>
+
 #include "loma_mfma.h"
 
 namespace loma {
+
+struct BwdTensors {   // all at the first row of the (b,h) sequence
+    const mfma::bf16_t *q, *k, *v, *dout;
+    const float *nl, *delta;   // per row: -lse * log2(e) and dout . out (written by the delta kernel)
+    mfma::bf16_t *dq, *dk, *dv;
+};
+
+struct BwdParams {
+    BwdTensors T;       // at sequence 0
+    int nbh, n, t, R, s;
+    int bm;             // owner rows per workgroup
+    float scale, sc;    // scale, scale * log2(e)
+};
+
+// the two passes, each in a translation unit of its own
+int launch_bwd_dq_pass(const BwdParams& P, int D, hipStream_t st);
+int launch_bwd_dkv_pass(const BwdParams& P, int D, hipStream_t st);
+
 namespace {
 
 using namespace mfma;
@@ -58,6 +79,26 @@ __device__ __forceinline__ int list_row(const RowList L, int j, int* slab_index 
     return (in0 ? L.base0 : L.base1) + a * (in0 ? L.stride0 : L.stride1) + (jj - a * slab);
 }
 
+// What a tile of 32 consecutive list entries from j0 on looks like: the row of entry j0, its range and slab,
+// and whether the 32 entries exist and are 32 consecutive rows (one range, one slab).  All wave-uniform.
+struct TileInfo {
+    int row, slab_index;
+    bool in0, contig;
+};
+__device__ __forceinline__ TileInfo tile_info(const RowList L, int nstr, int j0) {
+    TileInfo t;
+    const int j1 = j0 + 31;
+    t.in0 = j0 < L.n0;
+    const int jj = t.in0 ? j0 : j0 - L.n0;
+    const int slab = t.in0 ? L.slab0 : L.slab1;
+    const unsigned magic = t.in0 ? L.magic0 : L.magic1;
+    const int a0 = div_slab(jj, slab, magic), a1 = div_slab(jj + 31, slab, magic);
+    t.slab_index = a0;
+    t.row = (t.in0 ? L.base0 : L.base1) + a0 * (t.in0 ? L.stride0 : L.stride1) + (jj - a0 * slab);
+    t.contig = j1 < nstr && (j1 < L.n0) == t.in0 && a0 == a1;
+    return t;
+}
+
 struct BwdJob {
     RowList own;   // owner rows: entry `ooff + r` for block row r (range 0 only)
     int ooff, orows;
@@ -73,11 +114,6 @@ struct BwdJob {
     int rep;       // dQ pass on repetition rows: add the rows' own-key terms when they leave
 };
 
-struct BwdTensors {   // all at the first row of the (b,h) sequence
-    const bf16_t *q, *k, *v, *dout;
-    const float *lse, *delta;
-    bf16_t *dq, *dk, *dv;
-};
 
 template <int D>
 struct BCfg {
@@ -88,7 +124,7 @@ struct BCfg {
     static constexpr int DT = D / 32;
     static constexpr int TILE = BN * D;      // elements of one tensor's tile
     static constexpr int STAGE_BYTES = 2 * TILE * 2 + 64 * 4;   // X, Y, then 32 lse and 32 delta values
-    static constexpr int NS = 2;
+    static constexpr int NS = 4;             // tile stages: the loads run NS - 1 tiles ahead of the arithmetic
     static constexpr int FSTR = D + 4;       // row stride (floats) of the fp32 staging area rows leave through
     static constexpr int WAVE_STAGING_BYTES = 32 * FSTR * 4;
     static constexpr int smem_bytes(int nw) {
@@ -108,20 +144,52 @@ __device__ __forceinline__ void direct_load_4B(const float* src, float* lds_dst)
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(dst), "v"(src) : "memory", "m0");
 }
 
-// Direct HBM -> LDS copy of streamed tile [j0, j0 + 32): X and Y rows (entries past the list replay its
-// last row; the arithmetic masks them) and, for the dK/dV pass, the rows' lse and delta.
-template <int D, int NW, int PASS>
-__device__ __forceinline__ void request_tile(const BwdJob& J, const bf16_t* X, const bf16_t* Y, const float* lse,
-                                             const float* delta, int j0, int w, int lane, bf16_t* stage) {
-    using C = BCfg<D>;
-    constexpr int IPW = C::BN / C::RPI / NW;
+// wave-wide direct load with the row address in scalar registers and a per-lane byte offset
+__device__ __forceinline__ void direct_load_16B_at(const bf16_t* sbase, unsigned voff, bf16_t* lds_dst) {
+    const unsigned dst = __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)(__attribute__((address_space(3))) bf16_t*)lds_dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(sbase)
+                 : "memory", "m0");
+}
+
+// per-lane constants of the tile loads
+template <int D, int NW>
+struct LoadLane {
+    static constexpr int IPW = BCfg<D>::BN / BCfg<D>::RPI / NW;   // wave-wide loads per tensor and tile
     static_assert(IPW >= 1, "tile rows split over the waves");
-    const int p = lane % C::CPR;
+    unsigned off[IPW];      // byte offset of the lane's piece from the tile's first row, when the rows are consecutive
+    const float* ld;        // lanes 0..31: nl of tile row `lane`; lanes 32..63: delta of tile row `lane - 32` (tile at row 0)
+};
+
+// Direct HBM -> LDS copy of streamed tile [j0, j0 + 32): X and Y rows and, for the dK/dV pass, the rows' nl
+// and delta.  A tile of 32 consecutive rows (nearly all are) is addressed from a scalar base, no vector
+// arithmetic; otherwise every lane looks its row up (entries past the list replay its last row; the
+// arithmetic masks them).
+template <int D, int NW, int PASS>
+__device__ __forceinline__ void request_tile(const BwdJob& J, const bf16_t* X, const bf16_t* Y, const LoadLane<D, NW>& LL,
+                                             int j0, int w, int lane, bf16_t* stage) {
+    using C = BCfg<D>;
+    constexpr int IPW = LoadLane<D, NW>::IPW;
     bf16_t* Xs = stage;
     bf16_t* Ys = stage + C::TILE;
+    float* Ls = reinterpret_cast<float*>(stage + 2 * C::TILE);
+    const TileInfo ti = tile_info(J.str, J.nstr, j0);
+    if (ti.contig) {
+        const bf16_t* xb = uniform_ptr(X + (long)ti.row * D);
+        const bf16_t* yb = uniform_ptr(Y + (long)ti.row * D);
+#pragma unroll
+        for (int i = 0; i < IPW; ++i) {
+            const int rbase = (w * IPW + i) * C::RPI;   // wave-uniform
+            direct_load_16B_at(xb, LL.off[i], Xs + rbase * D);
+            direct_load_16B_at(yb, LL.off[i], Ys + rbase * D);
+        }
+        if constexpr (PASS == PASS_DKV) direct_load_4B(LL.ld + ti.row, Ls);
+        return;
+    }
+    const int p = lane % C::CPR;
 #pragma unroll
     for (int i = 0; i < IPW; ++i) {
-        const int rbase = (w * IPW + i) * C::RPI;   // wave-uniform
+        const int rbase = (w * IPW + i) * C::RPI;
         const int r = rbase + lane / C::CPR;
         const long row = list_row(J.str, min(j0 + r, J.nstr - 1));
         const int c = p ^ swz<C::CPR>(r);
@@ -131,8 +199,47 @@ __device__ __forceinline__ void request_tile(const BwdJob& J, const bf16_t* X, c
     if constexpr (PASS == PASS_DKV) {
         // every wave writes the same 64 values (keeps the waves' load counts equal)
         const long row = list_row(J.str, min(j0 + (lane & 31), J.nstr - 1));
-        direct_load_4B((lane < 32 ? lse : delta) + row, reinterpret_cast<float*>(stage + 2 * C::TILE));
+        direct_load_4B(LL.ld + (row - (lane & 31)), Ls);   // LL.ld already points at the lane's row of a tile at row 0
     }
+}
+
+// The dK/dV pass holds 2 x 64 accumulator registers next to 64 operand registers: more than the 256
+// ordinary registers of a lane, and as C++ values the compiler copies them between the register files
+// on every tile.  They therefore live in the accumulation registers a0..a127 BY NAME for the whole
+// kernel: dK^T in a[0:63], dV^T in a[64:127] (16 registers per 32 head-dim columns).  Every statement
+// below names them as clobbered, so the compiler keeps nothing of its own there across them (and, with
+// fewer than 256 ordinary registers in use, has no reason to touch them in between).  The
+// instructions are opaque to the compiler's hazard bookkeeping: consecutive MFMAs name different
+// accumulators, and settle_acc() comes before the first read of one.
+#define LOMA_ACC_REGS "a0","a1","a2","a3","a4","a5","a6","a7","a8","a9","a10","a11","a12","a13","a14","a15","a16","a17","a18","a19","a20","a21","a22","a23","a24","a25","a26","a27","a28","a29","a30","a31","a32","a33","a34","a35","a36","a37","a38","a39","a40","a41","a42","a43","a44","a45","a46","a47","a48","a49","a50","a51","a52","a53","a54","a55","a56","a57","a58","a59","a60","a61","a62","a63","a64","a65","a66","a67","a68","a69","a70","a71","a72","a73","a74","a75","a76","a77","a78","a79","a80","a81","a82","a83","a84","a85","a86","a87","a88","a89","a90","a91","a92","a93","a94","a95","a96","a97","a98","a99","a100","a101","a102","a103","a104","a105","a106","a107","a108","a109","a110","a111","a112","a113","a114","a115","a116","a117","a118","a119","a120","a121","a122","a123","a124","a125","a126","a127"
+template <int BASE>
+__device__ __forceinline__ void mfma_named(bf16x8 a, bf16x8 b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 a[%2:%3], %0, %1, a[%2:%3]" ::"v"(a), "v"(b), "n"(BASE), "n"(BASE + 15)
+                 : LOMA_ACC_REGS);
+}
+template <int I>
+__device__ __forceinline__ void zero_named() {
+    asm volatile("v_accvgpr_write_b32 a[%0], 0" ::"n"(I) : LOMA_ACC_REGS);
+}
+template <int I>
+__device__ __forceinline__ float read_named() {
+    float x;
+    asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(x) : "n"(I) : LOMA_ACC_REGS);
+    return x;
+}
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+// the last MFMA (16 passes of 4 cycles) has written its accumulator
+__device__ __forceinline__ void settle_acc() { asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory"); }
+// a[BASE .. BASE + 16 DT) -> accumulator values in the layout of the MFMA result
+template <int BASE, int DT>
+__device__ __forceinline__ void fetch_named(f32x16 (&acc)[DT]) {
+    static_for<0, 16 * DT>([&](auto i) { acc[i.value / 16][i.value % 16] = read_named<BASE + i.value>(); });
 }
 
 // fp32 accumulators (lane = owner row, registers = head-dim) times `mul` into the wave's staging area
@@ -208,7 +315,7 @@ __device__ __forceinline__ void store_staged_rep(const float* Of, const BwdTenso
         const u32x4 gg = *reinterpret_cast<const u32x4*>(T.dout + at);
         const float s = row_sum<C::CPR>(dot8(qq, kk));
         const float dw = row_sum<C::CPR>(dot8(gg, vv));
-        const float wgt = __builtin_amdgcn_exp2f(s * sc - T.lse[row] * LOG2E);
+        const float wgt = __builtin_amdgcn_exp2f(fmaf(s, sc, T.nl[row]));
         const float da = wgt * (dw - T.delta[row]);
         const float4 a = *reinterpret_cast<const float4*>(Of + r * C::FSTR + pc * 8);
         const float4 b = *reinterpret_cast<const float4*>(Of + r * C::FSTR + pc * 8 + 4);
@@ -240,7 +347,20 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
     const long orow = list_row(J.own, J.ooff + r_own);
     const int ntiles = (J.nstr + C::BN - 1) / C::BN;
 
-    if (ntiles > 0) request_tile<D, NW, PASS>(J, X, Y, T.lse, T.delta, 0, w, lane, smem);
+    LoadLane<D, NW> LL;
+#pragma unroll
+    for (int i = 0; i < LoadLane<D, NW>::IPW; ++i) {
+        const int r = (w * LoadLane<D, NW>::IPW + i) * C::RPI + lane / C::CPR;
+        LL.off[i] = 2u * (r * D + (((lane % C::CPR) ^ swz<C::CPR>(r)) * 8));
+    }
+    LL.ld = (lane < 32 ? T.nl : T.delta) + (lane & 31);
+
+    // the loads run AHEAD tiles ahead of the arithmetic
+    constexpr int AHEAD = C::NS - 1;
+    constexpr int LPT = 2 * (C::BN / C::RPI / NW) + (PASS == PASS_DKV ? 1 : 0);   // direct loads per wave and tile
+#pragma unroll
+    for (int t = 0; t < AHEAD; ++t)
+        if (t < ntiles) request_tile<D, NW, PASS>(J, X, Y, LL, t * C::BN, w, lane, smem + t * (C::STAGE_BYTES / 2));
 
     // owner rows as B operands: lane (row l32, half g) holds head-dim 16*ks + 8*g .. +7
     bf16x8 xo[C::KSTEPS], yo[C::KSTEPS];
@@ -251,7 +371,7 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
     }
     float nl_own = 0.f, dl_own = 0.f;
     if constexpr (PASS == PASS_DQ) {
-        nl_own = -T.lse[orow] * LOG2E;
+        nl_own = T.nl[orow];
         dl_own = T.delta[orow];
     }
     // who sees whom: per-lane and per-wave quantities of the job's rule
@@ -275,26 +395,25 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
     }
 
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    f32x16 accX[C::DT];                         // dQ^T (dQ pass) or dK^T (dK/dV pass)
-    f32x16 accY[PASS == PASS_DKV ? C::DT : 1];  // dV^T
+    f32x16 accX[C::DT];   // dQ^T (dQ pass; the dK/dV pass accumulates in named registers)
 #pragma unroll
     for (int dt = 0; dt < C::DT; ++dt) accX[dt] = zero16;
-#pragma unroll
-    for (int dt = 0; dt < (PASS == PASS_DKV ? C::DT : 1); ++dt) accY[dt] = zero16;
+    if constexpr (PASS == PASS_DKV) static_for<0, 128>([&](auto i) { zero_named<i.value>(); });
 
+    // The first AHEAD tiles were requested before the owner rows; one wait covers everything.  It has to
+    // be a full one: the compiler counts only the loads it issued itself (the owner rows), and would
+    // otherwise wait for them inside the loop with counts that also drain the tiles in flight.
     wait_direct_loads();
     __syncthreads();
 
     for (int kt = 0; kt < ntiles; ++kt) {
-        bf16_t* stage = smem + (kt & 1) * (C::STAGE_BYTES / 2);
-        if (kt + 1 < ntiles)
-            request_tile<D, NW, PASS>(J, X, Y, T.lse, T.delta, (kt + 1) * C::BN, w, lane,
-                                      smem + ((kt + 1) & 1) * (C::STAGE_BYTES / 2));
+        bf16_t* stage = smem + (kt % C::NS) * (C::STAGE_BYTES / 2);
+        if (kt + AHEAD < ntiles)
+            request_tile<D, NW, PASS>(J, X, Y, LL, (kt + AHEAD) * C::BN, w, lane,
+                                      smem + ((kt + AHEAD) % C::NS) * (C::STAGE_BYTES / 2));
         const int j0 = kt * C::BN, j1 = min(j0 + C::BN, J.nstr) - 1;   // first and last live streamed row
         // does this wave's 32 x 32 block hold no visible pair, only visible pairs, or both?
         bool none = !has_rows, cut = j0 + C::BN > J.nstr;
-        int z0 = 0, z1 = 0;   // VIS_MEMKEYS: chunk of the tile's first and last row
-        bool r0_first = false, r0_last = false;
         if (J.vis == VIS_CAUSAL) {
             none = none || j0 > J.cb + r_hi;
             cut = cut || j0 + C::BN - 1 > J.cb + row0;
@@ -302,29 +421,53 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
             none = none || j1 < row0;
             cut = cut || j0 < r_hi;
         } else {
-            int a0, a1;
-            list_row(J.str, j0, &a0);
-            list_row(J.str, j1, &a1);
-            r0_first = j0 < J.str.n0; r0_last = j1 < J.str.n0;
-            z0 = J.y_first + a0 + (r0_first ? 1 : 0);
-            z1 = J.y_first + a1 + (r0_last ? 1 : 0);
-            if (r0_first != r0_last || z0 != z1) cut = true;
-            else if (r0_first) { none = none || yk_lo >= z0; cut = cut || yk_hi >= z0; }
-            else { none = none || z0 < yk_lo || z0 > yk_hi; cut = cut || yk_lo != z0 || yk_hi != z0; }
+            const TileInfo ti = tile_info(J.str, J.nstr, j0);
+            const int z = J.y_first + ti.slab_index + (ti.in0 ? 1 : 0);   // chunk of the tile's rows, if it has just one
+            if (!ti.contig) cut = true;
+            else if (ti.in0) { none = none || yk_lo >= z; cut = cut || yk_hi >= z; }
+            else { none = none || z < yk_lo || z > yk_hi; cut = cut || yk_lo != z || yk_hi != z; }
         }
         if (!none) {
             const bf16_t* Xs = stage;
             const bf16_t* Ys = stage + C::TILE;
+            auto read_t = [&](const bf16_t* base, int step, int dt) -> bf16x8 {
+                const s16x4 lo = lds_read_tr(base + toff[0][dt] + 16 * step * D);
+                const s16x4 hi = lds_read_tr(base + toff[1][dt] + 16 * step * D);
+                return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            };
             // ---- S' = X xo^T, dP' = Y yo^T: accumulator i of lane (l32, g) is streamed row 8*(i/4) + 4*g + i%4 ----
+            // The LDS operands are read PF k-steps ahead of the MFMAs that use them (the scheduling
+            // barriers keep the reads from sinking back next to their uses).
             f32x16 S = zero16, dP = zero16;
+            {
+                constexpr int PF = C::KSTEPS >= 4 ? 4 : C::KSTEPS;
+                bf16x8 ax[PF], ay[PF];
 #pragma unroll
-            for (int ks = 0; ks < C::KSTEPS; ++ks) {
-                const bf16x8 ax = *reinterpret_cast<const bf16x8*>(Xs + poff[ks]);
-                const bf16x8 ay = *reinterpret_cast<const bf16x8*>(Ys + poff[ks]);
-                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax, xo[ks], S, 0, 0, 0);
-                dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ay, yo[ks], dP, 0, 0, 0);
+                for (int ks = 0; ks < PF; ++ks) {
+                    ax[ks] = *reinterpret_cast<const bf16x8*>(Xs + poff[ks]);
+                    ay[ks] = *reinterpret_cast<const bf16x8*>(Ys + poff[ks]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ks = 0; ks < C::KSTEPS; ++ks) {
+                    S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax[ks % PF], xo[ks], S, 0, 0, 0);
+                    dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ay[ks % PF], yo[ks], dP, 0, 0, 0);
+                    if (ks + PF < C::KSTEPS) {
+                        ax[ks % PF] = *reinterpret_cast<const bf16x8*>(Xs + poff[ks + PF]);
+                        ay[ks % PF] = *reinterpret_cast<const bf16x8*>(Ys + poff[ks + PF]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-            // ---- P = exp2(S' sc - lse log2 e), dS = P (dP' - delta) ----------------------------------------------
+            // the transposed operands of the first 16 streamed rows are requested before the arithmetic below
+            bf16x8 tx[2][C::DT], ty[2][PASS == PASS_DKV ? C::DT : 1];
+#pragma unroll
+            for (int dt = 0; dt < C::DT; ++dt) {
+                tx[0][dt] = read_t(Xs, 0, dt);
+                if constexpr (PASS == PASS_DKV) ty[0][dt] = read_t(Ys, 0, dt);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // ---- P = exp2(S' sc + nl), dS = P (dP' - delta) ----------------------------------------------
             if constexpr (PASS == PASS_DQ) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
@@ -340,7 +483,7 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
                     const float lsv[4] = {ls.x, ls.y, ls.z, ls.w}, dlv[4] = {dl.x, dl.y, dl.z, dl.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float p = __builtin_amdgcn_exp2f(fmaf(S[4 * a + e], sc, -lsv[e] * LOG2E));
+                        const float p = __builtin_amdgcn_exp2f(fmaf(S[4 * a + e], sc, lsv[e]));
                         S[4 * a + e] = p;
                         dP[4 * a + e] = p * (dP[4 * a + e] - dlv[e]);
                     }
@@ -371,51 +514,57 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
                 pw.w = pack_bf16(A[8 * step + 6], A[8 * step + 7]);
                 return __builtin_bit_cast(bf16x8, pw);
             };
-            auto read_t = [&](const bf16_t* base, int step, int dt) -> bf16x8 {
-                const s16x4 lo = lds_read_tr(base + toff[0][dt] + 16 * step * D);
-                const s16x4 hi = lds_read_tr(base + toff[1][dt] + 16 * step * D);
-                return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            };
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int step = 0; step < 2; ++step) {
+                if (step == 0) {
+#pragma unroll
+                    for (int dt = 0; dt < C::DT; ++dt) {
+                        tx[1][dt] = read_t(Xs, 1, dt);
+                        if constexpr (PASS == PASS_DKV) ty[1][dt] = read_t(Ys, 1, dt);
+                    }
+                }
                 const bf16x8 bds = pack8(dP, step);
                 const bf16x8 bp = pack8(S, step);
+                if constexpr (PASS == PASS_DKV) {
+                    static_for<0, C::DT>([&](auto dt) {
+                        mfma_named<16 * dt.value>(tx[step][dt.value], bds);
+                        mfma_named<64 + 16 * dt.value>(ty[step][dt.value], bp);
+                    });
+                } else {
 #pragma unroll
-                for (int dt = 0; dt < C::DT; ++dt) {
-                    accX[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t(Xs, step, dt), bds, accX[dt], 0, 0, 0);
-                    if constexpr (PASS == PASS_DKV)
-                        accY[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t(Ys, step, dt), bp, accY[dt], 0, 0, 0);
+                    for (int dt = 0; dt < C::DT; ++dt)
+                        accX[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tx[step][dt], bds, accX[dt], 0, 0, 0);
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        wait_direct_loads();
+        wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
         __syncthreads();
     }
 
     // rows leave through the wave's own fp32 staging area (the tile stages are free: the loop ended on a barrier)
     float* Of = reinterpret_cast<float*>(smem) + w * (C::WAVE_STAGING_BYTES / 4);
+    if constexpr (PASS == PASS_DKV) settle_acc();
     if (has_rows) {
-        stage_acc<D>(accX, scale, Of, lane);
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         if constexpr (PASS == PASS_DQ) {
+            stage_acc<D>(accX, scale, Of, lane);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             if (J.rep) store_staged_rep<D>(Of, T, J, row0, scale, sc, lane);
             else store_staged<D>(Of, T.dq, J, row0, lane);
         } else {
+            fetch_named<0, C::DT>(accX);
+            stage_acc<D>(accX, scale, Of, lane);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             store_staged<D>(Of, T.dk, J, row0, lane);
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            stage_acc<D>(accY, 1.f, Of, lane);
+            fetch_named<64, C::DT>(accX);
+            stage_acc<D>(accX, 1.f, Of, lane);
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             store_staged<D>(Of, T.dv, J, row0, lane);
         }
     }
 }
-
-struct BwdParams {
-    BwdTensors T;       // at sequence 0
-    int nbh, n, t, R, s;
-    int bm;             // owner rows per workgroup
-    float scale, sc;    // scale, scale * log2(e)
-};
 
 __device__ __forceinline__ void split_block(long long id, int nbh, int jobs_per_bh, int& bh, int& u) {
     // (b,h) pairs are dealt to the 8 XCDs (workgroup id % 8) so that one pair's rows stay in one L2
@@ -430,10 +579,11 @@ __device__ __forceinline__ void split_block(long long id, int nbh, int jobs_per_
     }
 }
 
+constexpr int ONE_SLAB = 1 << 30;   // slab length of a range that is a single run of rows (its magic is 0: slab index 0)
 __device__ __forceinline__ RowList one_range(int base, int n) {
     RowList L;
-    L.base0 = 0; L.n0 = 0; L.slab0 = 1; L.stride0 = 1; L.magic0 = 0;
-    L.base1 = base; L.n1 = n; L.slab1 = 1; L.stride1 = 1; L.magic1 = 0;
+    L.base0 = 0; L.n0 = 0; L.slab0 = ONE_SLAB; L.stride0 = 0; L.magic0 = 0;
+    L.base1 = base; L.n1 = n; L.slab1 = ONE_SLAB; L.stride1 = 0; L.magic1 = 0;
     return L;
 }
 __device__ __forceinline__ RowList owner_range(int base) {   // entry r of range 0 is row base + r
@@ -445,86 +595,9 @@ __device__ __forceinline__ RowList owner_range(int base) {   // entry r of range
 __device__ __forceinline__ BwdTensors at_sequence(const BwdTensors& T, long seq, int D) {
     BwdTensors U;
     U.q = T.q + seq * D; U.k = T.k + seq * D; U.v = T.v + seq * D; U.dout = T.dout + seq * D;
-    U.lse = T.lse + seq; U.delta = T.delta + seq;
+    U.nl = T.nl + seq; U.delta = T.delta + seq;
     U.dq = T.dq + seq * D; U.dk = T.dk + seq * D; U.dv = T.dv + seq * D;
     return U;
-}
-
-// dQ pass: the forward pass's blocks (one zone of one chunk, bm rows), last chunk first
-template <int D, int NW>
-__global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(BwdParams P) {
-    extern __shared__ __align__(16) bf16_t smem[];
-    const MaskSchedule sch = MaskSchedule::make(P.nbh, P.t, P.R / P.t, P.n, P.bm);
-    const MaskJob mj = sch.decode(blockIdx.x);
-    const int chunk = mj.y * P.s;
-    BwdJob J;
-    J.ooff = 0; J.orows = mj.rows;
-    J.vis = VIS_CAUSAL; J.cb = NO_CAUSAL; J.t = P.t; J.y_first = 0; J.magic_t = 0; J.rep = 0;
-    if (mj.zone == ZONE_READ) {
-        J.own = owner_range(chunk + mj.o0);
-        J.str = one_range(chunk, mj.o0 + mj.rows);
-        J.str.base0 = P.R; J.str.n0 = mj.y * P.t; J.str.slab0 = P.t; J.str.stride0 = P.s; J.str.magic0 = magic_of(P.t);
-        J.cb = J.str.n0 + mj.o0;
-    } else if (mj.zone == ZONE_MEM) {
-        J.own = owner_range(chunk + P.R + mj.o0);
-        J.str = one_range(chunk, P.R + P.t);
-    } else {
-        J.own = owner_range(chunk + P.R + P.t + mj.o0);
-        J.str = one_range(chunk + P.R, P.t);
-        J.rep = 1;
-    }
-    J.nstr = J.str.n0 + J.str.n1;
-    const BwdTensors T = at_sequence(P.T, (long)mj.bh * P.n * P.s, D);
-    bwd_job<D, NW, PASS_DQ>(J, T, P.scale, P.sc, smem);
-}
-
-// dK/dV pass: per (b,h) the blocks of memory keys (longest first: the first block is seen by every later
-// chunk), then the reading-zone key blocks of every chunk.  Repetition-zone keys belong to the dQ pass.
-template <int D, int NW>
-__global__ __launch_bounds__(64 * NW) void bwd_dkv_kernel(BwdParams P) {
-    extern __shared__ __align__(16) bf16_t smem[];
-    const int nMK = (P.n * P.t + P.bm - 1) / P.bm;    // blocks of memory keys
-    const int nRB = (P.R + P.bm - 1) / P.bm;          // reading-zone key blocks per chunk
-    int bh, u;
-    split_block(blockIdx.x, P.nbh, nMK + P.n * nRB, bh, u);
-    BwdJob J;
-    J.rep = 0; J.t = P.t; J.magic_t = magic_of(P.t); J.y_first = 0; J.cb = 0;
-    if (u < nMK) {
-        const int mk0 = u * P.bm;
-        J.vis = VIS_MEMKEYS;
-        J.ooff = mk0; J.orows = min(P.bm, P.n * P.t - mk0);
-        J.own = owner_range(P.R);
-        J.own.slab0 = P.t; J.own.stride0 = P.s; J.own.magic0 = J.magic_t;
-        const int y_first = mk0 / P.t, y_last = (mk0 + J.orows - 1) / P.t;
-        J.y_first = y_first;
-        J.str.base0 = (y_first + 1) * P.s; J.str.n0 = (P.n - 1 - y_first) * P.R;
-        J.str.slab0 = P.R; J.str.stride0 = P.s; J.str.magic0 = magic_of(P.R);
-        J.str.base1 = y_first * P.s + P.R; J.str.n1 = (y_last - y_first + 1) * (P.s - P.R);
-        J.str.slab1 = P.s - P.R; J.str.stride1 = P.s; J.str.magic1 = magic_of(P.s - P.R);
-    } else {
-        u -= nMK;
-        const int y = u / nRB, o0 = (u % nRB) * P.bm;
-        J.vis = VIS_FROM_ROW;
-        J.ooff = 0; J.orows = min(P.bm, P.R - o0);
-        J.own = owner_range(y * P.s + o0);
-        J.str = one_range(y * P.s + o0, P.R + P.t - o0);
-    }
-    J.nstr = J.str.n0 + J.str.n1;
-    const BwdTensors T = at_sequence(P.T, (long)bh * P.n * P.s, D);
-    bwd_job<D, NW, PASS_DKV>(J, T, P.scale, P.sc, smem);
-}
-
-// delta[row] = dout[row] . out[row], rows in the row layout (lane = 16-byte piece)
-template <int D>
-__global__ __launch_bounds__(256) void bwd_delta_kernel(const bf16_t* out, const bf16_t* dout, float* delta, long rows) {
-    constexpr int CPR = D / 8;
-    const long row = ((long)blockIdx.x * 256 + threadIdx.x) / CPR;
-    const int pc = threadIdx.x % CPR;
-    const long rc = row < rows ? row : rows - 1;
-    const u32x4 a = *reinterpret_cast<const u32x4*>(out + rc * D + pc * 8);
-    const u32x4 b = *reinterpret_cast<const u32x4*>(dout + rc * D + pc * 8);
-    const float s = row_sum<CPR>(dot8(a, b));
-    if (pc == 0 && row < rows) delta[row] = s;
 }
 
 template <typename K>
@@ -537,47 +610,5 @@ int launch(K kernel, long long grid, int threads, int smem_bytes, const BwdParam
     return hipGetLastError() == hipSuccess ? LOMA_OK : LOMA_ERR_LAUNCH;
 }
 
-template <int D, int NW>
-int launch_passes(const BwdParams& P, hipStream_t st) {
-    const int smem = BCfg<D>::smem_bytes(NW);
-    const long long dq_grid = MaskSchedule::make(P.nbh, P.t, P.R / P.t, P.n, P.bm).size();
-    if (int rc = launch(bwd_dq_kernel<D, NW>, dq_grid, 64 * NW, smem, P, st)) return rc;
-    const long long nMK = ((long long)P.n * P.t + P.bm - 1) / P.bm, nRB = (P.R + P.bm - 1) / P.bm;
-    return launch(bwd_dkv_kernel<D, NW>, (long long)P.nbh * (nMK + (long long)P.n * nRB), 64 * NW, smem, P, st);
-}
-
-template <int D>
-int launch_d(const BwdParams& P, const void* out, long long rows, hipStream_t st) {
-    const long long dgrid = (rows * (D / 8) + 255) / 256;
-    if (dgrid > 0x7fffffffLL) return LOMA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(bwd_delta_kernel<D>, dim3((unsigned)dgrid), dim3(256), 0, st, (const bf16_t*)out, P.T.dout,
-                       const_cast<float*>(P.T.delta), (long)rows);
-    if (hipGetLastError() != hipSuccess) return LOMA_ERR_LAUNCH;
-    if (P.bm == 128) return launch_passes<D, 4>(P, st);
-    if (P.bm == 64) return launch_passes<D, 2>(P, st);
-    return launch_passes<D, 1>(P, st);
-}
-
 }  // namespace
-
-bool mask_attn_bwd_mfma_fits(const Geometry& g) {
-    // the slab divisions by multiplication are exact while (list index) * (slab length) < 2^32
-    return (long long)g.S * g.s < (1LL << 32);
-}
-
-int launch_mask_attn_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
-                              const void* dout, void* dq, void* dk, void* dv, float* delta,
-                              int nbh, int D, const Geometry& g, float scale, hipStream_t st) {
-    BwdParams P;
-    P.T.q = (const bf16_t*)q; P.T.k = (const bf16_t*)k; P.T.v = (const bf16_t*)v; P.T.dout = (const bf16_t*)dout;
-    P.T.lse = lse; P.T.delta = delta;
-    P.T.dq = (bf16_t*)dq; P.T.dk = (bf16_t*)dk; P.T.dv = (bf16_t*)dv;
-    P.nbh = nbh; P.n = g.n; P.t = g.t; P.R = g.R; P.s = g.s;
-    P.bm = mask_block_rows(g.R);
-    P.scale = scale; P.sc = scale * LOG2E;
-    const long long rows = (long long)nbh * g.S;
-    if (D == 128) return launch_d<128>(P, out, rows, st);
-    return launch_d<64>(P, out, rows, st);
-}
-
 }  // namespace loma

@@ -114,14 +114,14 @@ int launch_decode_generic(const void* q, const void* k_new, const void* v_new,
                           void* out, int nbh, int D, int R, int n_mem_keys, int mem_capacity, int read_fill,
                           float scale, int dtype, hipStream_t st);
 
-// Gradients of the mask pass; `delta` is the caller's workspace, nbh*S floats.
+// Gradients of the mask pass; the caller's workspace holds two floats per row (the generic kernels use the first nbh*S).
 int launch_mask_attn_bwd_generic(const void* q, const void* k, const void* v, const void* out, const float* lse,
                                  const void* dout, void* dq, void* dk, void* dv, float* delta,
                                  int nbh, int D, const Geometry& g, float scale, int dtype, hipStream_t st);
 
 bool mask_attn_bwd_mfma_fits(const Geometry& g);
 int launch_mask_attn_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
-                              const void* dout, void* dq, void* dk, void* dv, float* delta,
+                              const void* dout, void* dq, void* dk, void* dv, float* workspace,
                               int nbh, int D, const Geometry& g, float scale, hipStream_t st);
 
 // Several new tokens against the cache: memory keys and live reading rows in full, new tokens causally.

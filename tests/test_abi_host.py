@@ -143,7 +143,7 @@ def test_mask_bwd_rejects_bad_arguments(lib):
              c=4, n=2, scale=0.1, dtype=BF16, ws=P, wsb=0):
         return lib.loma_mask_attn_bwd(q, k, v, out, lse, dout, dq, dk, dv, B, H, d, t, c, n, scale, dtype, ws, wsb, None)
     need = lib.loma_mask_attn_bwd_workspace_bytes(1, 2, 128, 16, 4, 2, BF16)
-    assert need == 4 * 2 * 2 * 16 * 9
+    assert need == 2 * 4 * 2 * 2 * 16 * 9            # two floats per row
     # every call below keeps the workspace too small, so even a call with good pointers stops at the host
     assert call(wsb=need - 1) == EWS
     assert call(ws=None, wsb=need) == EWS
