@@ -138,17 +138,21 @@ struct BCfg {
 template <int CPR>
 __device__ __forceinline__ int swz(int r) { return (4 * (r & 3) + ((r >> 2) & 3)) % CPR; }
 
-__device__ __forceinline__ void direct_load_4B(const float* src, float* lds_dst) {
-    const unsigned dst = __builtin_amdgcn_readfirstlane(
-        (unsigned)(size_t)(__attribute__((address_space(3))) float*)lds_dst);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(dst), "v"(src) : "memory", "m0");
+// Wave-wide direct loads HBM -> LDS.  The LDS destination is a byte address in a scalar register (taken
+// once from the shared-memory pointer: converting a pointer at every load costs a null check each time);
+// lane l's data lands at lds_addr + l * (bytes per lane).
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+    return __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) const char*)p);
 }
-
-// wave-wide direct load with the row address in scalar registers and a per-lane byte offset
-__device__ __forceinline__ void direct_load_16B_at(const bf16_t* sbase, unsigned voff, bf16_t* lds_dst) {
-    const unsigned dst = __builtin_amdgcn_readfirstlane(
-        (unsigned)(size_t)(__attribute__((address_space(3))) bf16_t*)lds_dst);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(sbase)
+__device__ __forceinline__ void direct_load_4B(const float* src, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(src) : "memory", "m0");
+}
+__device__ __forceinline__ void direct_load_16B_to(const bf16_t* src, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(src) : "memory", "m0");
+}
+// ... with the row address in scalar registers and a per-lane byte offset
+__device__ __forceinline__ void direct_load_16B_at(const bf16_t* sbase, unsigned voff, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase)
                  : "memory", "m0");
 }
 
@@ -167,23 +171,21 @@ struct LoadLane {
 // arithmetic masks them).
 template <int D, int NW, int PASS>
 __device__ __forceinline__ void request_tile(const BwdJob& J, const bf16_t* X, const bf16_t* Y, const LoadLane<D, NW>& LL,
-                                             int j0, int w, int lane, bf16_t* stage) {
+                                             int j0, int w, int lane, unsigned stage_addr) {
     using C = BCfg<D>;
     constexpr int IPW = LoadLane<D, NW>::IPW;
-    bf16_t* Xs = stage;
-    bf16_t* Ys = stage + C::TILE;
-    float* Ls = reinterpret_cast<float*>(stage + 2 * C::TILE);
+    const unsigned xs = stage_addr, ys = stage_addr + 2 * C::TILE, ls = stage_addr + 4 * C::TILE;   // LDS byte addresses
     const TileInfo ti = tile_info(J.str, J.nstr, j0);
     if (ti.contig) {
         const bf16_t* xb = uniform_ptr(X + (long)ti.row * D);
         const bf16_t* yb = uniform_ptr(Y + (long)ti.row * D);
 #pragma unroll
         for (int i = 0; i < IPW; ++i) {
-            const int rbase = (w * IPW + i) * C::RPI;   // wave-uniform
-            direct_load_16B_at(xb, LL.off[i], Xs + rbase * D);
-            direct_load_16B_at(yb, LL.off[i], Ys + rbase * D);
+            const unsigned rb = 2u * ((w * IPW + i) * C::RPI * D);   // wave-uniform
+            direct_load_16B_at(xb, LL.off[i], xs + rb);
+            direct_load_16B_at(yb, LL.off[i], ys + rb);
         }
-        if constexpr (PASS == PASS_DKV) direct_load_4B(LL.ld + ti.row, Ls);
+        if constexpr (PASS == PASS_DKV) direct_load_4B(LL.ld + ti.row, ls);
         return;
     }
     const int p = lane % C::CPR;
@@ -193,13 +195,13 @@ __device__ __forceinline__ void request_tile(const BwdJob& J, const bf16_t* X, c
         const int r = rbase + lane / C::CPR;
         const long row = list_row(J.str, min(j0 + r, J.nstr - 1));
         const int c = p ^ swz<C::CPR>(r);
-        direct_load_16B(X + row * D + c * 8, Xs + rbase * D);
-        direct_load_16B(Y + row * D + c * 8, Ys + rbase * D);
+        direct_load_16B_to(X + row * D + c * 8, xs + 2u * (rbase * D));
+        direct_load_16B_to(Y + row * D + c * 8, ys + 2u * (rbase * D));
     }
     if constexpr (PASS == PASS_DKV) {
         // every wave writes the same 64 values (keeps the waves' load counts equal)
         const long row = list_row(J.str, min(j0 + (lane & 31), J.nstr - 1));
-        direct_load_4B(LL.ld + (row - (lane & 31)), Ls);   // LL.ld already points at the lane's row of a tile at row 0
+        direct_load_4B(LL.ld + (row - (lane & 31)), ls);   // LL.ld already points at the lane's row of a tile at row 0
     }
 }
 
@@ -355,12 +357,13 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
     }
     LL.ld = (lane < 32 ? T.nl : T.delta) + (lane & 31);
 
+    const unsigned smem_addr = lds_address(smem);
     // the loads run AHEAD tiles ahead of the arithmetic
     constexpr int AHEAD = C::NS - 1;
     constexpr int LPT = 2 * (C::BN / C::RPI / NW) + (PASS == PASS_DKV ? 1 : 0);   // direct loads per wave and tile
 #pragma unroll
     for (int t = 0; t < AHEAD; ++t)
-        if (t < ntiles) request_tile<D, NW, PASS>(J, X, Y, LL, t * C::BN, w, lane, smem + t * (C::STAGE_BYTES / 2));
+        if (t < ntiles) request_tile<D, NW, PASS>(J, X, Y, LL, t * C::BN, w, lane, smem_addr + t * C::STAGE_BYTES);
 
     // owner rows as B operands: lane (row l32, half g) holds head-dim 16*ks + 8*g .. +7
     bf16x8 xo[C::KSTEPS], yo[C::KSTEPS];
@@ -410,7 +413,7 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
         bf16_t* stage = smem + (kt % C::NS) * (C::STAGE_BYTES / 2);
         if (kt + AHEAD < ntiles)
             request_tile<D, NW, PASS>(J, X, Y, LL, (kt + AHEAD) * C::BN, w, lane,
-                                      smem + ((kt + AHEAD) % C::NS) * (C::STAGE_BYTES / 2));
+                                      smem_addr + ((kt + AHEAD) % C::NS) * C::STAGE_BYTES);
         const int j0 = kt * C::BN, j1 = min(j0 + C::BN, J.nstr) - 1;   // first and last live streamed row
         // does this wave's 32 x 32 block hold no visible pair, only visible pairs, or both?
         bool none = !has_rows, cut = j0 + C::BN > J.nstr;
