@@ -284,6 +284,11 @@ def main():
                                                 "unit": "TFLOP/s", "frac": fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF,
                                                 "traffic": TRAFFIC_BYTES["long_context_mask"]}
         result["long_context_mask_bwd"] = time_backward(c4, *sets[0])
+        bw = result["long_context_mask_bwd"]
+        # its dominant kernel: the dK/dV pass (four of the seven matrix products the three launches issue)
+        result["roofline_long_context_mask_bwd"] = {"kernel": "bwd_dkv_kernel<128, 4> (+ bwd_dq_kernel<128, 4>, bwd_delta_kernel<128>)",
+                                                    "bound": "mfma", "achieved": bw["useful_tflops"], "peak": MFMA_BF16_PEAK_TF,
+                                                    "unit": "TFLOP/s", "frac": bw["frac_of_mfma_peak"], "traffic": None}
         del sets
     if not args.no_extra and not args.no_high_ratio:
         del gen_layers

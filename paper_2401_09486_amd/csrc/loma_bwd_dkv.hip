@@ -63,9 +63,9 @@ template <int D>
 int launch_dkv(const BwdParams& P, hipStream_t st) {
     const long long nMK = ((long long)P.n * P.t + P.bm - 1) / P.bm, nRB = (P.R + P.bm - 1) / P.bm;
     const long long grid = (long long)P.nbh * (nMK + (long long)P.n * nRB);
-    if (P.bm == 128) return launch(bwd_dkv_kernel<D, 4>, grid, 256, BCfg<D>::smem_bytes(4), P, st);
-    if (P.bm == 64) return launch(bwd_dkv_kernel<D, 2>, grid, 128, BCfg<D>::smem_bytes(2), P, st);
-    return launch(bwd_dkv_kernel<D, 1>, grid, 64, BCfg<D>::smem_bytes(1), P, st);
+    if (P.bm == 128) return launch(bwd_dkv_kernel<D, 4>, grid, 256, BCfg<D>::smem_bytes(4, Stages<PASS_DKV, 4>::NS), P, st);
+    if (P.bm == 64) return launch(bwd_dkv_kernel<D, 2>, grid, 128, BCfg<D>::smem_bytes(2, Stages<PASS_DKV, 2>::NS), P, st);
+    return launch(bwd_dkv_kernel<D, 1>, grid, 64, BCfg<D>::smem_bytes(1, Stages<PASS_DKV, 1>::NS), P, st);
 }
 
 template <int D>

@@ -35,9 +35,9 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(BwdParams P) {
 template <int D>
 int launch_dq(const BwdParams& P, hipStream_t st) {
     const long long grid = MaskSchedule::make(P.nbh, P.t, P.R / P.t, P.n, P.bm).size();
-    if (P.bm == 128) return launch(bwd_dq_kernel<D, 4>, grid, 256, BCfg<D>::smem_bytes(4), P, st);
-    if (P.bm == 64) return launch(bwd_dq_kernel<D, 2>, grid, 128, BCfg<D>::smem_bytes(2), P, st);
-    return launch(bwd_dq_kernel<D, 1>, grid, 64, BCfg<D>::smem_bytes(1), P, st);
+    if (P.bm == 128) return launch(bwd_dq_kernel<D, 4>, grid, 256, BCfg<D>::smem_bytes(4, Stages<PASS_DQ, 4>::NS), P, st);
+    if (P.bm == 64) return launch(bwd_dq_kernel<D, 2>, grid, 128, BCfg<D>::smem_bytes(2, Stages<PASS_DQ, 2>::NS), P, st);
+    return launch(bwd_dq_kernel<D, 1>, grid, 64, BCfg<D>::smem_bytes(1, Stages<PASS_DQ, 1>::NS), P, st);
 }
 
 }  // namespace

@@ -124,12 +124,19 @@ struct BCfg {
     static constexpr int DT = D / 32;
     static constexpr int TILE = BN * D;      // elements of one tensor's tile
     static constexpr int STAGE_BYTES = 2 * TILE * 2 + 64 * 4;   // X, Y, then 32 lse and 32 delta values
-    static constexpr int NS = 4;             // tile stages: the loads run NS - 1 tiles ahead of the arithmetic
     static constexpr int FSTR = D + 4;       // row stride (floats) of the fp32 staging area rows leave through
     static constexpr int WAVE_STAGING_BYTES = 32 * FSTR * 4;
-    static constexpr int smem_bytes(int nw) {
-        return NS * STAGE_BYTES > nw * WAVE_STAGING_BYTES ? NS * STAGE_BYTES : nw * WAVE_STAGING_BYTES;
+    static constexpr int smem_bytes(int nw, int ns) {
+        return ns * STAGE_BYTES > nw * WAVE_STAGING_BYTES ? ns * STAGE_BYTES : nw * WAVE_STAGING_BYTES;
     }
+};
+// Tile stages: the loads run NS - 1 tiles ahead of the arithmetic.  Four stages cost nothing where the
+// rows' staging area is as large anyway (4 waves) and where one workgroup per SIMD pair is all the
+// registers allow (dK/dV pass); the dQ pass with fewer waves walks short lists and would rather fit
+// more workgroups on a CU.
+template <int PASS, int NW>
+struct Stages {
+    static constexpr int NS = (PASS == 1 || NW == 4) ? 4 : 2;
 };
 
 // position of 16-byte piece c of tile row r: c ^ swz(r).  16 consecutive rows give 16 different values
@@ -359,7 +366,8 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
 
     const unsigned smem_addr = lds_address(smem);
     // the loads run AHEAD tiles ahead of the arithmetic
-    constexpr int AHEAD = C::NS - 1;
+    constexpr int NS = Stages<PASS, NW>::NS;
+    constexpr int AHEAD = NS - 1;
     constexpr int LPT = 2 * (C::BN / C::RPI / NW) + (PASS == PASS_DKV ? 1 : 0);   // direct loads per wave and tile
 #pragma unroll
     for (int t = 0; t < AHEAD; ++t)
@@ -410,10 +418,10 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
     __syncthreads();
 
     for (int kt = 0; kt < ntiles; ++kt) {
-        bf16_t* stage = smem + (kt % C::NS) * (C::STAGE_BYTES / 2);
+        bf16_t* stage = smem + (kt % NS) * (C::STAGE_BYTES / 2);
         if (kt + AHEAD < ntiles)
             request_tile<D, NW, PASS>(J, X, Y, LL, (kt + AHEAD) * C::BN, w, lane,
-                                      smem_addr + ((kt + AHEAD) % C::NS) * C::STAGE_BYTES);
+                                      smem_addr + ((kt + AHEAD) % NS) * C::STAGE_BYTES);
         const int j0 = kt * C::BN, j1 = min(j0 + C::BN, J.nstr) - 1;   // first and last live streamed row
         // does this wave's 32 x 32 block hold no visible pair, only visible pairs, or both?
         bool none = !has_rows, cut = j0 + C::BN > J.nstr;
