@@ -417,9 +417,15 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
     wait_direct_loads();
     __syncthreads();
 
+    // All waves leave the barrier together, and the two phases that read operands from LDS would then
+    // coincide in every wave, with the LDS idle in between.  Odd waves therefore request the next tile
+    // (address arithmetic, no LDS) at the END of their iteration instead of the beginning: their LDS
+    // phases fall into the others' arithmetic.  Either way the stage a request overwrites was last read
+    // in the iteration before the barrier this wave has passed, and the same loads are in flight at the wait.
+    const bool late_request = (w & 1) != 0;
     for (int kt = 0; kt < ntiles; ++kt) {
         bf16_t* stage = smem + (kt % NS) * (C::STAGE_BYTES / 2);
-        if (kt + AHEAD < ntiles)
+        if (!late_request && kt + AHEAD < ntiles)
             request_tile<D, NW, PASS>(J, X, Y, LL, (kt + AHEAD) * C::BN, w, lane,
                                       smem_addr + ((kt + AHEAD) % NS) * C::STAGE_BYTES);
         const int j0 = kt * C::BN, j1 = min(j0 + C::BN, J.nstr) - 1;   // first and last live streamed row
@@ -550,6 +556,9 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        if (late_request && kt + AHEAD < ntiles)
+            request_tile<D, NW, PASS>(J, X, Y, LL, (kt + AHEAD) * C::BN, w, lane,
+                                      smem_addr + ((kt + AHEAD) % NS) * C::STAGE_BYTES);
         wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
         __syncthreads();
     }
