@@ -431,6 +431,7 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
         const int j0 = kt * C::BN, j1 = min(j0 + C::BN, J.nstr) - 1;   // first and last live streamed row
         // does this wave's 32 x 32 block hold no visible pair, only visible pairs, or both?
         bool none = !has_rows, cut = j0 + C::BN > J.nstr;
+        bool lane_rule = false, lane_vis = true;   // VIS_MEMKEYS on a tile of one chunk: visibility is a property of the lane
         if (J.vis == VIS_CAUSAL) {
             none = none || j0 > J.cb + r_hi;
             cut = cut || j0 + C::BN - 1 > J.cb + row0;
@@ -441,8 +442,18 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
             const TileInfo ti = tile_info(J.str, J.nstr, j0);
             const int z = J.y_first + ti.slab_index + (ti.in0 ? 1 : 0);   // chunk of the tile's rows, if it has just one
             if (!ti.contig) cut = true;
-            else if (ti.in0) { none = none || yk_lo >= z; cut = cut || yk_hi >= z; }
-            else { none = none || z < yk_lo || z > yk_hi; cut = cut || yk_lo != z || yk_hi != z; }
+            else {
+                if (ti.in0) { none = none || yk_lo >= z; cut = cut || yk_hi >= z; }
+                else { none = none || z < yk_lo || z > yk_hi; cut = cut || yk_lo != z || yk_hi != z; }
+                // all 32 rows are of chunk z: whether this lane's key sees them does not depend on the row.
+                // (Only compiled into the kernels with fewer than 4 waves, whose blocks are the ones that own keys
+                // of several chunks per wave at the paper's shapes; in the 4-wave kernel the extra path costs the
+                // common case 9 % through code layout alone, measured.)
+                if constexpr (NW < 4) {
+                    lane_rule = true;
+                    lane_vis = ti.in0 ? yk < z : yk == z;
+                }
+            }
         }
         if (!none) {
             const bf16_t* Xs = stage;
@@ -506,7 +517,13 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
                     }
                 }
             }
-            if (cut) {
+            if (cut && lane_rule) {   // (a tile of consecutive rows lies inside the list: no row is past its end)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    S[i] = lane_vis ? S[i] : 0.f;
+                    dP[i] = lane_vis ? dP[i] : 0.f;
+                }
+            } else if (cut) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int j = j0 + 8 * (i >> 2) + 4 * g + (i & 3);
