@@ -92,7 +92,9 @@ int loma_mask_attn_fwd(const void* q, const void* k, const void* v, void* out, f
  * their products), fp32 throughout for f32 data.  dq, dk, dv are fully overwritten; they must not
  * alias an input.  Deterministic: every output row is summed by one owner, no atomics.
  * workspace: device scratch of at least loma_mask_attn_bwd_workspace_bytes(...) bytes (two
- * floats per row: dout . out and the rescaled lse), 16-byte aligned; contents are don't-care on entry and exit.
+ * floats per row: dout . out and the rescaled lse; for some shapes also fp32 partial sums of the
+ * memory-zone keys' dk, dv, added in a fixed order), 16-byte aligned; contents are don't-care on
+ * entry and exit; calls sharing a workspace must be stream-ordered.
  */
 int loma_mask_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
                        const void* dout, void* dq, void* dk, void* dv,

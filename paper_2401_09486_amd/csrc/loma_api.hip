@@ -63,6 +63,12 @@ size_t loma_mask_attn_bwd_workspace_bytes(int B, int H, int head_dim, int t, int
     if (check_common(B, H, head_dim, t, c, 1.f, dtype) != LOMA_OK || n_chunks < 1) return 0;
     const long long S = (long long)n_chunks * t * (2 * c + 1);
     if (S > (1LL << 30)) return 0;
+    if (loma::use_mfma_path(dtype, head_dim)) {
+        Geometry g;
+        g.t = t; g.c = c; g.n = n_chunks; g.R = t * c; g.s = t * (2 * c + 1); g.S = (int)S;
+        if (loma::mask_attn_bwd_mfma_fits(g))
+            return loma::mask_attn_bwd_mfma_workspace_floats(B * H, head_dim, g) * sizeof(float);
+    }
     return (size_t)B * H * (size_t)S * 2 * sizeof(float);   // per row: dout . out and -lse * log2(e)
 }
 

@@ -13,7 +13,8 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(BwdParams P) {
     const int chunk = mj.y * P.s;
     BwdJob J;
     J.ooff = 0; J.orows = mj.rows;
-    J.vis = VIS_CAUSAL; J.cb = NO_CAUSAL; J.t = P.t; J.y_first = 0; J.magic_t = 0; J.rep = 0;
+    J.vis = VIS_CAUSAL; J.cb = NO_CAUSAL; J.t = P.t; J.z0 = J.z1 = 0; J.magic_t = 0; J.rep = 0;
+    J.part_k = J.part_v = nullptr;
     if (mj.zone == ZONE_READ) {
         J.own = owner_range(chunk + mj.o0);
         J.str = one_range(chunk, mj.o0 + mj.rows);

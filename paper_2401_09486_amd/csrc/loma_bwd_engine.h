@@ -40,6 +40,8 @@ struct BwdParams {
     BwdTensors T;       // at sequence 0
     int nbh, n, t, R, s;
     int bm;             // owner rows per workgroup
+    int split;          // workgroups that share the stream of one block of memory keys in the dK/dV pass (1 or 2)
+    float* partials;    // split > 1: fp32 [nbh][split][2 (dK, dV)][n*t][head_dim]
     float scale, sc;    // scale, scale * log2(e)
 };
 
@@ -107,11 +109,14 @@ struct BwdJob {
     int vis;       // which rule decides whether streamed row j and owner row r interact
     int cb;        // VIS_CAUSAL: j <= cb + r.   VIS_FROM_ROW: j >= r.
     // VIS_MEMKEYS: owner r is memory key ooff + r of chunk yk = (ooff + r) / t; streamed row j of range 0
-    // is a reading row of chunk y_first + 1 + slab index (visible iff yk < that chunk), of range 1 a memory
-    // or repetition row of chunk y_first + slab index (visible iff yk == that chunk)
-    int t, y_first;
+    // is a reading row of chunk z0 + slab index (visible iff yk < that chunk), of range 1 a memory
+    // or repetition row of chunk z1 + slab index (visible iff yk == that chunk)
+    int t, z0, z1;
     unsigned magic_t;
     int rep;       // dQ pass on repetition rows: add the rows' own-key terms when they leave
+    // dK/dV pass of a block whose stream is shared out over several workgroups: fp32 partial sums, row
+    // `ooff + r` of each (nullptr: the block is whole and writes dk, dv itself)
+    float *part_k, *part_v;
 };
 
 
@@ -286,6 +291,22 @@ __device__ __forceinline__ void store_staged(const float* Of, bf16_t* dst, const
     }
 }
 
+// staged rows -> fp32 rows `J.ooff + row` of a partial-sum buffer
+template <int D>
+__device__ __forceinline__ void store_staged_partial(const float* Of, float* dst, const BwdJob& J, int row0, int lane) {
+    using C = BCfg<D>;
+    const int rl = lane / C::CPR, pc = lane % C::CPR;
+#pragma unroll
+    for (int i = 0; i < 32 / C::RPI; ++i) {
+        const int r = i * C::RPI + rl;
+        if (row0 + r < J.orows) {
+            float* at = dst + (long)(J.ooff + row0 + r) * D + pc * 8;
+            *reinterpret_cast<float4*>(at) = *reinterpret_cast<const float4*>(Of + r * C::FSTR + pc * 8);
+            *reinterpret_cast<float4*>(at + 4) = *reinterpret_cast<const float4*>(Of + r * C::FSTR + pc * 8 + 4);
+        }
+    }
+}
+
 __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {   // a, b: bf16 pairs
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
 }
@@ -440,7 +461,7 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
             cut = cut || j0 < r_hi;
         } else {
             const TileInfo ti = tile_info(J.str, J.nstr, j0);
-            const int z = J.y_first + ti.slab_index + (ti.in0 ? 1 : 0);   // chunk of the tile's rows, if it has just one
+            const int z = (ti.in0 ? J.z0 : J.z1) + ti.slab_index;   // chunk of the tile's rows, if it has just one
             if (!ti.contig) cut = true;
             else {
                 if (ti.in0) { none = none || yk_lo >= z; cut = cut || yk_hi >= z; }
@@ -533,7 +554,7 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
                     else {
                         int a;
                         list_row(J.str, min(j, J.nstr - 1), &a);
-                        vis = vis && (j < J.str.n0 ? yk < J.y_first + 1 + a : yk == J.y_first + a);
+                        vis = vis && (j < J.str.n0 ? yk < J.z0 + a : yk == J.z1 + a);
                     }
                     S[i] = vis ? S[i] : 0.f;
                     dP[i] = vis ? dP[i] : 0.f;
@@ -593,12 +614,14 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
             fetch_named<0, C::DT>(accX);
             stage_acc<D>(accX, scale, Of, lane);
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            store_staged<D>(Of, T.dk, J, row0, lane);
+            if (J.part_k) store_staged_partial<D>(Of, J.part_k, J, row0, lane);
+            else store_staged<D>(Of, T.dk, J, row0, lane);
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             fetch_named<64, C::DT>(accX);
             stage_acc<D>(accX, 1.f, Of, lane);
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            store_staged<D>(Of, T.dv, J, row0, lane);
+            if (J.part_v) store_staged_partial<D>(Of, J.part_v, J, row0, lane);
+            else store_staged<D>(Of, T.dv, J, row0, lane);
         }
     }
 }

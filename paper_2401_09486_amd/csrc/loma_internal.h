@@ -120,6 +120,7 @@ int launch_mask_attn_bwd_generic(const void* q, const void* k, const void* v, co
                                  int nbh, int D, const Geometry& g, float scale, int dtype, hipStream_t st);
 
 bool mask_attn_bwd_mfma_fits(const Geometry& g);
+size_t mask_attn_bwd_mfma_workspace_floats(int nbh, int D, const Geometry& g);   // what `workspace` below must hold
 int launch_mask_attn_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
                               const void* dout, void* dq, void* dk, void* dv, float* workspace,
                               int nbh, int D, const Geometry& g, float scale, hipStream_t st);
