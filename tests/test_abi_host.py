@@ -156,6 +156,12 @@ def test_mask_bwd_rejects_bad_arguments(lib):
     assert call(n=0, wsb=need) == EINVAL
     assert call(scale=-1.0, wsb=need) == EINVAL
     assert call(d=100, wsb=need) == EUNSUP and call(dtype=3, wsb=need) == EUNSUP
+    # the Llama-shaped training configuration shares its memory-key streams out over two workgroups and needs room
+    # for their fp32 partial sums; the long-context one is balanced without and needs the two floats per row only
+    rows2, rows4 = 2 * 32 * 28 * 16 * 9, 32 * 60 * 32 * 17
+    assert lib.loma_mask_attn_bwd_workspace_bytes(2, 32, 128, 16, 4, 28, BF16) == 8 * rows2 + 4 * (64 * 2 * 2 * 28 * 16 * 128)
+    assert lib.loma_mask_attn_bwd_workspace_bytes(1, 32, 128, 32, 8, 60, BF16) == 8 * rows4
+    assert lib.loma_mask_attn_bwd_workspace_bytes(2, 32, 128, 16, 4, 28, F32) == 8 * rows2     # generic kernels
     assert lib.loma_mask_attn_bwd_workspace_bytes(1, 2, 128, 16, 4, 0, BF16) == 0
     assert lib.loma_mask_attn_bwd_workspace_bytes(1, 2, 100, 16, 4, 2, BF16) == 0
 
