@@ -115,8 +115,8 @@ def cpu_baseline(wl, layers):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (every (b,h) is independent; see DESIGN.md for how the "
-              "path would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (every (b,h) pair is independent, so the path would shard over "
+              "batch or heads without any exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2401_09486_amd import loma
