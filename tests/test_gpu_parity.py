@@ -395,6 +395,9 @@ def test_mask_pass_gradients_generic_small(loma, c_oracle, cfg):
     small("bwd_bf16_d64_t16c4", 1, 2, 64, 16, 4, 5),
     small("bwd_bf16_d64_t32c8", 1, 1, 64, 32, 8, 3),
     small("bwd_bf16_nbh8_xcd", 1, 8, 128, 16, 2, 6),            # B*H multiple of 8
+    small("bwd_bf16_one_chunk", 1, 2, 128, 32, 8, 1),           # a single chunk: no memory key is seen from outside its chunk
+    small("bwd_bf16_one_chunk_t16", 2, 1, 64, 16, 4, 1),
+    small("bwd_bf16_t32c8_n9_split", 1, 1, 128, 32, 8, 9),      # 4 waves, memory-key streams shared by two workgroups
 ], ids=lambda c: c.name)
 def test_mask_pass_gradients_mfma_small(loma, c_oracle, cfg):
     run_mask_bwd(loma, c_oracle, cfg)
