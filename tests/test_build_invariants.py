@@ -1,0 +1,32 @@
+"""Properties of the compiled gfx950 code that the kernels rely on and the compiler does not promise.
+
+The dK/dV pass of the gradient kernels keeps its accumulators in the accumulation registers a0..a127 by name,
+inside inline assembly.  That is only sound while the compiler allocates no accumulation register of its own
+in those kernels (it would be free to use one between two of the assembly statements).  The check compiles the
+translation unit to assembly (device side only, no GPU needed) and reads the register counts from the kernel
+metadata: exactly the 128 named registers, no scratch memory.
+"""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"), reason="hipcc not available")
+def test_dkv_kernels_use_only_the_named_accumulation_registers(tmp_path):
+    from paper_2401_09486_amd import build as hip_build
+    src = os.path.join(hip_build.CSRC, "loma_bwd_dkv.hip")
+    out = str(tmp_path / "dkv.s")
+    cmd = [hip_build.HIPCC, *hip_build.FLAGS, "--cuda-device-only", "-S", src, "-o", out]
+    subprocess.run(cmd, check=True, capture_output=True)
+    text = open(out).read()
+    kernels = re.findall(r"\.agpr_count:\s+(\d+).*?\.name:\s+(\S+).*?\.private_segment_fixed_size:\s+(\d+)", text, flags=re.S)
+    dkv = [(name, int(agpr), int(scratch)) for agpr, name, scratch in kernels if "bwd_dkv_kernel" in name]
+    assert len(dkv) == 6, [k[0] for k in dkv]           # head_dim 64 and 128, 1, 2 and 4 waves
+    for name, agpr, scratch in dkv:
+        assert agpr == 128, f"{name}: {agpr} accumulation registers allocated; the kernel names a0..a127 and relies on no others"
+        assert scratch == 0, f"{name}: {scratch} bytes of scratch memory"
