@@ -285,8 +285,8 @@ def main():
                                                 "traffic": TRAFFIC_BYTES["long_context_mask"]}
         result["long_context_mask_bwd"] = time_backward(c4, *sets[0])
         bw = result["long_context_mask_bwd"]
-        # its dominant kernel: the dK/dV pass (four of the seven matrix products the three launches issue)
-        result["roofline_long_context_mask_bwd"] = {"kernel": "bwd_dkv_kernel<128, 4> (+ bwd_dq_kernel<128, 4>, bwd_delta_kernel<128>)",
+        # its dominant kernel: the dK/dV pass (four of the seven matrix products the two launches issue)
+        result["roofline_long_context_mask_bwd"] = {"kernel": "bwd_dkv_kernel<128, 4> (+ bwd_dq_kernel<128, 4>)",
                                                     "bound": "mfma", "achieved": bw["useful_tflops"], "peak": MFMA_BF16_PEAK_TF,
                                                     "unit": "TFLOP/s", "frac": bw["frac_of_mfma_peak"], "traffic": None}
         del sets

@@ -1,5 +1,5 @@
-// dK/dV pass of the mask pass's gradients on the matrix cores (engine and notation: loma_bwd_engine.h),
-// the per-row delta that both passes read, and the entry that runs all three.
+// dK/dV pass of the mask pass's gradients on the matrix cores (engine and notation: loma_bwd_engine.h), the sum of
+// shared blocks' partial results, and the entry that runs the passes.
 #include "loma_bwd_engine.h"
 
 namespace loma {
@@ -82,24 +82,6 @@ __global__ __launch_bounds__(256) void bwd_reduce_kernel(BwdParams P) {
     *reinterpret_cast<uint4*>(P.T.dv + row * D + pc * 8) = ov;
 }
 
-// Per row: delta = dout . out and nl = -lse * log2(e) (the form the exp2 of the passes wants); rows in the
-// row layout (lane = 16-byte piece).
-template <int D>
-__global__ __launch_bounds__(256) void bwd_delta_kernel(const bf16_t* out, const bf16_t* dout, const float* lse,
-                                                        float* delta, float* nl, long rows) {
-    constexpr int CPR = D / 8;
-    const long row = ((long)blockIdx.x * 256 + threadIdx.x) / CPR;
-    const int pc = threadIdx.x % CPR;
-    const long rc = row < rows ? row : rows - 1;
-    const u32x4 a = *reinterpret_cast<const u32x4*>(out + rc * D + pc * 8);
-    const u32x4 b = *reinterpret_cast<const u32x4*>(dout + rc * D + pc * 8);
-    const float s = row_sum<CPR>(dot8(a, b));
-    if (pc == 0 && row < rows) {
-        delta[row] = s;
-        nl[row] = -lse[row] * LOG2E;
-    }
-}
-
 template <int D>
 int launch_dkv(const BwdParams& P, hipStream_t st) {
     const long long nmk = (long long)P.n * P.t;
@@ -111,15 +93,6 @@ int launch_dkv(const BwdParams& P, hipStream_t st) {
     else rc = launch(bwd_dkv_kernel<D, 1>, grid, 64, BCfg<D>::smem_bytes(1, Stages<PASS_DKV, 1>::NS), P, st);
     if (rc != LOMA_OK || P.split == 1) return rc;
     return launch(bwd_reduce_kernel<D>, ((long long)P.nbh * nmk * (D / 8) + 255) / 256, 256, 0, P, st);
-}
-
-template <int D>
-int launch_delta(const void* out, const float* lse, const BwdParams& P, long long rows, hipStream_t st) {
-    const long long grid = (rows * (D / 8) + 255) / 256;
-    if (grid > 0x7fffffffLL) return LOMA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(bwd_delta_kernel<D>, dim3((unsigned)grid), dim3(256), 0, st, (const bf16_t*)out, P.T.dout, lse,
-                       const_cast<float*>(P.T.delta), const_cast<float*>(P.T.nl), (long)rows);
-    return hipGetLastError() == hipSuccess ? LOMA_OK : LOMA_ERR_LAUNCH;
 }
 
 }  // namespace
@@ -165,6 +138,7 @@ int launch_mask_attn_bwd_mfma(const void* q, const void* k, const void* v, const
                               int nbh, int D, const Geometry& g, float scale, hipStream_t st) {
     BwdParams P;
     P.T.q = (const bf16_t*)q; P.T.k = (const bf16_t*)k; P.T.v = (const bf16_t*)v; P.T.dout = (const bf16_t*)dout;
+    P.T.out = (const bf16_t*)out; P.T.lse = lse;
     P.T.dq = (bf16_t*)dq; P.T.dk = (bf16_t*)dk; P.T.dv = (bf16_t*)dv;
     P.nbh = nbh; P.n = g.n; P.t = g.t; P.R = g.R; P.s = g.s;
     P.bm = mask_block_rows(g.R);
@@ -173,7 +147,6 @@ int launch_mask_attn_bwd_mfma(const void* q, const void* k, const void* v, const
     P.T.delta = workspace; P.T.nl = workspace + rows;   // two floats per row, then the partial sums
     P.split = mask_attn_bwd_stream_split(nbh, g);
     P.partials = workspace + 2 * rows;
-    if (int rc = D == 128 ? launch_delta<128>(out, lse, P, rows, st) : launch_delta<64>(out, lse, P, rows, st)) return rc;
     if (int rc = launch_bwd_dq_pass(P, D, st)) return rc;
     return launch_bwd_dkv_pass(P, D, st);
 }

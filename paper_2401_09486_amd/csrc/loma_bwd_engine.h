@@ -31,8 +31,10 @@
 namespace loma {
 
 struct BwdTensors {   // all at the first row of the (b,h) sequence
-    const mfma::bf16_t *q, *k, *v, *dout;
-    const float *nl, *delta;   // per row: -lse * log2(e) and dout . out (written by the delta kernel)
+    const mfma::bf16_t *q, *k, *v, *dout, *out;
+    const float* lse;
+    float *nl, *delta;   // per row: -lse * log2(e) and dout . out; written by the dQ pass (every row is an owner row
+                         // of exactly one of its blocks), read by the dK/dV pass
     mfma::bf16_t *dq, *dk, *dv;
 };
 
@@ -343,10 +345,12 @@ __device__ __forceinline__ void store_staged_rep(const float* Of, const BwdTenso
         const u32x4 kk = *reinterpret_cast<const u32x4*>(T.k + at);
         const u32x4 vv = *reinterpret_cast<const u32x4*>(T.v + at);
         const u32x4 gg = *reinterpret_cast<const u32x4*>(T.dout + at);
+        const u32x4 oo = *reinterpret_cast<const u32x4*>(T.out + at);
         const float s = row_sum<C::CPR>(dot8(qq, kk));
         const float dw = row_sum<C::CPR>(dot8(gg, vv));
-        const float wgt = __builtin_amdgcn_exp2f(fmaf(s, sc, T.nl[row]));
-        const float da = wgt * (dw - T.delta[row]);
+        const float delta = row_sum<C::CPR>(dot8(gg, oo));   // (formed again here: other lanes hold the prologue's copy)
+        const float wgt = __builtin_amdgcn_exp2f(fmaf(s, sc, -T.lse[row] * LOG2E));
+        const float da = wgt * (dw - delta);
         const float4 a = *reinterpret_cast<const float4*>(Of + r * C::FSTR + pc * 8);
         const float4 b = *reinterpret_cast<const float4*>(Of + r * C::FSTR + pc * 8 + 4);
         const float4 z = {0.f, 0.f, 0.f, 0.f};
@@ -403,8 +407,20 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
     }
     float nl_own = 0.f, dl_own = 0.f;
     if constexpr (PASS == PASS_DQ) {
-        nl_own = T.nl[orow];
-        dl_own = T.delta[orow];
+        // delta = dout . out of the owner row (half of the head-dim in each of the lanes l and l ^ 32) and the lse in
+        // the form the exp2 below wants; both also go to the workspace for the dK/dV pass
+        float part = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < C::KSTEPS; ++ks) {
+            const u32x4 oo = *reinterpret_cast<const u32x4*>(T.out + orow * D + 16 * ks + 8 * g);
+            part += dot8(oo, __builtin_bit_cast(u32x4, yo[ks]));
+        }
+        dl_own = pair_sum(part);
+        nl_own = -T.lse[orow] * LOG2E;
+        if (g == 0 && row0 + l32 < J.orows) {
+            T.delta[orow] = dl_own;
+            T.nl[orow] = nl_own;
+        }
     }
     // who sees whom: per-lane and per-wave quantities of the job's rule
     const int yk = J.vis == VIS_MEMKEYS ? div_slab(J.ooff + r_own, J.t, J.magic_t) : 0;
@@ -654,8 +670,8 @@ __device__ __forceinline__ RowList owner_range(int base) {   // entry r of range
 
 __device__ __forceinline__ BwdTensors at_sequence(const BwdTensors& T, long seq, int D) {
     BwdTensors U;
-    U.q = T.q + seq * D; U.k = T.k + seq * D; U.v = T.v + seq * D; U.dout = T.dout + seq * D;
-    U.nl = T.nl + seq; U.delta = T.delta + seq;
+    U.q = T.q + seq * D; U.k = T.k + seq * D; U.v = T.v + seq * D; U.dout = T.dout + seq * D; U.out = T.out + seq * D;
+    U.lse = T.lse + seq; U.nl = T.nl + seq; U.delta = T.delta + seq;
     U.dq = T.dq + seq * D; U.dk = T.dk + seq * D; U.dv = T.dv + seq * D;
     return U;
 }
