@@ -33,7 +33,10 @@ MFMA_BF16_PEAK_TF = 2500.0  # MI355X dense bf16
 # the factors being what the same counters read for 1 GiB device copies: --copy-calibration).  Counters cannot be
 # read from inside a timed run, so these are the figures of the committed profile, not of this process.
 TRAFFIC_BYTES = {"decode": (2.0 * 68783.5 + 192) * 1024, "mask": (2.0 * 114529 + 64512) * 1024,
-                 "long_context_mask": (2.0 * 508406 + 261120) * 1024}
+                 "long_context_mask": (2.0 * 508406 + 261120) * 1024,
+                 # gradients: dQ pass + dK/dV pass (+ the sum of shared blocks at the Llama shape)
+                 "mask_bwd": (2.0 * (228791.1 + 119580.9 + 28695.9) + 123949.5 + 114688 + 14336) * 1024,
+                 "long_context_mask_bwd": (2.0 * (948240.5 + 1288200.7) + 515043.2 + 276480) * 1024}
 
 
 def parse():
@@ -265,6 +268,10 @@ def main():
 
     if not args.no_extra:
         result["mask_bwd"] = time_backward(mc, *mask_layers[0])
+        b2 = result["mask_bwd"]
+        result["roofline_mask_bwd"] = {"kernel": "bwd_dkv_kernel<128, 2> (+ bwd_dq_kernel<128, 2>, bwd_reduce_kernel<128>)", "bound": "hbm",
+                                       "achieved": b2["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                       "frac": b2["frac_of_hbm_peak"], "traffic": TRAFFIC_BYTES["mask_bwd"]}
 
     # ---- the other single-GPU configurations, timed on their own ---------------------------------
     if not args.no_extra:
@@ -288,7 +295,8 @@ def main():
         # its dominant kernel: the dK/dV pass (four of the seven matrix products the two launches issue)
         result["roofline_long_context_mask_bwd"] = {"kernel": "bwd_dkv_kernel<128, 4> (+ bwd_dq_kernel<128, 4>)",
                                                     "bound": "mfma", "achieved": bw["useful_tflops"], "peak": MFMA_BF16_PEAK_TF,
-                                                    "unit": "TFLOP/s", "frac": bw["frac_of_mfma_peak"], "traffic": None}
+                                                    "unit": "TFLOP/s", "frac": bw["frac_of_mfma_peak"],
+                                                    "traffic": TRAFFIC_BYTES["long_context_mask_bwd"]}
         del sets
     if not args.no_extra and not args.no_high_ratio:
         del gen_layers
