@@ -127,10 +127,13 @@ int mask_attn_bwd_stream_split(int nbh, const Geometry& g) {
     return (g.n >= 4 && longest * slots * 100 > total * 115) ? 2 : 1;
 }
 
+// floats ahead of the partial sums: two per row, rounded up so that the partial sums start 16-byte aligned
+inline size_t per_row_floats(size_t rows) { return (2 * rows + 3) / 4 * 4; }
+
 size_t mask_attn_bwd_mfma_workspace_floats(int nbh, int D, const Geometry& g) {
     const size_t rows = (size_t)nbh * g.S;
     const int split = mask_attn_bwd_stream_split(nbh, g);
-    return 2 * rows + (split > 1 ? (size_t)nbh * split * 2 * (size_t)g.n * g.t * D : 0);
+    return split > 1 ? per_row_floats(rows) + (size_t)nbh * split * 2 * (size_t)g.n * g.t * D : 2 * rows;
 }
 
 int launch_mask_attn_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
@@ -146,7 +149,7 @@ int launch_mask_attn_bwd_mfma(const void* q, const void* k, const void* v, const
     const long long rows = (long long)nbh * g.S;
     P.T.delta = workspace; P.T.nl = workspace + rows;   // two floats per row, then the partial sums
     P.split = mask_attn_bwd_stream_split(nbh, g);
-    P.partials = workspace + 2 * rows;
+    P.partials = workspace + per_row_floats((size_t)rows);
     if (int rc = launch_bwd_dq_pass(P, D, st)) return rc;
     return launch_bwd_dkv_pass(P, D, st);
 }
