@@ -30,7 +30,13 @@
  *     done on the host before anything is enqueued; on error nothing was launched
  *     (LOMA_ERR_LAUNCH excepted, which reports a failed hipLaunch).
  *   - A masked (query, key) pair is excluded from the softmax: its weight is exactly
- *     0 and its K/V values never influence the result (Eq. 8-9).
+ *     0 (Eq. 8-9).  K/V rows that no row of a workgroup's block may see are never loaded,
+ *     whatever they hold (NaN and Inf included).  One precondition: the reading-zone rows
+ *     that FOLLOW a reading row inside the same block of 32..128 rows share that block's
+ *     causal diagonal tiles, which the matrix cores multiply whole; there the hidden pair
+ *     contributes 0 * V, which is 0 only for finite V.  K and V must therefore be finite
+ *     wherever some row of the sample can see them (any finite value leaves the hidden
+ *     rows' results bit-identical).
  */
 #ifndef LOMA_H_
 #define LOMA_H_
@@ -154,6 +160,29 @@ int loma_decode_attn(const void* q, const void* k_new, const void* v_new,
                      int n_mem_chunks, int mem_capacity, int read_fill,
                      float scale, int dtype,
                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The decode step for n_layers independent caches of one shape in ONE launch (Sec. 3.1 steps 1
+ * and 3 applied to every layer's cache of a model: the per-token cost the method is after is the
+ * sum over the layers, and at small batch a launch per layer costs as much as the step itself).
+ * Every tensor argument of loma_decode_attn becomes a DEVICE array of n_layers device pointers
+ * (8-byte aligned; entry l points at layer l's tensor, laid out as there; the arrays and the
+ * tensors are caller-owned and not checked on the host); k_new and v_new are both arrays or
+ * both NULL; k_memcache/v_memcache may be NULL when n_mem_chunks == 0.  B, H, head_dim, t, c and
+ * the cache state (n_mem_chunks, mem_capacity, read_fill) are shared by the layers.  Layer l's
+ * result and its appended K/V row are bit-identical to a loma_decode_attn call on its tensors.
+ * workspace: at least loma_decode_layers_workspace_bytes(...) bytes (n_layers blocks of the
+ * single-call size).  bf16 with head_dim 64 or 128 only (else LOMA_ERR_UNSUPPORTED).
+ */
+int loma_decode_attn_layers(const void* const* q, const void* const* k_new, const void* const* v_new,
+                            const void* const* k_memcache, const void* const* v_memcache,
+                            void* const* k_read, void* const* v_read, void* const* out,
+                            int n_layers, int B, int H, int head_dim, int t, int c,
+                            int n_mem_chunks, int mem_capacity, int read_fill,
+                            float scale, int dtype,
+                            void* workspace, size_t workspace_bytes, void* stream);
+size_t loma_decode_layers_workspace_bytes(int n_layers, int B, int H, int head_dim, int t, int c,
+                                          int n_mem_chunks, int dtype);
 
 /*
  * Generation form, several new tokens per sequence at once: a prompt or a piece of one

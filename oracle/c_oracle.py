@@ -38,7 +38,7 @@ def _load():
         I, D, L = ctypes.c_int, ctypes.c_double, ctypes.c_long
         lib.loma_oracle_mask_attn.argtypes = [vp, vp, vp, dp, dp, I, I, I, I, I, I, D, I, ip, I, I]
         lib.loma_oracle_mask_attn.restype = I
-        lib.loma_oracle_attend_segments.argtypes = [vp, I, vp, vp, L, I, vp, vp, L, I, dp,
+        lib.loma_oracle_attend_segments.argtypes = [vp, I, vp, vp, L, I, vp, vp, L, I, dp, dp,
                                                     I, I, I, D, I, ip, I, I]
         lib.loma_oracle_attend_segments.restype = I
         lib.loma_oracle_mask_attn_bwd.argtypes = [vp, vp, vp, vp, dp, dp, dp, I, I, I, I, I, I, D, I, I]
@@ -102,9 +102,10 @@ def mask_attn_bwd(q, k, v, dout, t, c, n_chunks, scale, nthreads=0):
     return dq, dk, dv
 
 
-def attend_segments(q, k1, v1, n1, k2, v2, n2, scale, bh_list=None, nthreads=0):
+def attend_segments(q, k1, v1, n1, k2, v2, n2, scale, bh_list=None, nthreads=0, return_lse=False):
     """All-visible attention of q [B, H, Lq, d] over rows [0, n1) of k1/v1 [B, H, cap1, d]
-    followed by rows [0, n2) of k2/v2 [B, H, cap2, d].  Returns fp64 [nbh, Lq, d]."""
+    followed by rows [0, n2) of k2/v2 [B, H, cap2, d].  Returns fp64 [nbh, Lq, d] (and, with
+    return_lse, the log-sum-exp of the scaled scores, fp64 [nbh, Lq])."""
     q = np.ascontiguousarray(q)
     code = _dtype_code(q)
     B, H, Lq, d = q.shape
@@ -123,13 +124,14 @@ def attend_segments(q, k1, v1, n1, k2, v2, n2, scale, bh_list=None, nthreads=0):
         bh_arr = np.ascontiguousarray(bh_list, dtype=np.int32)
         nbh = bh_arr.size
     out = np.empty((nbh, Lq, d), dtype=np.float64)
+    lse = np.empty((nbh, Lq), dtype=np.float64) if return_lse else None
     rc = _load().loma_oracle_attend_segments(
         _ptr(q), Lq, _ptr(k1) if n1 > 0 else None, _ptr(v1) if n1 > 0 else None, s1, n1,
         _ptr(k2) if n2 > 0 else None, _ptr(v2) if n2 > 0 else None, s2, n2,
-        _ptr(out), B, H, d, float(scale), code, _ptr(bh_arr), nbh, nthreads)
+        _ptr(out), _ptr(lse), B, H, d, float(scale), code, _ptr(bh_arr), nbh, nthreads)
     if rc != 0:
         raise RuntimeError("loma_oracle_attend_segments failed")
-    return out
+    return (out, lse) if return_lse else out
 
 
 class GenerationCache:
@@ -153,8 +155,10 @@ class GenerationCache:
         self.k_read[:, :, self.read_fill] = k_new[:, :, 0]
         self.v_read[:, :, self.read_fill] = v_new[:, :, 0]
         self.read_fill += 1
-        return attend_segments(q, self.k_mem, self.v_mem, self.n_mem_chunks * self.t,
-                               self.k_read, self.v_read, self.read_fill, self.scale, bh_list)
+        out, self.last_lse = attend_segments(q, self.k_mem, self.v_mem, self.n_mem_chunks * self.t,
+                                             self.k_read, self.v_read, self.read_fill, self.scale, bh_list,
+                                             return_lse=True)
+        return out
 
     def prefill(self, q, k_new, v_new, bh_list=None):
         """l tokens at once (Appendix A, several input tokens): token i sees the cache and new tokens
@@ -162,7 +166,11 @@ class GenerationCache:
         l = q.shape[2]
         if l < 1 or self.read_fill + l > self.R:
             raise ValueError("the new tokens must fit the reading zone")
-        outs = [self.decode(q[:, :, i:i + 1], k_new[:, :, i:i + 1], v_new[:, :, i:i + 1], bh_list) for i in range(l)]
+        outs, lses = [], []
+        for i in range(l):
+            outs.append(self.decode(q[:, :, i:i + 1], k_new[:, :, i:i + 1], v_new[:, :, i:i + 1], bh_list))
+            lses.append(self.last_lse)
+        self.last_lse = np.concatenate(lses, axis=1)      # [nbh, l]: one value per new token
         return np.concatenate(outs, axis=2)
 
     def compress(self, q_m, k_m, v_m, bh_list=None):

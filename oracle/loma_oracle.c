@@ -227,12 +227,14 @@ int loma_oracle_mask_attn_bwd(const void* q, const void* k, const void* v, const
  * decode:   Lq = 1, segment1 = memory cache (n1 = n_mem_chunks*t), segment2 = reading zone
  *           INCLUDING the new token (n2 = fill).
  * compress: Lq = t, segment1 = reading zone (n1 = t*c), segment2 = the <m> tokens' own K/V (n2 = t).
- * bh_list: optional subset of (b*H + h) indices (NULL = all); out: [nbh, Lq, d] fp64.
+ * bh_list: optional subset of (b*H + h) indices (NULL = all); out: [nbh, Lq, d] fp64;
+ * lse (optional, may be NULL): [nbh, Lq] fp64, log of the softmax denominator of Eq. 7 taken over the
+ * scaled scores: max + log(sum exp(score - max)).
  */
 int loma_oracle_attend_segments(const void* q, int Lq,
                                 const void* k1, const void* v1, long stride1, int n1,
                                 const void* k2, const void* v2, long stride2, int n2,
-                                double* out, int B, int H, int d, double scale, int dtype,
+                                double* out, double* lse, int B, int H, int d, double scale, int dtype,
                                 const int* bh_list, int nbh, int nthreads) {
     if (!q || !out || B < 1 || H < 1 || d < 1 || Lq < 1 || n1 < 0 || n2 < 0 || n1 + n2 < 1) return -1;
     if ((n1 > 0 && (!k1 || !v1 || stride1 < n1)) || (n2 > 0 && (!k2 || !v2 || stride2 < n2))) return -1;
@@ -277,6 +279,7 @@ int loma_oracle_attend_segments(const void* q, int Lq,
                         const double w = scores[j] / den;
                         for (int e = 0; e < d; ++e) o[e] += w * krow[e];
                     }
+                    if (lse) lse[(size_t)i * Lq + r] = mx + log(den);
                 }
             }
         }

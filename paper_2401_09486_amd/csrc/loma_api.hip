@@ -54,7 +54,7 @@ int loma_mask_attn_fwd(const void* q, const void* k, const void* v, void* out, f
     g.S = (int)S;
     const int nbh = B * H;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (loma::use_mfma_path(dtype, head_dim))
+    if (loma::use_mfma_path(dtype, head_dim) && loma::mask_attn_mfma_fits(g))
         return loma::launch_mask_attn_mfma(q, k, v, out, lse, nbh, head_dim, g, scale, st);
     return loma::launch_mask_attn_generic(q, k, v, out, lse, nbh, head_dim, g, scale, dtype, st);
 }
@@ -132,23 +132,38 @@ size_t loma_decode_workspace_bytes(int B, int H, int head_dim, int t, int c, int
     return loma::decode_workspace_bytes(B * H, head_dim, (int)nmax);
 }
 
-int loma_decode_attn(const void* q, const void* k_new, const void* v_new,
+}  // extern "C" (reopened below)
+
+namespace {
+
+// Argument checks shared by the forms of the decode step (everything except the tensors' own pointers).
+int check_decode_state(int B, int H, int head_dim, int t, int c, int n_mem_chunks, int mem_capacity, int read_fill,
+                       bool has_new, float scale, int dtype, long long* n_mem_keys) {
+    if (int rc = check_common(B, H, head_dim, t, c, scale, dtype)) return rc;
+    const int R = t * c;
+    if (n_mem_chunks < 0 || mem_capacity < 0 || read_fill < 0) return LOMA_ERR_INVALID_ARG;
+    *n_mem_keys = (long long)n_mem_chunks * t;
+    if (*n_mem_keys > mem_capacity) return LOMA_ERR_INVALID_ARG;
+    // Appendix A keeps the reading zone shorter than t*c whenever a token is fed
+    if (has_new ? read_fill >= R : read_fill > R) return LOMA_ERR_INVALID_ARG;
+    if (*n_mem_keys + read_fill + (has_new ? 1 : 0) < 1) return LOMA_ERR_INVALID_ARG;
+    return LOMA_OK;
+}
+
+int decode_attn_impl(const void* q, const void* k_new, const void* v_new,
                      const void* k_memcache, const void* v_memcache,
                      void* k_read, void* v_read, void* out,
                      int B, int H, int head_dim, int t, int c,
                      int n_mem_chunks, int mem_capacity, int read_fill,
                      float scale, int dtype,
                      void* workspace, size_t workspace_bytes, void* stream) {
-    if (int rc = check_common(B, H, head_dim, t, c, scale, dtype)) return rc;
-    const int R = t * c;
-    if (n_mem_chunks < 0 || mem_capacity < 0 || read_fill < 0) return LOMA_ERR_INVALID_ARG;
-    const long long n_mem_keys = (long long)n_mem_chunks * t;
-    if (n_mem_keys > mem_capacity) return LOMA_ERR_INVALID_ARG;
     if ((k_new == nullptr) != (v_new == nullptr)) return LOMA_ERR_INVALID_ARG;
     const bool has_new = k_new != nullptr;
-    // Appendix A keeps the reading zone shorter than t*c whenever a token is fed
-    if (has_new ? read_fill >= R : read_fill > R) return LOMA_ERR_INVALID_ARG;
-    if (n_mem_keys + read_fill + (has_new ? 1 : 0) < 1) return LOMA_ERR_INVALID_ARG;
+    long long n_mem_keys = 0;
+    if (int rc = check_decode_state(B, H, head_dim, t, c, n_mem_chunks, mem_capacity, read_fill, has_new, scale, dtype,
+                                    &n_mem_keys))
+        return rc;
+    const int R = t * c;
     if (!good_ptr(q) || !good_ptr(out) || !good_ptr(k_read) || !good_ptr(v_read)) return LOMA_ERR_INVALID_ARG;
     if (has_new && (!aligned16(k_new) || !aligned16(v_new))) return LOMA_ERR_INVALID_ARG;
     if (n_mem_chunks > 0 && (!good_ptr(k_memcache) || !good_ptr(v_memcache))) return LOMA_ERR_INVALID_ARG;
@@ -156,15 +171,68 @@ int loma_decode_attn(const void* q, const void* k_new, const void* v_new,
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (loma::use_mfma_path(dtype, head_dim)) {
         const size_t need = loma::decode_workspace_bytes(nbh, head_dim, (int)n_mem_keys + R);
-        if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned16(workspace)))
-            return LOMA_ERR_WORKSPACE;
         if (nbh > 65535) return LOMA_ERR_UNSUPPORTED;
+        if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned16(workspace))) {
+            return LOMA_ERR_WORKSPACE;
+        }
         return loma::launch_decode_splitk(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, nbh,
                                           head_dim, R, (int)n_mem_keys, mem_capacity, read_fill, scale,
                                           need > 0 ? workspace : nullptr, st);
     }
     return loma::launch_decode_generic(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, nbh,
                                        head_dim, R, (int)n_mem_keys, mem_capacity, read_fill, scale, dtype, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int loma_decode_attn(const void* q, const void* k_new, const void* v_new,
+                     const void* k_memcache, const void* v_memcache,
+                     void* k_read, void* v_read, void* out,
+                     int B, int H, int head_dim, int t, int c,
+                     int n_mem_chunks, int mem_capacity, int read_fill,
+                     float scale, int dtype,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+    return decode_attn_impl(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, B, H, head_dim, t, c,
+                            n_mem_chunks, mem_capacity, read_fill, scale, dtype, workspace, workspace_bytes, stream);
+}
+
+size_t loma_decode_layers_workspace_bytes(int n_layers, int B, int H, int head_dim, int t, int c,
+                                          int n_mem_chunks, int dtype) {
+    if (n_layers < 1) return 0;
+    return (size_t)n_layers * loma_decode_workspace_bytes(B, H, head_dim, t, c, n_mem_chunks, dtype);
+}
+
+int loma_decode_attn_layers(const void* const* q, const void* const* k_new, const void* const* v_new,
+                            const void* const* k_memcache, const void* const* v_memcache,
+                            void* const* k_read, void* const* v_read, void* const* out,
+                            int n_layers, int B, int H, int head_dim, int t, int c,
+                            int n_mem_chunks, int mem_capacity, int read_fill,
+                            float scale, int dtype,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    if (n_layers < 1) return LOMA_ERR_INVALID_ARG;
+    if ((k_new == nullptr) != (v_new == nullptr)) return LOMA_ERR_INVALID_ARG;
+    const bool has_new = k_new != nullptr;
+    long long n_mem_keys = 0;
+    if (int rc = check_decode_state(B, H, head_dim, t, c, n_mem_chunks, mem_capacity, read_fill, has_new, scale, dtype,
+                                    &n_mem_keys))
+        return rc;
+    auto good_table = [](const void* p) { return p != nullptr && (reinterpret_cast<uintptr_t>(p) & 7u) == 0; };
+    if (!good_table(q) || !good_table(out) || !good_table(k_read) || !good_table(v_read)) return LOMA_ERR_INVALID_ARG;
+    if (has_new && (!good_table(k_new) || !good_table(v_new))) return LOMA_ERR_INVALID_ARG;
+    if (n_mem_chunks > 0 && (!good_table(k_memcache) || !good_table(v_memcache))) return LOMA_ERR_INVALID_ARG;
+    if (!loma::use_mfma_path(dtype, head_dim)) return LOMA_ERR_UNSUPPORTED;
+    const int nbh = B * H, R = t * c;
+    if (nbh > 65535 || n_layers > 65535) return LOMA_ERR_UNSUPPORTED;
+    const size_t need = (size_t)n_layers * loma::decode_workspace_bytes(nbh, head_dim, (int)n_mem_keys + R);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned16(workspace))) return LOMA_ERR_WORKSPACE;
+    const void* const* tables[8] = {q, k_new, v_new, k_memcache, v_memcache,
+                                    const_cast<const void* const*>(k_read), const_cast<const void* const*>(v_read),
+                                    const_cast<const void* const*>(out)};
+    return loma::launch_decode_splitk_layers(tables, has_new, n_layers, nbh, head_dim, R, (int)n_mem_keys, mem_capacity,
+                                             read_fill, scale, need > 0 ? workspace : nullptr,
+                                             static_cast<hipStream_t>(stream));
 }
 
 int loma_prefill_attn(const void* q, const void* k_new, const void* v_new,
@@ -195,6 +263,11 @@ int loma_prefill_attn(const void* q, const void* k_new, const void* v_new,
 long long loma_mask_schedule_size(int B, int H, int head_dim, int t, int c, int n_chunks, int dtype) {
     if (check_common(B, H, head_dim, t, c, 1.f, dtype) != LOMA_OK || n_chunks < 1) return 0;
     if (!loma::use_mfma_path(dtype, head_dim)) return 0;
+    const long long S = (long long)n_chunks * t * (2 * c + 1);
+    if (S > (1LL << 30)) return 0;
+    Geometry g;
+    g.t = t; g.c = c; g.n = n_chunks; g.R = t * c; g.s = t * (2 * c + 1); g.S = (int)S;
+    if (!loma::mask_attn_mfma_fits(g)) return 0;
     return loma::MaskSchedule::make(B * H, t, c, n_chunks, loma::mask_block_rows(t * c)).size();
 }
 

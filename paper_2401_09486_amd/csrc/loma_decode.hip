@@ -31,9 +31,23 @@ constexpr int DEC_SMALL_NBH = 1024;    // below: 16-wave workgroups, ~1 per CU; 
 constexpr int DEC_TARGET_WGS_16 = 256;
 constexpr int DEC_TARGET_WGS_4 = 4096;
 
+// Pointer tables of the layered form: one device pointer per layer and tensor, read by the kernel.
+struct LayerTables {
+    const bf16_t* const* q;
+    const bf16_t* const* k_new;
+    const bf16_t* const* v_new;
+    const bf16_t* const* k_mem;
+    const bf16_t* const* v_mem;
+    bf16_t* const* k_read;
+    bf16_t* const* v_read;
+    bf16_t* const* out;
+};
+
 struct DecodeParams {
     const bf16_t *q, *k_new, *v_new, *k_mem, *v_mem;
     bf16_t *k_read, *v_read, *out;
+    LayerTables tab;     // layered form only
+    long ws_layer_floats;   // floats of workspace per layer (layered form)
     float* ws_acc;   // [nbh * nsplit, D]
     float* ws_ml;    // [nbh * nsplit, 2]
     long mem_rows;   // mem_capacity
@@ -69,7 +83,9 @@ __device__ __forceinline__ float row_sum(float x) {
     return x;
 }
 
-template <int D, int DEC_WAVES>
+// LAYERED: blockIdx.z is a layer; its eight tensors come from the pointer tables, everything else (shapes,
+// cache state, split plan) is shared by the layers, so a layer's result is computed exactly as by a call of its own.
+template <int D, int DEC_WAVES, bool LAYERED>
 __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodeParams P) {
     constexpr int LPR = D / 8;            // lanes per key row
     constexpr int RPL = 64 / LPR;         // rows per wave-wide load
@@ -84,6 +100,18 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodePara
     const int kbeg = sp * P.keys_per_split;
     const int kend = min(P.L, kbeg + P.keys_per_split);
 
+    if constexpr (LAYERED) {
+        const int layer = blockIdx.z;
+        P.q = P.tab.q[layer];
+        P.k_new = P.has_new ? P.tab.k_new[layer] : nullptr;
+        P.v_new = P.has_new ? P.tab.v_new[layer] : nullptr;
+        P.k_mem = P.n_mem > 0 ? P.tab.k_mem[layer] : nullptr;
+        P.v_mem = P.n_mem > 0 ? P.tab.v_mem[layer] : nullptr;
+        P.k_read = P.tab.k_read[layer];
+        P.v_read = P.tab.v_read[layer];
+        P.out = P.tab.out[layer];
+        if (P.ws_acc != nullptr) { P.ws_acc += layer * P.ws_layer_floats; P.ws_ml += layer * P.ws_layer_floats; }
+    }
     const bf16_t* kmem = P.k_mem + bh * P.mem_rows * D;
     const bf16_t* vmem = P.v_mem + bh * P.mem_rows * D;
     const bf16_t* kread = P.k_read + bh * (long)P.R * D;
@@ -195,10 +223,16 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodePara
     }
 }
 
-template <int D>
+template <int D, bool LAYERED>
 __global__ __launch_bounds__(D) void decode_combine_kernel(DecodeParams P) {
     const long bh = blockIdx.x;
     const int tid = threadIdx.x;
+    if constexpr (LAYERED) {
+        const int layer = blockIdx.y;
+        P.out = P.tab.out[layer];
+        P.ws_acc += layer * P.ws_layer_floats;
+        P.ws_ml += layer * P.ws_layer_floats;
+    }
     float M = -INFINITY;
     for (int sp = 0; sp < P.nsplit; ++sp) M = fmaxf(M, P.ws_ml[(bh * P.nsplit + sp) * 2]);
     float Lsum = 0.f, o = 0.f;
@@ -228,19 +262,20 @@ void plan_splits(int nbh, int D, int n_keys, int& nsplit, int& keys_per_split) {
     keys_per_split = ups * kpi;
 }
 
-template <int D>
-int launch_decode_d(DecodeParams& P, int nbh, void* workspace, hipStream_t st) {
+template <int D, bool LAYERED>
+int launch_decode_d(DecodeParams& P, int nbh, int n_layers, void* workspace, hipStream_t st) {
     plan_splits(nbh, D, P.L, P.nsplit, P.keys_per_split);
     P.ws_acc = static_cast<float*>(workspace);
     P.ws_ml = P.ws_acc ? P.ws_acc + (size_t)nbh * target_splits(nbh) * D : nullptr;
-    if (nbh > 65535) return LOMA_ERR_UNSUPPORTED;
+    P.ws_layer_floats = (long)nbh * target_splits(nbh) * (D + 2);
+    if (nbh > 65535 || n_layers > 65535) return LOMA_ERR_UNSUPPORTED;
     if (wg_waves(nbh) == 16)
-        hipLaunchKernelGGL((decode_split_kernel<D, 16>), dim3(P.nsplit, nbh), dim3(1024), 0, st, P);
+        hipLaunchKernelGGL((decode_split_kernel<D, 16, LAYERED>), dim3(P.nsplit, nbh, n_layers), dim3(1024), 0, st, P);
     else
-        hipLaunchKernelGGL((decode_split_kernel<D, 4>), dim3(P.nsplit, nbh), dim3(256), 0, st, P);
+        hipLaunchKernelGGL((decode_split_kernel<D, 4, LAYERED>), dim3(P.nsplit, nbh, n_layers), dim3(256), 0, st, P);
     if (hipGetLastError() != hipSuccess) return LOMA_ERR_LAUNCH;
     if (P.nsplit > 1) {
-        hipLaunchKernelGGL(decode_combine_kernel<D>, dim3(nbh), dim3(D), 0, st, P);
+        hipLaunchKernelGGL((decode_combine_kernel<D, LAYERED>), dim3(nbh, n_layers), dim3(D), 0, st, P);
         if (hipGetLastError() != hipSuccess) return LOMA_ERR_LAUNCH;
     }
     return LOMA_OK;
@@ -264,7 +299,7 @@ int launch_decode_splitk(const void* q, const void* k_new, const void* v_new,
                          const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
                          void* out, int nbh, int D, int R, int n_mem_keys, int mem_capacity, int read_fill,
                          float scale, void* workspace, hipStream_t st) {
-    DecodeParams P;
+    DecodeParams P = {};
     P.q = static_cast<const bf16_t*>(q);
     P.k_new = static_cast<const bf16_t*>(k_new); P.v_new = static_cast<const bf16_t*>(v_new);
     P.k_mem = static_cast<const bf16_t*>(k_memcache); P.v_mem = static_cast<const bf16_t*>(v_memcache);
@@ -274,7 +309,28 @@ int launch_decode_splitk(const void* q, const void* k_new, const void* v_new,
     P.has_new = k_new != nullptr;
     P.L = n_mem_keys + read_fill + (P.has_new ? 1 : 0);
     P.sc = scale * LOG2E;
-    return D == 128 ? launch_decode_d<128>(P, nbh, workspace, st) : launch_decode_d<64>(P, nbh, workspace, st);
+    return D == 128 ? launch_decode_d<128, false>(P, nbh, 1, workspace, st)
+                    : launch_decode_d<64, false>(P, nbh, 1, workspace, st);
+}
+
+int launch_decode_splitk_layers(const void* const* tables[8], bool has_new, int n_layers, int nbh, int D, int R,
+                                int n_mem_keys, int mem_capacity, int read_fill, float scale, void* workspace,
+                                hipStream_t st) {
+    DecodeParams P = {};
+    P.tab.q = reinterpret_cast<const bf16_t* const*>(tables[0]);
+    P.tab.k_new = reinterpret_cast<const bf16_t* const*>(tables[1]);
+    P.tab.v_new = reinterpret_cast<const bf16_t* const*>(tables[2]);
+    P.tab.k_mem = reinterpret_cast<const bf16_t* const*>(tables[3]);
+    P.tab.v_mem = reinterpret_cast<const bf16_t* const*>(tables[4]);
+    P.tab.k_read = (bf16_t* const*)(tables[5]);
+    P.tab.v_read = (bf16_t* const*)(tables[6]);
+    P.tab.out = (bf16_t* const*)(tables[7]);
+    P.mem_rows = mem_capacity; P.R = R; P.n_mem = n_mem_keys; P.n_read = read_fill;
+    P.has_new = has_new;
+    P.L = n_mem_keys + read_fill + (has_new ? 1 : 0);
+    P.sc = scale * LOG2E;
+    return D == 128 ? launch_decode_d<128, true>(P, nbh, n_layers, workspace, st)
+                    : launch_decode_d<64, true>(P, nbh, n_layers, workspace, st);
 }
 
 }  // namespace loma

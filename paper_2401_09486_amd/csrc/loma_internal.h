@@ -95,6 +95,12 @@ inline bool use_mfma_path(int dtype, int head_dim) {
     return dtype == LOMA_BF16 && (head_dim == 64 || head_dim == 128);
 }
 
+// The MFMA mask-pass kernels find the chunk of memory key j (j < (n-1)*t) with a multiply-high by
+// floor(2^32 / t) + 1, which is exact only while j * t < 2^32; longer samples take the generic kernels.
+inline bool mask_attn_mfma_fits(const Geometry& g) {
+    return (unsigned long long)(g.n - 1) * (unsigned long long)g.t * (unsigned long long)g.t < (1ULL << 32);
+}
+
 // ---- launchers (each returns LOMA_OK or LOMA_ERR_LAUNCH) -----------------------------------
 int launch_mask_attn_mfma(const void* q, const void* k, const void* v, void* out, float* lse,
                           int nbh, int D, const Geometry& g, float scale, hipStream_t st);
@@ -142,5 +148,12 @@ int launch_decode_splitk(const void* q, const void* k_new, const void* v_new,
                          const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
                          void* out, int nbh, int D, int R, int n_mem_keys, int mem_capacity, int read_fill,
                          float scale, void* workspace, hipStream_t st);
+
+// The same for n_layers independent caches in ONE launch: tables[i] is a DEVICE array of n_layers device pointers
+// (q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out); shapes and cache state are shared by the layers.
+// The workspace holds n_layers blocks of decode_workspace_bytes() each.
+int launch_decode_splitk_layers(const void* const* tables[8], bool has_new, int n_layers, int nbh, int D, int R,
+                                int n_mem_keys, int mem_capacity, int read_fill, float scale, void* workspace,
+                                hipStream_t st);
 
 }  // namespace loma

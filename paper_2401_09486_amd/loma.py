@@ -46,6 +46,10 @@ def _load() -> ctypes.CDLL:
     lib.loma_compress_step.restype = I
     lib.loma_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, F, I, vp, Z, vp]
     lib.loma_decode_attn.restype = I
+    lib.loma_decode_attn_layers.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, I, F, I, vp, Z, vp]
+    lib.loma_decode_attn_layers.restype = I
+    lib.loma_decode_layers_workspace_bytes.argtypes = [I, I, I, I, I, I, I, I]
+    lib.loma_decode_layers_workspace_bytes.restype = Z
     lib.loma_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, I, F, I, vp]
     lib.loma_prefill_attn.restype = I
     lib.loma_decode_workspace_bytes.argtypes = [I, I, I, I, I, I, I]
@@ -193,6 +197,38 @@ def loma_decode_attn(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, t,
     if rc != OK:
         raise LomaError(rc, "loma_decode_attn")
     return out
+
+
+def pointer_table(tensors) -> torch.Tensor:
+    """Device array of the tensors' device addresses (what the layered entry points take per argument)."""
+    for x in tensors:
+        if not x.is_cuda or not x.is_contiguous():
+            raise ValueError("layer tensors must be contiguous GPU tensors")
+    return torch.tensor([x.data_ptr() for x in tensors], dtype=torch.int64, device=tensors[0].device)
+
+
+def loma_decode_layers_workspace_bytes(n_layers, B, H, d, t, c, n_mem_chunks, dtype=torch.bfloat16) -> int:
+    code = F32 if dtype == torch.float32 else BF16
+    return int(lib.loma_decode_layers_workspace_bytes(n_layers, B, H, d, t, c, n_mem_chunks, code))
+
+
+def loma_decode_attn_layers(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, n_layers, B, H, d, t, c,
+                            n_mem_chunks, mem_capacity, read_fill, scale, dtype=torch.bfloat16, workspace=None,
+                            stream=None):
+    """One decode step on n_layers caches in one launch.  The first eight arguments are pointer tables
+    (pointer_table(list of that argument's per-layer tensors), or None where loma_decode_attn allows it)."""
+    tabs = []
+    for name, tab in (("q", q), ("k_new", k_new), ("v_new", v_new), ("k_memcache", k_memcache),
+                      ("v_memcache", v_memcache), ("k_read", k_read), ("v_read", v_read), ("out", out)):
+        tabs.append(None if tab is None else _dev(tab, name, (n_layers,), torch.int64))
+    pws, nws = None, 0
+    if workspace is not None:
+        pws, nws = _dev(workspace, "workspace"), workspace.numel() * workspace.element_size()
+    code = F32 if dtype == torch.float32 else BF16
+    rc = lib.loma_decode_attn_layers(*tabs, n_layers, B, H, d, t, c, n_mem_chunks, mem_capacity, read_fill,
+                                     float(scale), code, pws, nws, _stream(stream))
+    if rc != OK:
+        raise LomaError(rc, "loma_decode_attn_layers")
 
 
 def loma_prefill_attn(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, t, c, n_mem_chunks, read_fill, scale,

@@ -44,19 +44,22 @@ def check(got: np.ndarray, want: np.ndarray, dtype: str, what: str = ""):
 
 
 def check_grad(got: np.ndarray, want: np.ndarray, dtype: str, what: str = ""):
-    """Gradients are sums over many rows and are not bounded by the value range as the outputs are, so
-    the bar scales with the value: fp32 data |err| <= 1e-5 (1 + |want|); bf16 data
-    |err| <= 2e-2 (1 + |want|) and mean |err| <= 2e-3 (1 + mean |want|) -- the output bar at magnitude
-    <= 1, and a few bf16 roundings (2^-9 each: weights, score gradients, result) above it."""
+    """The bar of the outputs, applied to the gradients as it stands: fp32 data max |err| <= 1e-5 max(1, |want|)
+    (fp32 rounding is relative); bf16 data max |err| <= 2e-2 and mean |err| <= 2e-3, absolute.  Gradients are sums
+    over many rows, returned in the storage dtype (bf16 rounds at 2^-9 |value|), so the absolute bar only holds
+    while |value| stays in the single digits: with unit-normal upstream gradients and the configurations' input
+    scales it does (max |value| 4.5 at the long-context shape); the magnitudes are printed with the errors."""
     assert got.shape == want.shape, (got.shape, want.shape)
     assert np.isfinite(got).all(), f"{what}: non-finite gradient"
     err = np.abs(got - want)
     mag = np.abs(want)
-    rel = float((err / (1.0 + mag)).max())
+    mx, mean = float(err.max()), float(err.mean())
+    print(f"[grad] {what}: max abs err {mx:.3e} mean abs err {mean:.3e} max|ref| {float(mag.max()):.3e} "
+          f"mean|ref| {float(mag.mean()):.3e}", flush=True)
     if dtype == "f32":
-        assert rel <= F32_MAX, f"{what}: scaled max err {rel:.3e} > {F32_MAX}"
+        rel = float((err / np.maximum(1.0, mag)).max())
+        assert rel <= F32_MAX, f"{what}: max err {rel:.3e} (relative above 1) > {F32_MAX}"
     else:
-        assert rel <= BF16_MAX, f"{what}: scaled max err {rel:.3e} > {BF16_MAX}"
-        mean, bar = float(err.mean()), BF16_MEAN * (1.0 + float(mag.mean()))
-        assert mean <= bar, f"{what}: mean abs err {mean:.3e} > {bar:.3e}"
-    return rel
+        assert mx <= BF16_MAX, f"{what}: max abs err {mx:.3e} > {BF16_MAX}"
+        assert mean <= BF16_MEAN, f"{what}: mean abs err {mean:.3e} > {BF16_MEAN}"
+    return mx

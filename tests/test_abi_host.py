@@ -213,3 +213,32 @@ def test_schedule_size_zero_for_shapes_on_the_generic_path(lib):
     assert lib.loma_mask_schedule_size(1, 1, 64, 4, 4, 4, F32) == 0
     assert lib.loma_mask_schedule_size(1, 1, 96, 4, 4, 4, BF16) == 0
     assert lib.loma_mask_schedule_size(2, 32, 128, 16, 4, 28, BF16) == 2 * 32 * 28 * 3
+
+
+def test_mask_pass_dispatch_respects_the_division_bound(lib):
+    """The MFMA kernels divide a memory-key index by t with a multiply-high that is exact while
+    (n_chunks - 1) * t * t < 2^32; a longer sample must not take them (it takes the generic kernels)."""
+    assert lib.loma_mask_schedule_size(1, 1, 128, 4096, 1, 256, BF16) > 0     # 255 * 4096^2 < 2^32
+    assert lib.loma_mask_schedule_size(1, 1, 128, 4096, 1, 258, BF16) == 0    # 257 * 4096^2 >= 2^32, S = 3.2M still allowed
+
+
+def test_new_decode_forms_reject_bad_arguments(lib):
+    def layers_call(**kw):
+        a = dict(q=P, kn=P, vn=P, kc=P, vc=P, kr=P, vr=P, out=P, L=4, B=1, H=8, d=128, t=16, c=4, nmem=4, cap=64,
+                 fill=3, scale=0.1, dtype=BF16, ws=P, wsb=1 << 30)
+        a.update(kw)
+        return lib.loma_decode_attn_layers(a["q"], a["kn"], a["vn"], a["kc"], a["vc"], a["kr"], a["vr"], a["out"], a["L"],
+                                           a["B"], a["H"], a["d"], a["t"], a["c"], a["nmem"], a["cap"], a["fill"],
+                                           a["scale"], a["dtype"], a["ws"], a["wsb"], None)
+    assert layers_call(L=0) == EINVAL
+    assert layers_call(q=None) == EINVAL
+    assert layers_call(kr=P + 4) == EINVAL            # a pointer table must be 8-byte aligned
+    assert layers_call(kn=None) == EINVAL             # k_new without v_new
+    assert layers_call(kc=None) == EINVAL             # memory rows but no cache table
+    assert layers_call(fill=64) == EINVAL
+    assert layers_call(dtype=F32) == EUNSUP
+    assert layers_call(d=96) == EUNSUP
+    need = lib.loma_decode_layers_workspace_bytes(4, 1, 8, 128, 16, 4, 4, BF16)
+    assert need == 4 * lib.loma_decode_workspace_bytes(1, 8, 128, 16, 4, 4, BF16) > 0
+    assert layers_call(ws=None) == EWS
+    assert layers_call(wsb=need - 1) == EWS

@@ -24,9 +24,23 @@ def test_dkv_kernels_use_only_the_named_accumulation_registers(tmp_path):
     cmd = [hip_build.HIPCC, *hip_build.FLAGS, "--cuda-device-only", "-S", src, "-o", out]
     subprocess.run(cmd, check=True, capture_output=True)
     text = open(out).read()
-    kernels = re.findall(r"\.agpr_count:\s+(\d+).*?\.name:\s+(\S+).*?\.private_segment_fixed_size:\s+(\d+)", text, flags=re.S)
-    dkv = [(name, int(agpr), int(scratch)) for agpr, name, scratch in kernels if "bwd_dkv_kernel" in name]
+    kernels = re.findall(r"\.agpr_count:\s+(\d+).*?\.name:\s+(\S+).*?\.private_segment_fixed_size:\s+(\d+)"
+                         r".*?\.sgpr_spill_count:\s+(\d+).*?\.vgpr_count:\s+(\d+).*?\.vgpr_spill_count:\s+(\d+)", text, flags=re.S)
+    dkv = [(name, int(agpr), int(scratch), int(sspill), int(vgpr), int(vspill))
+           for agpr, name, scratch, sspill, vgpr, vspill in kernels if "bwd_dkv_kernel" in name]
     assert len(dkv) == 6, [k[0] for k in dkv]           # head_dim 64 and 128, 1, 2 and 4 waves
-    for name, agpr, scratch in dkv:
+    for name, agpr, scratch, sspill, vgpr, vspill in dkv:
         assert agpr == 128, f"{name}: {agpr} accumulation registers allocated; the kernel names a0..a127 and relies on no others"
         assert scratch == 0, f"{name}: {scratch} bytes of scratch memory"
+        # a value the compiler parks in an accumulation register between two assembly statements would be a spill
+        # copy: none may exist, and the ordinary registers must not be exhausted (256 is the file's limit per wave)
+        assert vspill == 0, f"{name}: {vspill} vector registers spilled"
+        # vgpr_count is the sum of both files; 256 ordinary registers is the limit per wave
+        assert vgpr - agpr <= 248, f"{name}: {vgpr - agpr} ordinary vector registers leave no headroom"
+        # every access to an accumulation register outside the MFMAs is one of the kernel's own 128 clears or of its
+        # final reads (one per accumulator: 2 * head_dim / 2); a copy the compiler parked there would add to these
+        body = re.search(re.escape(name) + r":.*?\.Lfunc_end", text, flags=re.S).group(0)
+        head_dim = 128 if "ILi128E" in name else 64
+        assert body.count("v_accvgpr_write") == 128, f"{name}: {body.count('v_accvgpr_write')} writes to accumulation registers"
+        assert body.count("v_accvgpr_read") == head_dim, f"{name}: {body.count('v_accvgpr_read')} reads of accumulation registers"
+        assert "v_accvgpr_mov" not in body

@@ -18,33 +18,22 @@ def loma():
     return m
 
 
-def sampled_rows(cfg, stride):
-    """Every stride-th row, plus whole zones of the first and last chunk and all zone borders."""
-    R, t, s, n = cfg.R, cfg.t, cfg.s, cfg.n_chunks
-    rows = set(range(0, cfg.S, stride))
-    for y in (0, n // 2, n - 1):
-        base = y * s
-        rows.update(range(base, base + min(R, 40)))                   # start of the reading zone
-        rows.update(range(base + R - 3, base + R + t + 3))           # read/memory/repetition borders
-        rows.update(range(base + s - 3, base + s))                   # end of the chunk
-        rows.update(range(base + R + t + R // 2, base + R + t + R // 2 + 4))
-    return np.array(sorted(r for r in rows if 0 <= r < cfg.S), dtype=np.int32)
-
-
-@pytest.mark.parametrize("idx,stride", [(1, 31), (3, 257)], ids=["config2_llama7b_mask", "config4_long_mask"])
-def test_mask_pass_full_size(loma, c_oracle, idx, stride):
+@pytest.mark.parametrize("idx", [1, 3], ids=["config2_llama7b_mask", "config4_long_mask"])
+def test_mask_pass_full_size(loma, c_oracle, idx):
+    """Every row of every (b,h) pair, output and log-sum-exp, against the oracle."""
     cfg = wl.CONFIGS[idx]
     print(f"[case] full-size mask pass {cfg}", flush=True)
     q, k, v = wl.mask_inputs(cfg)
-    out = loma.loma_mask_attn_fwd(to_dev(q), to_dev(k), to_dev(v), cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
+    lse = torch.empty((cfg.B, cfg.H, cfg.S), dtype=torch.float32, device="cuda")
+    out = loma.loma_mask_attn_fwd(to_dev(q), to_dev(k), to_dev(v), cfg.t, cfg.c, cfg.n_chunks, cfg.scale, lse=lse)
     torch.cuda.synchronize()
-    rows = sampled_rows(cfg, stride)
-    ref = c_oracle.mask_attn(q, k, v, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, rows=rows)
-    got = to_host_f64(out[:, :, torch.from_numpy(rows.astype(np.int64)).cuda()])
-    mx, mean = check(got, ref, cfg.dtype, cfg.name)
-    print(f"[result] {cfg.name}: {rows.size} rows x {cfg.B * cfg.H} (b,h): max abs {mx:.3e} mean abs {mean:.3e}", flush=True)
-    # every output element finite, also outside the sample
-    assert torch.isfinite(out.float()).all()
+    print("[progress] GPU pass done; oracle running", flush=True)
+    ref, ref_lse = c_oracle.mask_attn(q, k, v, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, return_lse=True)
+    mx, mean = check(to_host_f64(out), ref, cfg.dtype, cfg.name)
+    lse_err = float(np.abs(lse.cpu().numpy().astype(np.float64) - ref_lse).max())
+    print(f"[result] {cfg.name}: all {cfg.S} rows x {cfg.B * cfg.H} (b,h): max abs {mx:.3e} mean abs {mean:.3e} "
+          f"lse max abs {lse_err:.3e}", flush=True)
+    assert lse_err <= 1e-4
 
 
 @pytest.mark.parametrize("idx,npairs", [(1, 8), (3, 4)], ids=["config2_llama7b_mask", "config4_long_mask"])
@@ -69,7 +58,7 @@ def test_mask_pass_gradients_full_size(loma, c_oracle, idx, npairs):
     rq, rk, rv = c_oracle.mask_attn_bwd(pick(q), pick(k), pick(v), pick(g), cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
     for name, got, want in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
         rel = check_grad(pick(to_host_f64(got)), want, cfg.dtype, f"{cfg.name} {name}")
-        print(f"[result] {cfg.name} {name}: {len(sel)} (b,h) pairs, all rows: scaled max err {rel:.3e}", flush=True)
+        print(f"[result] {cfg.name} {name}: {len(sel)} (b,h) pairs, all rows: max abs err {rel:.3e}", flush=True)
         assert torch.isfinite(got.float()).all()
 
 

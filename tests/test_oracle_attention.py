@@ -282,6 +282,8 @@ def test_prefill_equals_single_steps_and_mask_pass_rows(c_oracle, t, c, n, d, pi
             np.testing.assert_allclose(gen.last_lse, full_lse[:, :, p:p + l], atol=1e-12)
             got_c = cg.prefill(q[:, :, p:p + l].copy(), k[:, :, p:p + l].copy(), v[:, :, p:p + l].copy())
             np.testing.assert_allclose(got_c.reshape(B, H, l, d), got, atol=1e-12)
+            # the C route's log-sum-exp: equal to the mask pass's, which scipy's logsumexp pins
+            np.testing.assert_allclose(cg.last_lse.reshape(B, H, l), full_lse[:, :, p:p + l], atol=1e-12)
             p += l
             assert gen.read_fill == cg.read_fill == p - y * s
         m0, m1 = y * s + R, y * s + R + t
