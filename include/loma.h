@@ -162,6 +162,27 @@ int loma_decode_attn(const void* q, const void* k_new, const void* v_new,
                      void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The decode step for callers that cannot allocate device memory and hold no workspace of their
+ * own: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and same result, bit for bit, as loma_decode_attn, without `workspace`: the split-K
+ * partial results go to a fixed array inside the library's device image
+ * (loma_decode_static_scratch_bytes() bytes, 4 MiB, held by every GPU the library runs on until
+ * the process ends).  Nothing is allocated or freed, here or in any library it calls.  Shapes
+ * whose partial results do not fit (loma_decode_workspace_bytes(...) above that size) return
+ * LOMA_ERR_UNSUPPORTED and launch nothing.  The array's address on a device is looked up on the
+ * first call made with that device current (make that call outside graph capture).  Every call on
+ * a GPU shares that GPU's array; its contents are don't-care between calls (every slot read was
+ * written by the same call), but calls that overlap in time on one GPU (different streams) race.
+ */
+int loma_decode_attn_static(const void* q, const void* k_new, const void* v_new,
+                            const void* k_memcache, const void* v_memcache,
+                            void* k_read, void* v_read, void* out,
+                            int B, int H, int head_dim, int t, int c,
+                            int n_mem_chunks, int mem_capacity, int read_fill,
+                            float scale, int dtype, void* stream);
+size_t loma_decode_static_scratch_bytes(void);
+
+/*
  * The decode step for n_layers independent caches of one shape in ONE launch (Sec. 3.1 steps 1
  * and 3 applied to every layer's cache of a model: the per-token cost the method is after is the
  * sum over the layers, and at small batch a launch per layer costs as much as the step itself).

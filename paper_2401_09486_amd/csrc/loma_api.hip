@@ -155,7 +155,7 @@ int decode_attn_impl(const void* q, const void* k_new, const void* v_new,
                      void* k_read, void* v_read, void* out,
                      int B, int H, int head_dim, int t, int c,
                      int n_mem_chunks, int mem_capacity, int read_fill,
-                     float scale, int dtype,
+                     float scale, int dtype, bool static_scratch,
                      void* workspace, size_t workspace_bytes, void* stream) {
     if ((k_new == nullptr) != (v_new == nullptr)) return LOMA_ERR_INVALID_ARG;
     const bool has_new = k_new != nullptr;
@@ -172,7 +172,11 @@ int decode_attn_impl(const void* q, const void* k_new, const void* v_new,
     if (loma::use_mfma_path(dtype, head_dim)) {
         const size_t need = loma::decode_workspace_bytes(nbh, head_dim, (int)n_mem_keys + R);
         if (nbh > 65535) return LOMA_ERR_UNSUPPORTED;
-        if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned16(workspace))) {
+        if (static_scratch) {
+            if (need > loma::decode_static_scratch_bytes()) return LOMA_ERR_UNSUPPORTED;
+            workspace = nullptr;
+            if (need > 0 && (workspace = loma::decode_static_scratch_ptr()) == nullptr) return LOMA_ERR_LAUNCH;
+        } else if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned16(workspace))) {
             return LOMA_ERR_WORKSPACE;
         }
         return loma::launch_decode_splitk(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, nbh,
@@ -195,8 +199,20 @@ int loma_decode_attn(const void* q, const void* k_new, const void* v_new,
                      float scale, int dtype,
                      void* workspace, size_t workspace_bytes, void* stream) {
     return decode_attn_impl(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, B, H, head_dim, t, c,
-                            n_mem_chunks, mem_capacity, read_fill, scale, dtype, workspace, workspace_bytes, stream);
+                            n_mem_chunks, mem_capacity, read_fill, scale, dtype, false, workspace, workspace_bytes, stream);
 }
+
+int loma_decode_attn_static(const void* q, const void* k_new, const void* v_new,
+                            const void* k_memcache, const void* v_memcache,
+                            void* k_read, void* v_read, void* out,
+                            int B, int H, int head_dim, int t, int c,
+                            int n_mem_chunks, int mem_capacity, int read_fill,
+                            float scale, int dtype, void* stream) {
+    return decode_attn_impl(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, B, H, head_dim, t, c,
+                            n_mem_chunks, mem_capacity, read_fill, scale, dtype, true, nullptr, 0, stream);
+}
+
+size_t loma_decode_static_scratch_bytes(void) { return loma::decode_static_scratch_bytes(); }
 
 size_t loma_decode_layers_workspace_bytes(int n_layers, int B, int H, int head_dim, int t, int c,
                                           int n_mem_chunks, int dtype) {

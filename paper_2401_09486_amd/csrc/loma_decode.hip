@@ -16,6 +16,8 @@
 // and a second tiny kernel merges them in a fixed order (deterministic, no atomics).  The new
 // token's K/V are read from k_new/v_new and appended to the reading zone by split 0 -- no
 // workgroup reads the row another one is writing.
+#include <mutex>
+
 #include "loma_internal.h"
 
 namespace loma {
@@ -281,6 +283,16 @@ int launch_decode_d(DecodeParams& P, int nbh, int n_layers, void* workspace, hip
     return LOMA_OK;
 }
 
+// Split-K partial results of the entry point that allocates nothing: a fixed array in the library's own
+// device image, one copy per GPU, alive until the process ends.  The host never uses this name as an address:
+// the per-device address comes from hipGetSymbolAddress (static_scratch_ptr).
+constexpr size_t DEC_STATIC_SCRATCH_BYTES = size_t(4) << 20;
+static __device__ __align__(256) unsigned char scratch[DEC_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mu;
+void* scratch_ptr_of_device[MAX_DEVICES] = {};
+
 }  // namespace
 
 int decode_num_splits(int nbh, int n_keys) {
@@ -293,6 +305,20 @@ size_t decode_workspace_bytes(int nbh, int D, int /*n_keys_max*/) {
     const int tgt = target_splits(nbh);
     if (tgt <= 1) return 0;
     return (size_t)nbh * tgt * (D + 2) * sizeof(float);
+}
+
+size_t decode_static_scratch_bytes() { return DEC_STATIC_SCRATCH_BYTES; }
+
+void* decode_static_scratch_ptr() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (scratch_ptr_of_device[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        scratch_ptr_of_device[dev] = p;
+    }
+    return scratch_ptr_of_device[dev];
 }
 
 int launch_decode_splitk(const void* q, const void* k_new, const void* v_new,

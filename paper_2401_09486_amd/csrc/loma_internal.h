@@ -155,5 +155,9 @@ int launch_decode_splitk(const void* q, const void* k_new, const void* v_new,
 int launch_decode_splitk_layers(const void* const* tables[8], bool has_new, int n_layers, int nbh, int D, int R,
                                 int n_mem_keys, int mem_capacity, int read_fill, float scale, void* workspace,
                                 hipStream_t st);
+// Fixed split-K scratch inside the library's device image (for callers that cannot allocate): its size, and its
+// address on the current device (nullptr if the runtime cannot resolve it).
+size_t decode_static_scratch_bytes();
+void* decode_static_scratch_ptr();
 
 }  // namespace loma

@@ -46,6 +46,10 @@ def _load() -> ctypes.CDLL:
     lib.loma_compress_step.restype = I
     lib.loma_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, F, I, vp, Z, vp]
     lib.loma_decode_attn.restype = I
+    lib.loma_decode_attn_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, F, I, vp]
+    lib.loma_decode_attn_static.restype = I
+    lib.loma_decode_static_scratch_bytes.argtypes = []
+    lib.loma_decode_static_scratch_bytes.restype = Z
     lib.loma_decode_attn_layers.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, I, F, I, vp, Z, vp]
     lib.loma_decode_attn_layers.restype = I
     lib.loma_decode_layers_workspace_bytes.argtypes = [I, I, I, I, I, I, I, I]
@@ -197,6 +201,33 @@ def loma_decode_attn(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, t,
     if rc != OK:
         raise LomaError(rc, "loma_decode_attn")
     return out
+
+
+def loma_decode_attn_static(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, t, c, n_mem_chunks, read_fill, scale,
+                            out=None, stream=None):
+    """loma_decode_attn without a workspace: the split-K partials live in a fixed array inside the library."""
+    B, H, one, d = q.shape
+    if one != 1:
+        raise ValueError("q must be [B, H, 1, d]")
+    if out is None:
+        out = torch.empty_like(q)
+    dt = q.dtype
+    pkn = None if k_new is None else _dev(k_new, "k_new", q.shape, dt)
+    pvn = None if v_new is None else _dev(v_new, "v_new", q.shape, dt)
+    cap = 0 if k_memcache is None else k_memcache.shape[2]
+    pkm = None if k_memcache is None else _dev(k_memcache, "k_memcache", (B, H, cap, d), dt)
+    pvm = None if v_memcache is None else _dev(v_memcache, "v_memcache", (B, H, cap, d), dt)
+    rc = lib.loma_decode_attn_static(_dev(q, "q"), pkn, pvn, pkm, pvm, _dev(k_read, "k_read", (B, H, t * c, d), dt),
+                                     _dev(v_read, "v_read", (B, H, t * c, d), dt), _dev(out, "out", q.shape, dt),
+                                     B, H, d, t, c, n_mem_chunks, cap, read_fill, float(scale), _dtype_code(q),
+                                     _stream(stream))
+    if rc != OK:
+        raise LomaError(rc, "loma_decode_attn_static")
+    return out
+
+
+def decode_static_scratch_bytes() -> int:
+    return int(lib.loma_decode_static_scratch_bytes())
 
 
 def pointer_table(tensors) -> torch.Tensor:

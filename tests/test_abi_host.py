@@ -223,6 +223,23 @@ def test_mask_pass_dispatch_respects_the_division_bound(lib):
 
 
 def test_new_decode_forms_reject_bad_arguments(lib):
+    # static-scratch form: same state checks as loma_decode_attn, and a size limit instead of a workspace check
+    def static_call(**kw):
+        a = dict(q=P, kn=P, vn=P, kc=P, vc=P, kr=P, vr=P, out=P, B=1, H=8, d=128, t=16, c=4, nmem=4, cap=64, fill=3,
+                 scale=0.1, dtype=BF16)
+        a.update(kw)
+        return lib.loma_decode_attn_static(a["q"], a["kn"], a["vn"], a["kc"], a["vc"], a["kr"], a["vr"], a["out"], a["B"],
+                                           a["H"], a["d"], a["t"], a["c"], a["nmem"], a["cap"], a["fill"], a["scale"],
+                                           a["dtype"], None)
+    assert static_call(q=None) == EINVAL
+    assert static_call(fill=64) == EINVAL
+    assert static_call(nmem=5) == EINVAL
+    assert static_call(dtype=9) == EUNSUP
+    assert lib.loma_decode_static_scratch_bytes() == 4 << 20
+    # 4095 pairs x 2 splits x 130 floats do not fit the fixed array
+    assert lib.loma_decode_workspace_bytes(4095, 1, 128, 16, 4, 4, BF16) > lib.loma_decode_static_scratch_bytes()
+    assert static_call(B=4095, H=1) == EUNSUP
+
     def layers_call(**kw):
         a = dict(q=P, kn=P, vn=P, kc=P, vc=P, kr=P, vr=P, out=P, L=4, B=1, H=8, d=128, t=16, c=4, nmem=4, cap=64,
                  fill=3, scale=0.1, dtype=BF16, ws=P, wsb=1 << 30)
