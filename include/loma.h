@@ -56,6 +56,10 @@ extern "C" {
 #define LOMA_F32 0
 #define LOMA_BF16 1
 
+/* Position types of the memory tokens (Sec. 4.5; Appendix A, `position_type`). */
+#define LOMA_POS_INTERMITTENT 0 /* Eq. 14: the last id of every group of c reading tokens */
+#define LOMA_POS_CONTIGUOUS 1   /* the row numbers of the compressed cache */
+
 /* Human-readable name of a status code; never NULL. */
 const char* loma_status_string(int status);
 
@@ -204,6 +208,50 @@ int loma_decode_attn_layers(const void* const* q, const void* const* k_new, cons
                             void* workspace, size_t workspace_bytes, void* stream);
 size_t loma_decode_layers_workspace_bytes(int n_layers, int B, int H, int head_dim, int t, int c,
                                           int n_mem_chunks, int dtype);
+
+/*
+ * Position ids (Sec. 4.5, Eq. 14; Appendix A).  Host-only arithmetic on HOST arrays; launches nothing.
+ * The text is cut into reading zones of R = t*c tokens; reading token j of chunk i keeps its original id
+ * i*R + j.  The t memory tokens of chunk i (i = number of chunks compressed before it) take
+ *   LOMA_POS_INTERMITTENT: i*R + c-1, i*R + 2c-1, ..., i*R + tc-1   (Eq. 14 read with chunk length tc: ids inside
+ *                          the chunk, the last one adjacent to the next chunk's first reading id)
+ *   LOMA_POS_CONTIGUOUS:   i*t, i*t + 1, ..., i*t + t-1             (the appendix's mem_cursor + j)
+ * Both are arithmetic progressions: first id ids[0], step ids[1] - ids[0] (c or 1), which is how the *_rope entry
+ * points take them.  The paper gives no ids for repetition tokens; loma_sample_position_ids gives repetition
+ * token j the id of the reading token it reproduces, i*R + j.
+ *   loma_memory_position_ids: ids[0..t)               of chunk `chunk`
+ *   loma_sample_position_ids: ids[0..n_chunks*t(2c+1)) of a whole restructured sample, row by row
+ */
+int loma_memory_position_ids(int t, int c, int chunk, int position_type, int* ids);
+int loma_sample_position_ids(int t, int c, int n_chunks, int position_type, int* ids);
+
+/*
+ * The decode and compression steps with the rotary position embedding applied as q and k are loaded (the
+ * paper's model, Llama-2, rotates q and k by their position ids before the scores; Sec. 4.5 designs the ids).
+ * Same arguments and semantics as loma_decode_attn / loma_compress_step, except that q (q_mem) and k_new
+ * (k_mem) arrive UNROTATED and the caches hold rotated K: the appended / spliced K rows are the rotated ones,
+ * rounded to bf16 once.  Convention: head-dim element i < d/2 pairs with element i + d/2 and the pair turns by
+ * pos * rope_theta^(-2i/d) (Llama's "rotate-half" form).
+ *   decode:   pos is the id of the new token (the appendix's cursor); q and k_new turn by it.
+ *   compress: memory token j turns by pos_first + j * pos_stride (see the position-id helpers above).
+ *             `out` is used as scratch for the rotated queries before the results overwrite it, so it must
+ *             not alias q_mem.
+ * bf16 with head_dim 64 or 128 only (else LOMA_ERR_UNSUPPORTED); rope_theta > 0 (Llama-2: 10000).
+ */
+int loma_decode_attn_rope(const void* q, const void* k_new, const void* v_new,
+                          const void* k_memcache, const void* v_memcache,
+                          void* k_read, void* v_read, void* out,
+                          int B, int H, int head_dim, int t, int c,
+                          int n_mem_chunks, int mem_capacity, int read_fill,
+                          float scale, int dtype, int pos, float rope_theta,
+                          void* workspace, size_t workspace_bytes, void* stream);
+int loma_compress_step_rope(const void* q_mem, const void* k_mem, const void* v_mem,
+                            const void* k_read, const void* v_read,
+                            void* k_memcache, void* v_memcache, void* out,
+                            int B, int H, int head_dim, int t, int c,
+                            int n_mem_chunks, int mem_capacity,
+                            float scale, int dtype,
+                            int pos_first, int pos_stride, float rope_theta, void* stream);
 
 /*
  * Generation form, several new tokens per sequence at once: a prompt or a piece of one

@@ -4,6 +4,7 @@
 #include <cstdint>
 
 #include "loma_internal.h"
+#include "loma_rope.h"
 
 namespace {
 
@@ -103,25 +104,87 @@ int loma_mask_attn_bwd(const void* q, const void* k, const void* v, const void* 
                                               nbh, head_dim, g, scale, dtype, st);
 }
 
-int loma_compress_step(const void* q_mem, const void* k_mem, const void* v_mem,
+}  // extern "C" (reopened below)
+
+namespace {
+
+bool good_rope(int pos_first, int pos_stride, float theta) {
+    return pos_first >= 0 && pos_stride >= 0 && theta > 0.f && std::isfinite(theta);
+}
+
+int compress_step_impl(const void* q_mem, const void* k_mem, const void* v_mem,
                        const void* k_read, const void* v_read,
                        void* k_memcache, void* v_memcache, void* out,
                        int B, int H, int head_dim, int t, int c,
                        int n_mem_chunks, int mem_capacity,
-                       float scale, int dtype, void* stream) {
+                       float scale, int dtype, void* stream, const loma::RopeTable* rope) {
     if (int rc = check_common(B, H, head_dim, t, c, scale, dtype)) return rc;
     if (n_mem_chunks < 0 || mem_capacity < 1) return LOMA_ERR_INVALID_ARG;
     if (((long long)n_mem_chunks + 1) * t > mem_capacity) return LOMA_ERR_INVALID_ARG;
     if (!good_ptr(q_mem) || !good_ptr(k_mem) || !good_ptr(v_mem) || !good_ptr(k_read) || !good_ptr(v_read) ||
         !good_ptr(k_memcache) || !good_ptr(v_memcache) || !good_ptr(out))
         return LOMA_ERR_INVALID_ARG;
+    if (rope != nullptr && out == q_mem) return LOMA_ERR_INVALID_ARG;   // out holds the rotated queries meanwhile
     const int nbh = B * H;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (loma::use_mfma_path(dtype, head_dim))
         return loma::launch_compress_mfma(q_mem, k_mem, v_mem, k_read, v_read, k_memcache, v_memcache, out,
-                                          nbh, head_dim, t, c, n_mem_chunks, mem_capacity, scale, st);
+                                          nbh, head_dim, t, c, n_mem_chunks, mem_capacity, scale, st, rope);
+    if (rope != nullptr) return LOMA_ERR_UNSUPPORTED;
     return loma::launch_compress_generic(q_mem, k_mem, v_mem, k_read, v_read, k_memcache, v_memcache, out,
                                          nbh, head_dim, t, c, n_mem_chunks, mem_capacity, scale, dtype, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int loma_compress_step(const void* q_mem, const void* k_mem, const void* v_mem,
+                       const void* k_read, const void* v_read,
+                       void* k_memcache, void* v_memcache, void* out,
+                       int B, int H, int head_dim, int t, int c,
+                       int n_mem_chunks, int mem_capacity,
+                       float scale, int dtype, void* stream) {
+    return compress_step_impl(q_mem, k_mem, v_mem, k_read, v_read, k_memcache, v_memcache, out, B, H, head_dim, t, c,
+                              n_mem_chunks, mem_capacity, scale, dtype, stream, nullptr);
+}
+
+int loma_compress_step_rope(const void* q_mem, const void* k_mem, const void* v_mem,
+                            const void* k_read, const void* v_read,
+                            void* k_memcache, void* v_memcache, void* out,
+                            int B, int H, int head_dim, int t, int c,
+                            int n_mem_chunks, int mem_capacity,
+                            float scale, int dtype,
+                            int pos_first, int pos_stride, float rope_theta, void* stream) {
+    if (!good_rope(pos_first, pos_stride, rope_theta)) return LOMA_ERR_INVALID_ARG;
+    if (head_dim != 64 && head_dim != 128) return LOMA_ERR_UNSUPPORTED;
+    const loma::RopeTable rt = loma::make_rope_table(head_dim, rope_theta, pos_first, pos_stride);
+    return compress_step_impl(q_mem, k_mem, v_mem, k_read, v_read, k_memcache, v_memcache, out, B, H, head_dim, t, c,
+                              n_mem_chunks, mem_capacity, scale, dtype, stream, &rt);
+}
+
+int loma_memory_position_ids(int t, int c, int chunk, int position_type, int* ids) {
+    if (t < 1 || c < 1 || chunk < 0 || ids == nullptr) return LOMA_ERR_INVALID_ARG;
+    if (position_type != LOMA_POS_INTERMITTENT && position_type != LOMA_POS_CONTIGUOUS) return LOMA_ERR_INVALID_ARG;
+    const long long R = (long long)t * c;
+    if (((long long)chunk + 1) * R > 0x7fffffffLL) return LOMA_ERR_UNSUPPORTED;
+    for (int j = 0; j < t; ++j)
+        ids[j] = position_type == LOMA_POS_INTERMITTENT ? (int)(chunk * R + (long long)(j + 1) * c - 1)   // Eq. 14
+                                                         : chunk * t + j;                                  // mem_cursor + j
+    return LOMA_OK;
+}
+
+int loma_sample_position_ids(int t, int c, int n_chunks, int position_type, int* ids) {
+    if (t < 1 || c < 1 || n_chunks < 1 || ids == nullptr) return LOMA_ERR_INVALID_ARG;
+    if (position_type != LOMA_POS_INTERMITTENT && position_type != LOMA_POS_CONTIGUOUS) return LOMA_ERR_INVALID_ARG;
+    const long long R = (long long)t * c, s = 2 * R + t;
+    if (n_chunks * s > (1LL << 30)) return LOMA_ERR_UNSUPPORTED;
+    for (int y = 0; y < n_chunks; ++y) {
+        int* row = ids + y * s;
+        for (int j = 0; j < R; ++j) row[j] = row[R + t + j] = (int)(y * R + j);   // <r> tokens: the ids of the tokens they reproduce
+        if (int rc = loma_memory_position_ids(t, c, y, position_type, row + R)) return rc;
+    }
+    return LOMA_OK;
 }
 
 size_t loma_decode_workspace_bytes(int B, int H, int head_dim, int t, int c, int n_mem_chunks, int dtype) {
@@ -156,7 +219,7 @@ int decode_attn_impl(const void* q, const void* k_new, const void* v_new,
                      int B, int H, int head_dim, int t, int c,
                      int n_mem_chunks, int mem_capacity, int read_fill,
                      float scale, int dtype, bool static_scratch,
-                     void* workspace, size_t workspace_bytes, void* stream) {
+                     void* workspace, size_t workspace_bytes, void* stream, const loma::RopeTable* rope = nullptr) {
     if ((k_new == nullptr) != (v_new == nullptr)) return LOMA_ERR_INVALID_ARG;
     const bool has_new = k_new != nullptr;
     long long n_mem_keys = 0;
@@ -181,8 +244,9 @@ int decode_attn_impl(const void* q, const void* k_new, const void* v_new,
         }
         return loma::launch_decode_splitk(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, nbh,
                                           head_dim, R, (int)n_mem_keys, mem_capacity, read_fill, scale,
-                                          need > 0 ? workspace : nullptr, st);
+                                          need > 0 ? workspace : nullptr, st, rope);
     }
+    if (rope != nullptr) return LOMA_ERR_UNSUPPORTED;
     return loma::launch_decode_generic(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, nbh,
                                        head_dim, R, (int)n_mem_keys, mem_capacity, read_fill, scale, dtype, st);
 }
@@ -210,6 +274,21 @@ int loma_decode_attn_static(const void* q, const void* k_new, const void* v_new,
                             float scale, int dtype, void* stream) {
     return decode_attn_impl(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, B, H, head_dim, t, c,
                             n_mem_chunks, mem_capacity, read_fill, scale, dtype, true, nullptr, 0, stream);
+}
+
+int loma_decode_attn_rope(const void* q, const void* k_new, const void* v_new,
+                          const void* k_memcache, const void* v_memcache,
+                          void* k_read, void* v_read, void* out,
+                          int B, int H, int head_dim, int t, int c,
+                          int n_mem_chunks, int mem_capacity, int read_fill,
+                          float scale, int dtype, int pos, float rope_theta,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+    if (!good_rope(pos, 0, rope_theta)) return LOMA_ERR_INVALID_ARG;
+    if (head_dim != 64 && head_dim != 128) return LOMA_ERR_UNSUPPORTED;
+    const loma::RopeTable rt = loma::make_rope_table(head_dim, rope_theta, pos, 0);
+    return decode_attn_impl(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, B, H, head_dim, t, c,
+                            n_mem_chunks, mem_capacity, read_fill, scale, dtype, false, workspace, workspace_bytes, stream,
+                            &rt);
 }
 
 size_t loma_decode_static_scratch_bytes(void) { return loma::decode_static_scratch_bytes(); }

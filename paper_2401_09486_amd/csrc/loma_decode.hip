@@ -17,8 +17,10 @@
 // token's K/V are read from k_new/v_new and appended to the reading zone by split 0 -- no
 // workgroup reads the row another one is writing.
 #include <mutex>
+#include <type_traits>
 
 #include "loma_internal.h"
+#include "loma_rope.h"
 
 namespace loma {
 namespace {
@@ -87,8 +89,12 @@ __device__ __forceinline__ float row_sum(float x) {
 
 // LAYERED: blockIdx.z is a layer; its eight tensors come from the pointer tables, everything else (shapes,
 // cache state, split plan) is shared by the layers, so a layer's result is computed exactly as by a call of its own.
-template <int D, int DEC_WAVES, bool LAYERED>
-__global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodeParams P) {
+// ROPE: q and the new token's K arrive unrotated and are turned by the new token's position id as they are
+// loaded (the cache holds rotated K); the appended K row is the rotated one.
+struct NoRope {};
+template <int D, int DEC_WAVES, bool LAYERED, bool ROPE>
+__global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodeParams P,
+                                                                      std::conditional_t<ROPE, RopeTable, NoRope> RT) {
     constexpr int LPR = D / 8;            // lanes per key row
     constexpr int RPL = 64 / LPR;         // rows per wave-wide load
     constexpr int KPW = RPL * DEC_UNROLL; // keys per wave iteration
@@ -121,7 +127,11 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodePara
     const bf16_t* knew = P.k_new + bh * D;
     const bf16_t* vnew = P.v_new + bh * D;
 
-    const uint4 qv = *reinterpret_cast<const uint4*>(P.q + bh * D + col * 8);
+    uint4 qv = *reinterpret_cast<const uint4*>(P.q + bh * D + col * 8);
+    if constexpr (ROPE) {
+        const u32x4 r = rope::load_rotated_piece<D>(P.q + bh * D, col, RT.pos_first, RT);
+        qv = uint4{r[0], r[1], r[2], r[3]};
+    }
     const bf16x2 q0 = as_bf16x2(qv.x), q1 = as_bf16x2(qv.y), q2 = as_bf16x2(qv.z), q3 = as_bf16x2(qv.w);
 
     float m = -INFINITY, l = 0.f;
@@ -141,6 +151,15 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodePara
                 else { kp = knew; vp = vnew; }
                 kk[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + col * 8));
                 vv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vp + col * 8));
+            }
+        }
+        if constexpr (ROPE) {   // the new token's key (the last key of the list, met by one lane group of one wave)
+            if (P.has_new && base + (DEC_UNROLL - 1) * RPL + RPL > P.n_mem + P.n_read) {
+#pragma unroll
+                for (int u = 0; u < DEC_UNROLL; ++u) {
+                    const int j = base + u * RPL + sub;
+                    if (j < kend && j >= P.n_mem + P.n_read) kk[u] = rope::load_rotated_piece<D>(knew, col, RT.pos_first, RT);
+                }
             }
         }
         float s[DEC_UNROLL];
@@ -219,7 +238,13 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodePara
     // append the new token to the reading zone (Appendix A: the cache grows by the input token)
     if (P.has_new && sp == 0 && tid < 2 * LPR) {
         const int which = tid / LPR, piece = tid % LPR;
-        const uint4 x = *reinterpret_cast<const uint4*>((which ? vnew : knew) + piece * 8);
+        uint4 x = *reinterpret_cast<const uint4*>((which ? vnew : knew) + piece * 8);
+        if constexpr (ROPE) {
+            if (which == 0) {
+                const u32x4 r = rope::load_rotated_piece<D>(knew, piece, RT.pos_first, RT);
+                x = uint4{r[0], r[1], r[2], r[3]};
+            }
+        }
         bf16_t* dst = (which ? P.v_read : P.k_read) + (bh * (long)P.R + P.n_read) * D;
         *reinterpret_cast<uint4*>(dst + piece * 8) = x;
     }
@@ -264,17 +289,18 @@ void plan_splits(int nbh, int D, int n_keys, int& nsplit, int& keys_per_split) {
     keys_per_split = ups * kpi;
 }
 
-template <int D, bool LAYERED>
-int launch_decode_d(DecodeParams& P, int nbh, int n_layers, void* workspace, hipStream_t st) {
+template <int D, bool LAYERED, bool ROPE = false>
+int launch_decode_d(DecodeParams& P, int nbh, int n_layers, void* workspace, hipStream_t st,
+                    std::conditional_t<ROPE, RopeTable, NoRope> RT = {}) {
     plan_splits(nbh, D, P.L, P.nsplit, P.keys_per_split);
     P.ws_acc = static_cast<float*>(workspace);
     P.ws_ml = P.ws_acc ? P.ws_acc + (size_t)nbh * target_splits(nbh) * D : nullptr;
     P.ws_layer_floats = (long)nbh * target_splits(nbh) * (D + 2);
     if (nbh > 65535 || n_layers > 65535) return LOMA_ERR_UNSUPPORTED;
     if (wg_waves(nbh) == 16)
-        hipLaunchKernelGGL((decode_split_kernel<D, 16, LAYERED>), dim3(P.nsplit, nbh, n_layers), dim3(1024), 0, st, P);
+        hipLaunchKernelGGL((decode_split_kernel<D, 16, LAYERED, ROPE>), dim3(P.nsplit, nbh, n_layers), dim3(1024), 0, st, P, RT);
     else
-        hipLaunchKernelGGL((decode_split_kernel<D, 4, LAYERED>), dim3(P.nsplit, nbh, n_layers), dim3(256), 0, st, P);
+        hipLaunchKernelGGL((decode_split_kernel<D, 4, LAYERED, ROPE>), dim3(P.nsplit, nbh, n_layers), dim3(256), 0, st, P, RT);
     if (hipGetLastError() != hipSuccess) return LOMA_ERR_LAUNCH;
     if (P.nsplit > 1) {
         hipLaunchKernelGGL((decode_combine_kernel<D, LAYERED>), dim3(nbh, n_layers), dim3(D), 0, st, P);
@@ -324,7 +350,7 @@ void* decode_static_scratch_ptr() {
 int launch_decode_splitk(const void* q, const void* k_new, const void* v_new,
                          const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
                          void* out, int nbh, int D, int R, int n_mem_keys, int mem_capacity, int read_fill,
-                         float scale, void* workspace, hipStream_t st) {
+                         float scale, void* workspace, hipStream_t st, const RopeTable* rope) {
     DecodeParams P = {};
     P.q = static_cast<const bf16_t*>(q);
     P.k_new = static_cast<const bf16_t*>(k_new); P.v_new = static_cast<const bf16_t*>(v_new);
@@ -335,6 +361,9 @@ int launch_decode_splitk(const void* q, const void* k_new, const void* v_new,
     P.has_new = k_new != nullptr;
     P.L = n_mem_keys + read_fill + (P.has_new ? 1 : 0);
     P.sc = scale * LOG2E;
+    if (rope != nullptr)
+        return D == 128 ? launch_decode_d<128, false, true>(P, nbh, 1, workspace, st, *rope)
+                        : launch_decode_d<64, false, true>(P, nbh, 1, workspace, st, *rope);
     return D == 128 ? launch_decode_d<128, false>(P, nbh, 1, workspace, st)
                     : launch_decode_d<64, false>(P, nbh, 1, workspace, st);
 }

@@ -20,7 +20,13 @@
 // transposing LDS read of gfx950 (ds_read_b64_tr_b16: inside 16 lanes, lane i receives the i-th
 // 16-bit column of four rows).  Tiles are double-buffered: the loads for tile i+1 are in flight
 // while tile i is multiplied; one barrier per tile.
+#include <mutex>
+#include <set>
+#include <type_traits>
+#include <utility>
+
 #include "loma_mfma.h"
+#include "loma_rope.h"
 
 namespace loma {
 namespace {
@@ -886,11 +892,18 @@ struct CompressParams {
     float sc;
 };
 
-template <int D, int NW, int BN>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void compress_kernel(CompressParams P) {
+// ROPE: q_mem and k_mem arrive unrotated.  A prologue turns the t <m> keys by their position ids and writes them
+// where they belong anyway -- the cache rows of the splice -- and turns the block's queries into its rows of
+// `out` (free until the results are stored); after a device-scope fence and a barrier the block reads both back
+// like any other rows.  Blocks of one (b,h) write the same key bytes.
+struct NoRopeArg {};
+template <int D, int NW, int BN, bool ROPE>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void compress_kernel(
+    CompressParams P, std::conditional_t<ROPE, RopeTable, NoRopeArg> RT) {
     constexpr int QT = 1;
     extern __shared__ __align__(16) bf16_t smem[];
     constexpr int BM = 32 * NW;
+    constexpr int CPR = D / 8;
     const int bh = blockIdx.x / P.nblk, blk = blockIdx.x % P.nblk;
     const int o0 = blk * BM;
     FlashJob J;
@@ -904,15 +917,36 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
     J.q = P.q_mem + ((long)bh * P.t + o0) * D;
     J.out = P.out + ((long)bh * P.t + o0) * D;
     J.lse = nullptr;
+    bf16_t* kd = P.k_cache + ((long)bh * P.cache_rows + P.cache_row0) * D;
+    bf16_t* vd = P.v_cache + ((long)bh * P.cache_rows + P.cache_row0) * D;
+    if constexpr (ROPE) {
+        for (int i = threadIdx.x; i < P.t * CPR; i += 64 * NW) {
+            const int r = i / CPR, pc = i % CPR;
+            const u32x4 x = rope::load_rotated_piece<D>(J.k2 + (long)r * D, pc, RT.pos_first + r * RT.pos_stride, RT);
+            *reinterpret_cast<u32x4*>(kd + (long)r * D + pc * 8) = x;
+        }
+        for (int i = threadIdx.x; i < J.q_rows * CPR; i += 64 * NW) {
+            const int r = i / CPR, pc = i % CPR;
+            const u32x4 x = rope::load_rotated_piece<D>(J.q + (long)r * D, pc, RT.pos_first + (o0 + r) * RT.pos_stride, RT);
+            *reinterpret_cast<u32x4*>(J.out + (long)r * D + pc * 8) = x;
+        }
+        __threadfence();
+        __syncthreads();
+        J.k2 = kd;
+        J.q = J.out;
+    }
     flash_job<D, NW, BN, QT>(J, P.sc, smem);
     // splice: the t new memory KVs join the compressed cache (Sec. 3.1 step 3)
     if (blk == 0) {
         const int pieces = P.t * D / 8;
         const uint4* ks = reinterpret_cast<const uint4*>(J.k2);
         const uint4* vs = reinterpret_cast<const uint4*>(J.v2);
-        uint4* kd = reinterpret_cast<uint4*>(P.k_cache + ((long)bh * P.cache_rows + P.cache_row0) * D);
-        uint4* vd = reinterpret_cast<uint4*>(P.v_cache + ((long)bh * P.cache_rows + P.cache_row0) * D);
-        for (int i = threadIdx.x; i < pieces; i += 64 * NW) { kd[i] = ks[i]; vd[i] = vs[i]; }
+        uint4* kd4 = reinterpret_cast<uint4*>(kd);
+        uint4* vd4 = reinterpret_cast<uint4*>(vd);
+        for (int i = threadIdx.x; i < pieces; i += 64 * NW) {
+            if (!ROPE) kd4[i] = ks[i];
+            vd4[i] = vs[i];
+        }
     }
 }
 
@@ -964,37 +998,48 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
     }
 }
 
-template <typename K, typename P>
-int launch(K kernel, long long grid, int threads, int smem_bytes, const P& params, hipStream_t st) {
+// The dynamic-LDS limit of a kernel is raised once per kernel and device, not on every enqueue.
+inline bool lds_limit_is_set(const void* kernel, int smem_bytes) {
+    static std::mutex mu;
+    static std::set<std::pair<const void*, int>> done;   // (kernel, device)
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count({kernel, dev})) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes) != hipSuccess) return false;
+    done.insert({kernel, dev});
+    return true;
+}
+
+template <typename K, typename... Args>
+int launch(K kernel, long long grid, int threads, int smem_bytes, hipStream_t st, const Args&... args) {
     if (grid <= 0) return LOMA_OK;
     if (grid > 0x7fffffffLL) return LOMA_ERR_UNSUPPORTED;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            smem_bytes) != hipSuccess)
-        return LOMA_ERR_LAUNCH;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(threads), smem_bytes, st, params);
+    if (!lds_limit_is_set(reinterpret_cast<const void*>(kernel), smem_bytes)) return LOMA_ERR_LAUNCH;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(threads), smem_bytes, st, args...);
     return hipGetLastError() == hipSuccess ? LOMA_OK : LOMA_ERR_LAUNCH;
 }
 
 template <int D>
 int launch_mask_d(const MaskParams& P, int bm, hipStream_t st) {
     const long long grid = P.sched.size();
-    if (bm == 128) return launch(mask_attn_kernel<D, 4, 64, 1>, grid, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, P, st);
-    if (bm == 64) return launch(mask_attn_kernel<D, 2, 32, 1>, grid, 128, Cfg<D, 2, 32, 1>::SMEM_BYTES, P, st);
-    return launch(mask_attn_kernel<D, 1, 32, 1>, grid, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, P, st);
+    if (bm == 128) return launch(mask_attn_kernel<D, 4, 64, 1>, grid, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, st, P);
+    if (bm == 64) return launch(mask_attn_kernel<D, 2, 32, 1>, grid, 128, Cfg<D, 2, 32, 1>::SMEM_BYTES, st, P);
+    return launch(mask_attn_kernel<D, 1, 32, 1>, grid, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, st, P);
 }
 
-template <int D>
-int launch_compress_d(CompressParams& P, int nbh, hipStream_t st) {
+template <int D, bool ROPE>
+int launch_compress_d(CompressParams& P, int nbh, hipStream_t st, std::conditional_t<ROPE, RopeTable, NoRopeArg> RT) {
     if (P.t > 64) {
         P.nblk = (P.t + 127) / 128;
-        return launch(compress_kernel<D, 4, 64>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, P, st);
+        return launch(compress_kernel<D, 4, 64, ROPE>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, st, P, RT);
     }
     if (P.t > 32) {
         P.nblk = 1;
-        return launch(compress_kernel<D, 2, 32>, nbh, 128, Cfg<D, 2, 32, 1>::SMEM_BYTES, P, st);
+        return launch(compress_kernel<D, 2, 32, ROPE>, nbh, 128, Cfg<D, 2, 32, 1>::SMEM_BYTES, st, P, RT);
     }
     P.nblk = 1;
-    return launch(compress_kernel<D, 1, 32>, nbh, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, P, st);
+    return launch(compress_kernel<D, 1, 32, ROPE>, nbh, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, st, P, RT);
 }
 
 template <int D>
@@ -1007,19 +1052,19 @@ int launch_prefill_d(PrefillParams& P, int nbh, hipStream_t st) {
     constexpr int RING4 = 2 * Cfg<D, 4, 64, 1>::RING_BYTES;   // 4 stages of 64 keys
     if (few && P.n_new <= 32) {
         P.nblk = 1;
-        return launch(prefill_kernel<D, 2, 64, 2, 4>, nbh, 128, RING4, P, st);
+        return launch(prefill_kernel<D, 2, 64, 2, 4>, nbh, 128, RING4, st, P);
     }
     if (few) {
         P.nblk = (P.n_new + 63) / 64;
-        return launch(prefill_kernel<D, 4, 64, 2, 4>, (long long)nbh * P.nblk, 256, RING4, P, st);
+        return launch(prefill_kernel<D, 4, 64, 2, 4>, (long long)nbh * P.nblk, 256, RING4, st, P);
     }
     if (P.n_new > 64) {
         P.nblk = (P.n_new + 127) / 128;
-        return launch(prefill_kernel<D, 4, 64, 1, 2>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, P, st);
+        return launch(prefill_kernel<D, 4, 64, 1, 2>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, st, P);
     }
     P.nblk = 1;
-    if (P.n_new > 32) return launch(prefill_kernel<D, 2, 64, 1, 2>, nbh, 128, Cfg<D, 2, 64, 1>::SMEM_BYTES, P, st);
-    return launch(prefill_kernel<D, 1, 32, 1, 2>, nbh, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, P, st);
+    if (P.n_new > 32) return launch(prefill_kernel<D, 2, 64, 1, 2>, nbh, 128, Cfg<D, 2, 64, 1>::SMEM_BYTES, st, P);
+    return launch(prefill_kernel<D, 1, 32, 1, 2>, nbh, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, st, P);
 }
 
 }  // namespace
@@ -1055,7 +1100,7 @@ int launch_mask_attn_mfma(const void* q, const void* k, const void* v, void* out
 int launch_compress_mfma(const void* q_mem, const void* k_mem, const void* v_mem,
                          const void* k_read, const void* v_read, void* k_memcache, void* v_memcache,
                          void* out, int nbh, int D, int t, int c, int n_mem_chunks, int mem_capacity,
-                         float scale, hipStream_t st) {
+                         float scale, hipStream_t st, const RopeTable* rope) {
     CompressParams P;
     P.q_mem = static_cast<const bf16_t*>(q_mem); P.k_mem = static_cast<const bf16_t*>(k_mem);
     P.v_mem = static_cast<const bf16_t*>(v_mem); P.k_read = static_cast<const bf16_t*>(k_read);
@@ -1065,7 +1110,9 @@ int launch_compress_mfma(const void* q_mem, const void* k_mem, const void* v_mem
     P.t = t; P.R = t * c; P.nblk = 1;
     P.cache_row0 = (long)n_mem_chunks * t; P.cache_rows = mem_capacity;
     P.sc = scale * LOG2E;
-    return D == 128 ? launch_compress_d<128>(P, nbh, st) : launch_compress_d<64>(P, nbh, st);
+    if (rope != nullptr)
+        return D == 128 ? launch_compress_d<128, true>(P, nbh, st, *rope) : launch_compress_d<64, true>(P, nbh, st, *rope);
+    return D == 128 ? launch_compress_d<128, false>(P, nbh, st, {}) : launch_compress_d<64, false>(P, nbh, st, {});
 }
 
 }  // namespace loma

@@ -107,7 +107,7 @@ int launch_mask_attn_mfma(const void* q, const void* k, const void* v, void* out
 int launch_compress_mfma(const void* q_mem, const void* k_mem, const void* v_mem,
                          const void* k_read, const void* v_read, void* k_memcache, void* v_memcache,
                          void* out, int nbh, int D, int t, int c, int n_mem_chunks, int mem_capacity,
-                         float scale, hipStream_t st);
+                         float scale, hipStream_t st, const struct RopeTable* rope = nullptr);
 
 int launch_mask_attn_generic(const void* q, const void* k, const void* v, void* out, float* lse,
                              int nbh, int D, const Geometry& g, float scale, int dtype, hipStream_t st);
@@ -144,10 +144,11 @@ int launch_prefill_generic(const void* q, const void* k_new, const void* v_new,
 // Split-K decode over [memory cache || reading zone || new token].
 int decode_num_splits(int nbh, int n_keys);
 size_t decode_workspace_bytes(int nbh, int D, int n_keys_max);
+struct RopeTable;   // loma_rope.h: rotary frequencies and the position ids of the rows to rotate; nullptr = no rotation
 int launch_decode_splitk(const void* q, const void* k_new, const void* v_new,
                          const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
                          void* out, int nbh, int D, int R, int n_mem_keys, int mem_capacity, int read_fill,
-                         float scale, void* workspace, hipStream_t st);
+                         float scale, void* workspace, hipStream_t st, const RopeTable* rope = nullptr);
 
 // The same for n_layers independent caches in ONE launch: tables[i] is a DEVICE array of n_layers device pointers
 // (q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out); shapes and cache state are shared by the layers.

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libloma.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3, -4
 F32, BF16 = 0, 1
+POS_INTERMITTENT, POS_CONTIGUOUS = 0, 1
 
 
 class LomaError(RuntimeError):
@@ -54,6 +55,14 @@ def _load() -> ctypes.CDLL:
     lib.loma_decode_attn_layers.restype = I
     lib.loma_decode_layers_workspace_bytes.argtypes = [I, I, I, I, I, I, I, I]
     lib.loma_decode_layers_workspace_bytes.restype = Z
+    lib.loma_decode_attn_rope.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, F, I, I, F, vp, Z, vp]
+    lib.loma_decode_attn_rope.restype = I
+    lib.loma_compress_step_rope.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, F, I, I, I, F, vp]
+    lib.loma_compress_step_rope.restype = I
+    lib.loma_memory_position_ids.argtypes = [I, I, I, I, ctypes.POINTER(I)]
+    lib.loma_memory_position_ids.restype = I
+    lib.loma_sample_position_ids.argtypes = [I, I, I, I, ctypes.POINTER(I)]
+    lib.loma_sample_position_ids.restype = I
     lib.loma_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, I, F, I, vp]
     lib.loma_prefill_attn.restype = I
     lib.loma_decode_workspace_bytes.argtypes = [I, I, I, I, I, I, I]
@@ -171,6 +180,46 @@ def loma_compress_step(q_mem, k_mem, v_mem, k_read, v_read, k_memcache, v_memcac
     return out
 
 
+def loma_compress_step_rope(q_mem, k_mem, v_mem, k_read, v_read, k_memcache, v_memcache, t, c, n_mem_chunks, scale,
+                            pos_first, pos_stride, rope_theta=10000.0, out=None, stream=None):
+    """loma_compress_step with q_mem and k_mem rotated on load by the ids pos_first + j * pos_stride."""
+    B, H, tt, d = q_mem.shape
+    if tt != t:
+        raise ValueError("q_mem must have t rows")
+    if out is None:
+        out = torch.empty_like(q_mem)
+    dt = q_mem.dtype
+    cap = k_memcache.shape[2]
+    args = [_dev(q_mem, "q_mem"), _dev(k_mem, "k_mem", q_mem.shape, dt), _dev(v_mem, "v_mem", q_mem.shape, dt),
+            _dev(k_read, "k_read", (B, H, t * c, d), dt), _dev(v_read, "v_read", (B, H, t * c, d), dt),
+            _dev(k_memcache, "k_memcache", (B, H, cap, d), dt), _dev(v_memcache, "v_memcache", (B, H, cap, d), dt),
+            _dev(out, "out", q_mem.shape, dt)]
+    rc = lib.loma_compress_step_rope(*args, B, H, d, t, c, n_mem_chunks, cap, float(scale), _dtype_code(q_mem),
+                                     int(pos_first), int(pos_stride), float(rope_theta), _stream(stream))
+    if rc != OK:
+        raise LomaError(rc, "loma_compress_step_rope")
+    return out
+
+
+def memory_position_ids(t, c, chunk, position_type=POS_INTERMITTENT):
+    """Ids of the t memory tokens of chunk `chunk` (host list)."""
+    buf = (ctypes.c_int * t)()
+    rc = lib.loma_memory_position_ids(t, c, chunk, position_type, buf)
+    if rc != OK:
+        raise LomaError(rc, "loma_memory_position_ids")
+    return list(buf)
+
+
+def sample_position_ids(t, c, n_chunks, position_type=POS_INTERMITTENT):
+    """Ids of every row of a restructured sample (host list of n_chunks * t * (2c + 1) ints)."""
+    n = n_chunks * t * (2 * c + 1)
+    buf = (ctypes.c_int * n)()
+    rc = lib.loma_sample_position_ids(t, c, n_chunks, position_type, buf)
+    if rc != OK:
+        raise LomaError(rc, "loma_sample_position_ids")
+    return list(buf)
+
+
 def loma_decode_workspace_bytes(B, H, d, t, c, n_mem_chunks, dtype=torch.bfloat16) -> int:
     code = F32 if dtype == torch.float32 else BF16
     return int(lib.loma_decode_workspace_bytes(B, H, d, t, c, n_mem_chunks, code))
@@ -200,6 +249,32 @@ def loma_decode_attn(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, t,
                               pws, nws, _stream(stream))
     if rc != OK:
         raise LomaError(rc, "loma_decode_attn")
+    return out
+
+
+def loma_decode_attn_rope(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, t, c, n_mem_chunks, read_fill, scale,
+                          pos, rope_theta=10000.0, out=None, workspace=None, stream=None):
+    """loma_decode_attn with q and k_new rotated on load by the new token's position id `pos`."""
+    B, H, one, d = q.shape
+    if one != 1:
+        raise ValueError("q must be [B, H, 1, d]")
+    if out is None:
+        out = torch.empty_like(q)
+    dt = q.dtype
+    pkn = None if k_new is None else _dev(k_new, "k_new", q.shape, dt)
+    pvn = None if v_new is None else _dev(v_new, "v_new", q.shape, dt)
+    cap = 0 if k_memcache is None else k_memcache.shape[2]
+    pkm = None if k_memcache is None else _dev(k_memcache, "k_memcache", (B, H, cap, d), dt)
+    pvm = None if v_memcache is None else _dev(v_memcache, "v_memcache", (B, H, cap, d), dt)
+    pws, nws = None, 0
+    if workspace is not None:
+        pws, nws = _dev(workspace, "workspace"), workspace.numel() * workspace.element_size()
+    rc = lib.loma_decode_attn_rope(_dev(q, "q"), pkn, pvn, pkm, pvm, _dev(k_read, "k_read", (B, H, t * c, d), dt),
+                                   _dev(v_read, "v_read", (B, H, t * c, d), dt), _dev(out, "out", q.shape, dt),
+                                   B, H, d, t, c, n_mem_chunks, cap, read_fill, float(scale), _dtype_code(q),
+                                   int(pos), float(rope_theta), pws, nws, _stream(stream))
+    if rc != OK:
+        raise LomaError(rc, "loma_decode_attn_rope")
     return out
 
 
