@@ -1,26 +1,33 @@
 #!/usr/bin/env python3
 """Benchmark of the LoMA attention hot path on one MI355X.
 
-One step = one pass of the whole hot path through a 32-layer, Llama-2-7B-shaped stack
-(every layer has its own tensors, so nothing is served from a cache warmed by the
-previous layer):
-    mask leg      32 x loma_mask_attn_fwd   B2 H32 d128 t16 c4, 28 chunks (S = 4032), bf16
-    compress leg  32 x loma_compress_step   B8 H32 d128 t16 c4, 64 prior chunks
-    decode leg    64 tokens x 32 layers x loma_decode_attn over 1040 memory KVs + the
-                  growing reading zone (one full reading zone: after 64 tokens the state is
-                  back at a compression boundary, so the step repeats exactly)
-`value` is the useful TFLOP/s of the mask leg (unmasked pairs only); the decode leg's
-GB/s is reported next to it.  Each leg is bracketed by HIP events on the launch stream.
+One step = one pass of the whole hot path at the two largest single-GPU configurations:
+    mask leg      1 x loma_mask_attn_fwd    config 4: B1 H32 d128 t32 c8, 60 chunks (S = 32640), bf16
+                                            (two tensor sets in rotation: a set is 1.07 GB, the Infinity Cache 256 MB)
+    compress leg  1 x loma_compress_step    config 5: B64 H32 d128 t16 c16, 512 prior chunks
+    decode leg    128 x loma_decode_attn    config 5: 8208 memory KVs + the reading zone growing from 1 to 128 rows
+                                            (8.9 GB of cache; after the leg the next step starts from the same state)
+`value` is the useful TFLOP/s of the mask leg (unmasked pairs only), the decode leg's GB/s is reported next to
+it, each against the chip's published peak; `roofline` describes the kernel the step spends its time in (decode),
+`roofline_long_context_mask` the mask kernel.  Legs are bracketed by HIP events on the launch stream.  The smaller
+configurations (2: Llama-7B-shaped mask pass, 3: generation with 32 layer caches), the prompt form, the gradients
+and the layered decode are timed afterwards on their own: median of 20 samples after 5 warm-up samples, every
+sample over tensors in rotation.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers 32] [--no-extra] [--no-high-ratio] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers 32] [--no-extra] [--no-cpu] [--no-peaks]
     python bench.py --copy-calibration     three plain 1 GiB device copies and nothing else: the known
                                            traffic the FETCH_SIZE / WRITE_SIZE counters are scaled by
+No random-number kernel runs on the GPU: tensors are tiled from a seeded pool drawn on the host (bit patterns
+differ from call to call of the tiling, values are unit normals), so the script also runs under counter collection.
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -29,14 +36,34 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_BF16_PEAK_TF = 2500.0  # MI355X dense bf16
-# HBM bytes per launch from rocprofv3 counter runs over this script (2.000 x FETCH_SIZE + 1.000 x WRITE_SIZE KiB,
-# the factors being what the same counters read for 1 GiB device copies: --copy-calibration).  Counters cannot be
-# read from inside a timed run, so these are the figures of the committed profile, not of this process.
-TRAFFIC_BYTES = {"decode": (2.0 * 68783.5 + 192) * 1024, "mask": (2.0 * 114529 + 64512) * 1024,
-                 "long_context_mask": (2.0 * 508406 + 261120) * 1024,
-                 # gradients: dQ pass + dK/dV pass (+ the sum of shared blocks at the Llama shape)
-                 "mask_bwd": (2.0 * (228791.1 + 119580.9 + 28695.9) + 123949.5 + 114688 + 14336) * 1024,
-                 "long_context_mask_bwd": (2.0 * (948240.5 + 1288200.7) + 515043.2 + 276480) * 1024}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "bench_hbm_traffic_pmc.md")
+
+
+def profile_traffic(path=TRAFFIC_PROFILE):
+    """HBM bytes per launch of every kernel listed in the committed counter profile: rocprofv3 FETCH_SIZE and
+    WRITE_SIZE (KiB per dispatch), each scaled by the factor the same counter showed for a plain copy of known
+    size (the profile's calibration table).  Counters cannot be read inside a timed run, so these are the
+    profile's figures, keyed by kernel name; a kernel that is not in the profile has no traffic figure."""
+    if not os.path.exists(path):
+        return {}
+    text = open(path).read()
+    factor = {}
+    for name in ("FETCH_SIZE", "WRITE_SIZE"):
+        m = re.search(r"^\|\s*%s\s*\|[^|]*\|[^|]*\|\s*x\s*([0-9.]+)\s*\|" % name, text, flags=re.M)
+        if not m:
+            return {}
+        factor[name] = float(m.group(1))
+    out = {}
+    for m in re.finditer(r"^\|\s*`([^`]+)`\s*\|[^|]*\|\s*\d+\s*\|\s*([0-9.]+)\s*\|\s*([0-9.]+)\s*\|", text, flags=re.M):
+        out[m.group(1)] = (factor["FETCH_SIZE"] * float(m.group(2)) + factor["WRITE_SIZE"] * float(m.group(3))) * 1024.0
+    return out
+
+
+def traffic_of(table, *kernels):
+    """Sum of the profile's traffic over the kernels of one call, or None if one of them is missing."""
+    if not all(k in table for k in kernels):
+        return None
+    return sum(table[k] for k in kernels)
 
 
 def parse():
@@ -44,75 +71,132 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--layers", type=int, default=32)
-    ap.add_argument("--no-extra", action="store_true", help="skip the long-context and high-ratio configurations")
-    ap.add_argument("--no-high-ratio", action="store_true", help="skip the high-ratio decode configuration (about 35 GB of state)")
+    ap.add_argument("--layers", type=int, default=32, help="layer caches of the generation configuration (extras)")
+    ap.add_argument("--samples", type=int, default=20, help="timed samples per extra (median reported)")
+    ap.add_argument("--no-extra", action="store_true", help="only the step: skip configurations 2 and 3, prompt form, gradients")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the measured MFMA-loop and stream peaks")
     ap.add_argument("--copy-calibration", action="store_true", help="run three 1 GiB device copies and exit")
     return ap.parse_args()
 
 
-def randn_bf16(shape, gen, scale=1.0):
-    import torch
-    out = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
-    flat = out.view(-1)
-    step = 1 << 26
-    for i in range(0, flat.numel(), step):
-        n = min(step, flat.numel() - i)
-        flat[i:i + n] = (torch.randn(n, generator=gen, device="cuda", dtype=torch.float32) * scale).to(torch.bfloat16)
-    return out
+class Pool:
+    """Seeded unit-normal bf16 values drawn once on the host; device tensors are tiled from it at offsets a host
+    generator picks.  (No GPU random-number kernel: those fault under rocprofv3 counter collection on this stack.)"""
 
-
-class Events:
-    def __init__(self):
+    def __init__(self, wl, seed, n=1 << 23):
+        import numpy as np
         import torch
+        rng = np.random.default_rng(seed)
+        bits = wl.f32_to_bf16_bits(rng.standard_normal(n, dtype=np.float32))
         self.torch = torch
-        self.pairs = {}
+        self.unit = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+        self.half = (self.unit.float() * 0.5).to(torch.bfloat16)      # exact: a power of two
+        self.rng = rng
+        self.n = n
 
-    def mark(self):
-        e = self.torch.cuda.Event(enable_timing=True)
-        e.record()
-        return e
+    def tensor(self, shape, scale=1.0):
+        torch = self.torch
+        src = self.unit if scale == 1.0 else self.half
+        assert scale in (1.0, 0.5)
+        out = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+        flat = out.view(-1)
+        piece = self.n // 2
+        for i in range(0, flat.numel(), piece):
+            m = min(piece, flat.numel() - i)
+            off = int(self.rng.integers(0, self.n - m + 1))
+            flat[i:i + m] = src[off:off + m]
+        return out
 
-    def add(self, name, a, b):
-        self.pairs.setdefault(name, []).append((a, b))
 
-    def total_ms(self, name):
-        return sum(a.elapsed_time(b) for a, b in self.pairs.get(name, []))
-
-
-def time_calls(fn, iters, warmup=2):
-    """Average milliseconds per call of fn(i) over `iters` back-to-back calls (HIP events)."""
+def time_median(fn, calls, samples=20, warmup=5):
+    """Median over `samples` samples of the milliseconds per call; a sample is `calls` back-to-back calls fn(i)
+    bracketed by HIP events on the current stream.  `warmup` untimed samples come first."""
     import torch
-    for i in range(warmup):
-        fn(i)
+    k = 0
+    for _ in range(warmup):
+        for _ in range(calls):
+            fn(k)
+            k += 1
     torch.cuda.synchronize()
-    a = torch.cuda.Event(enable_timing=True)
-    b = torch.cuda.Event(enable_timing=True)
-    a.record()
-    for i in range(iters):
-        fn(i)
-    b.record()
+    pairs = []
+    for _ in range(samples):
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(calls):
+            fn(k)
+            k += 1
+        b.record()
+        pairs.append((a, b))
     torch.cuda.synchronize()
-    return a.elapsed_time(b) / iters
+    return statistics.median(a.elapsed_time(b) for a, b in pairs) / calls
 
 
-def cpu_baseline(wl, layers):
-    """The fp64 oracle, as it stands, on the host cores: the mask leg of one step (the whole
-    mask pass of configs[1], once per layer; the layers reuse one set of host inputs)."""
+def measured_peaks(samples):
+    """What this machine reaches with nothing in the way: a pure v_mfma_f32_32x32x16_bf16 loop on every SIMD, a plain
+    copy and a plain read of 2 GiB."""
+    import torch
+    from paper_2401_09486_amd import build as hb
+    lib = ctypes.CDLL(hb.PEAKS_LIB)
+    vp = ctypes.c_void_p
+    lib.loma_peaks_mfma_loop.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
+    lib.loma_peaks_mfma_loop.restype = ctypes.c_double
+    lib.loma_peaks_stream_copy.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
+    lib.loma_peaks_stream_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, vp, vp]
+    st = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    wgs, iters = 256 * 8, 2048
+    flops = [0.0]
+
+    def mfma(i):
+        flops[0] = lib.loma_peaks_mfma_loop(wgs, iters, sink.data_ptr(), st)
+    ms = time_median(mfma, 1, samples)
+    assert flops[0] > 0
+    n = 1 << 31
+    src = torch.ones(n, dtype=torch.uint8, device="cuda")
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    cms = time_median(lambda i: lib.loma_peaks_stream_copy(src.data_ptr(), dst.data_ptr(), n, 256 * 16, st), 1, samples)
+    rms = time_median(lambda i: lib.loma_peaks_stream_read(src.data_ptr(), n, 256 * 16, sink.data_ptr(), st), 1, samples)
+    tf = flops[0] / (ms * 1e-3) / 1e12
+    return {"mfma_loop_tflops": tf, "mfma_loop_frac_of_peak": tf / MFMA_BF16_PEAK_TF,
+            "mfma_loop": f"v_mfma_f32_32x32x16_bf16, {wgs} workgroups x 4 waves x {iters * 8} instructions",
+            "stream_copy_GBps": 2.0 * n / (cms * 1e-3) / 1e9, "stream_read_GBps": n / (rms * 1e-3) / 1e9,
+            "stream_copy_frac_of_peak": 2.0 * n / (cms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "stream_read_frac_of_peak": n / (rms * 1e-3) / 1e9 / HBM_PEAK_GBS, "stream_bytes": n}
+
+
+def cpu_baseline(wl):
+    """The fp64 oracle as it stands, on the host cores, on a bounded sample of the step's workload: whole (b,h)
+    pairs of the long-context mask pass, and a few decode steps of a few (b,h) pairs of the high-ratio cache."""
+    import numpy as np
     from oracle import c_oracle
-    cfg = wl.CONFIGS[1]
-    q, k, v = wl.mask_inputs(cfg)
     c_oracle.build()
     threads = c_oracle.num_threads()
+    c4, c5 = wl.CONFIGS[3], wl.CONFIGS[4]
+    npairs = c4.B * c4.H
+    sub = wl.shrink(c4, H=npairs)
+    q, k, v = wl.mask_inputs(sub)
     t0 = time.perf_counter()
-    for _ in range(layers):
-        c_oracle.mask_attn(q, k, v, cfg.t, cfg.c, cfg.n_chunks, cfg.scale)
-    dt = time.perf_counter() - t0
-    flops = wl.mask_pass_useful_flops(cfg) * layers
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s (useful, fp64)", "cores": threads, "kind": "oracle",
-            "seconds": dt, "sample": f"mask leg of one step: whole mask pass of {cfg.name} (all {cfg.B * cfg.H} (b,h), "
-                                     f"all {cfg.S} rows) x {layers} layers"}
+    c_oracle.mask_attn(q, k, v, sub.t, sub.c, sub.n_chunks, sub.scale)
+    dt_mask = time.perf_counter() - t0
+    flops = wl.mask_pass_useful_flops(sub)
+    # decode: 64 (b,h) pairs, 64 steps over 8192 memory keys + the first reading rows
+    nb, nsteps = 64, 64
+    g = wl.shrink(c5, B=1, H=nb, steps=nsteps)
+    st = wl.gen_initial_state(g)
+    orc = c_oracle.GenerationCache(st["k_mem"], st["v_mem"], g.prior_chunks, st["k_read"], st["v_read"], 0, g.t, g.c, g.scale)
+    toks = [wl.gen_step_inputs(g, s) for s in range(nsteps)]
+    t0 = time.perf_counter()
+    for s in range(nsteps):
+        orc.decode(*toks[s])
+    dt_dec = time.perf_counter() - t0
+    dec_bytes = sum(wl.decode_bytes(1, nb, g.d, g.prior_chunks * g.t + s + 1, g.dtype) for s in range(nsteps))
+    return {"value": flops / dt_mask / 1e12, "unit": "TFLOP/s (useful, fp64, mask pass)", "cores": threads, "kind": "oracle",
+            "seconds": dt_mask + dt_dec, "decode_GBps": dec_bytes / dt_dec / 1e9,
+            "sample": f"mask leg: all {sub.S} rows of {npairs} of the {c4.B * c4.H} (b,h) pairs of {c4.name} ({dt_mask:.1f} s); "
+                      f"decode leg: {nsteps} steps of {nb} of the {c5.B * c5.H} (b,h) pairs of {c5.name} over {g.prior_chunks * g.t} "
+                      f"memory KVs ({dt_dec:.1f} s)"}
 
 
 def main():
@@ -135,194 +219,226 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read_per_copy": 1 << 30, "bytes_written_per_copy": 1 << 30, "copies": 3}}))
         return
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(wl.SEED_BASE)
-    L = args.layers
-    mc, gc = wl.CONFIGS[1], wl.CONFIGS[2]
+    pool = Pool(wl, wl.SEED_BASE)
+    traffic = profile_traffic()
+    K, NS = args.steps, args.samples
+    c2, c3, c4, c5 = wl.CONFIGS[1], wl.CONFIGS[2], wl.CONFIGS[3], wl.CONFIGS[4]
 
-    # ---- per-layer tensors ---------------------------------------------------------------------
-    mshape = (mc.B, mc.H, mc.S, mc.d)
-    mask_layers = [tuple(randn_bf16(mshape, gen, mc.value_scale) for _ in range(3)) + (torch.empty(mshape, dtype=torch.bfloat16, device="cuda"),)
-                   for _ in range(L)]
-    cap = (gc.prior_chunks + 1) * gc.t
-    gen_layers = []
-    for _ in range(L):
-        gen_layers.append({
-            "k_mem": randn_bf16((gc.B, gc.H, cap, gc.d), gen), "v_mem": randn_bf16((gc.B, gc.H, cap, gc.d), gen),
-            "k_read": randn_bf16((gc.B, gc.H, gc.R, gc.d), gen), "v_read": randn_bf16((gc.B, gc.H, gc.R, gc.d), gen),
-            "q_m": randn_bf16((gc.B, gc.H, gc.t, gc.d), gen), "k_m": randn_bf16((gc.B, gc.H, gc.t, gc.d), gen),
-            "v_m": randn_bf16((gc.B, gc.H, gc.t, gc.d), gen),
-            "q": randn_bf16((gc.B, gc.H, 1, gc.d), gen), "k_new": randn_bf16((gc.B, gc.H, 1, gc.d), gen),
-            "v_new": randn_bf16((gc.B, gc.H, 1, gc.d), gen),
-            "out_m": torch.empty((gc.B, gc.H, gc.t, gc.d), dtype=torch.bfloat16, device="cuda"),
-            "out": torch.empty((gc.B, gc.H, 1, gc.d), dtype=torch.bfloat16, device="cuda"),
-        })
-    ws = torch.empty(max(loma.loma_decode_workspace_bytes(gc.B, gc.H, gc.d, gc.t, gc.c, gc.prior_chunks + 1), 16),
-                     dtype=torch.uint8, device="cuda")
-    ev = Events()
+    def bf16_empty(shape):
+        return torch.empty(shape, dtype=torch.bfloat16, device="cuda")
 
-    def step(record):
-        e0 = ev.mark()
-        for (q, k, v, o) in mask_layers:
-            loma.loma_mask_attn_fwd(q, k, v, mc.t, mc.c, mc.n_chunks, mc.scale, out=o)
-        e1 = ev.mark()
-        for g in gen_layers:
-            loma.loma_compress_step(g["q_m"], g["k_m"], g["v_m"], g["k_read"], g["v_read"], g["k_mem"], g["v_mem"],
-                                    gc.t, gc.c, gc.prior_chunks, gc.scale, out=g["out_m"])
-        e2 = ev.mark()
-        for tok in range(gc.R):
-            for g in gen_layers:
-                loma.loma_decode_attn(g["q"], g["k_new"], g["v_new"], g["k_mem"], g["v_mem"], g["k_read"], g["v_read"],
-                                      gc.t, gc.c, gc.prior_chunks + 1, tok, gc.scale, out=g["out"], workspace=ws)
-        e3 = ev.mark()
+    # ---- the step: config 4 mask pass, config 5 compress + 128 decode steps -------------------------------------
+    shp4 = (c4.B, c4.H, c4.S, c4.d)
+    sets4 = [tuple(pool.tensor(shp4, c4.value_scale) for _ in range(3)) + (bf16_empty(shp4),) for _ in range(2)]
+    cap5 = c5.mem_capacity
+    st5 = {"k_mem": pool.tensor((c5.B, c5.H, cap5, c5.d)), "v_mem": pool.tensor((c5.B, c5.H, cap5, c5.d))}
+    reads5 = [(pool.tensor((c5.B, c5.H, c5.R, c5.d)), pool.tensor((c5.B, c5.H, c5.R, c5.d))) for _ in range(2)]
+    qm5, km5, vm5 = (pool.tensor((c5.B, c5.H, c5.t, c5.d), s) for s in (c5.q_scale, 1.0, 1.0))
+    om5 = bf16_empty((c5.B, c5.H, c5.t, c5.d))
+    q5 = pool.tensor((c5.B, c5.H, 1, c5.d), c5.q_scale)
+    kn5, vn5 = pool.tensor((c5.B, c5.H, 1, c5.d)), pool.tensor((c5.B, c5.H, 1, c5.d))
+    o5 = bf16_empty((c5.B, c5.H, 1, c5.d))
+    ws5 = torch.empty(max(loma.loma_decode_workspace_bytes(c5.B, c5.H, c5.d, c5.t, c5.c, c5.prior_chunks + 1), 16),
+                      dtype=torch.uint8, device="cuda")
+    nm5 = c5.prior_chunks + 1
+    marks = []
+
+    def mark():
+        e = torch.cuda.Event(enable_timing=True)
+        e.record()
+        return e
+
+    def step(i, record):
+        q, k, v, o = sets4[i % 2]
+        kr, vr = reads5[i % 2]
+        e0 = mark()
+        loma.loma_mask_attn_fwd(q, k, v, c4.t, c4.c, c4.n_chunks, c4.scale, out=o)
+        e1 = mark()
+        loma.loma_compress_step(qm5, km5, vm5, kr, vr, st5["k_mem"], st5["v_mem"], c5.t, c5.c, c5.prior_chunks, c5.scale, out=om5)
+        e2 = mark()
+        for f in range(c5.steps):
+            loma.loma_decode_attn(q5, kn5, vn5, st5["k_mem"], st5["v_mem"], kr, vr, c5.t, c5.c, nm5, f, c5.scale, out=o5,
+                                  workspace=ws5)
+        e3 = mark()
         if record:
-            ev.add("mask", e0, e1)
-            ev.add("compress", e1, e2)
-            ev.add("decode", e2, e3)
+            marks.append((e0, e1, e2, e3))
 
-    for _ in range(args.warmup):
-        step(False)
+    for i in range(args.warmup):
+        step(i, False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(True)
+    for i in range(K):
+        step(args.warmup + i, True)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    K = args.steps
 
-    # ---- mask leg --------------------------------------------------------------------------------
-    mask_ms = ev.total_ms("mask") / (K * L)                    # per launch
-    mask_flops = wl.mask_pass_useful_flops(mc)
-    mask_bytes = wl.mask_pass_bytes(mc)
+    mask_ms = sum(a.elapsed_time(b) for a, b, _, _ in marks) / K
+    comp_ms = sum(b.elapsed_time(c) for _, b, c, _ in marks) / K
+    dec_ms = sum(c.elapsed_time(d) for _, _, c, d in marks) / (K * c5.steps)
+    mask_flops = wl.mask_pass_useful_flops(c4)
+    mask_bytes = wl.mask_pass_bytes(c4)
     mask_tf = mask_flops / (mask_ms * 1e-3) / 1e12
-    mask_gbs = mask_bytes / (mask_ms * 1e-3) / 1e9
-    # ---- compress leg ----------------------------------------------------------------------------
-    comp_ms = ev.total_ms("compress") / (K * L)
-    comp_bytes = wl.compress_bytes(gc.B, gc.H, gc.d, gc.t, gc.c, gc.dtype)
-    comp_flops = wl.compress_useful_flops(gc.B, gc.H, gc.d, gc.t, gc.c)
-    # ---- decode leg ------------------------------------------------------------------------------
-    dec_calls = K * L * gc.R
-    dec_ms = ev.total_ms("decode") / dec_calls
-    n_mem_keys = (gc.prior_chunks + 1) * gc.t
-    dec_bytes = sum(wl.decode_bytes(gc.B, gc.H, gc.d, n_mem_keys + f + 1, gc.dtype) for f in range(gc.R)) / gc.R
+    dec_bytes = sum(wl.decode_bytes(c5.B, c5.H, c5.d, nm5 * c5.t + f + 1, c5.dtype) for f in range(c5.steps)) / c5.steps
     dec_gbs = dec_bytes / (dec_ms * 1e-3) / 1e9
+    comp_bytes = wl.compress_bytes(c5.B, c5.H, c5.d, c5.t, c5.c, c5.dtype)
+    comp_flops = wl.compress_useful_flops(c5.B, c5.H, c5.d, c5.t, c5.c)
+    KMASK4, KDEC5, KCOMB5, KCOMP5 = ("mask_attn_kernel<128, 4, 64, 1>", "decode_split_kernel<128, 4, false, false>",
+                                     "decode_combine_kernel<128, false>", "compress_kernel<128, 1, 32, false>")
 
     result = {
         "metric": "LoMA-mask attn useful TFLOP/s + decode GB/s (frac of MI355X roofline)",
         "value": mask_tf, "unit": "TFLOP/s (useful, mask pass)",
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": wall_ms / K,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{mc.name} (B{mc.B} H{mc.H} d{mc.d} t{mc.t} c{mc.c} n{mc.n_chunks}, S={mc.S}) x {L} layers"
-                               f" + {gc.name} slice (1 compress + {gc.R} decode tokens) x {L} layers",
-                   "layers": L},
-        "decode": {"value": dec_gbs, "unit": "GB/s (algorithmic)", "frac_of_hbm_peak": dec_gbs / HBM_PEAK_GBS,
-                   "us_per_call": dec_ms * 1e3, "bytes_per_call": dec_bytes, "calls": dec_calls,
-                   "keys": f"{n_mem_keys}+1..{n_mem_keys}+{gc.R}"},
-        "mask": {"useful_tflops": mask_tf, "frac_of_mfma_peak": mask_tf / MFMA_BF16_PEAK_TF, "us_per_call": mask_ms * 1e3,
-                 "algorithmic_GBps": mask_gbs, "frac_of_hbm_peak": mask_gbs / HBM_PEAK_GBS, "useful_flops": mask_flops,
-                 "bytes": mask_bytes},
-        "compress": {"us_per_call": comp_ms * 1e3, "algorithmic_GBps": comp_bytes / (comp_ms * 1e-3) / 1e9,
-                     "useful_tflops": comp_flops / (comp_ms * 1e-3) / 1e12},
-        # dominant kernel of the step by time: the split-K decode kernel (HBM-bound)
-        "roofline": {"kernel": "decode_split_kernel<128, 16>", "bound": "hbm", "achieved": dec_gbs,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dec_gbs / HBM_PEAK_GBS,
-                     "traffic": TRAFFIC_BYTES["decode"]},
-        # the mask-pass kernel at this shape is HBM-bound too (63 flop/byte)
-        "roofline_mask": {"kernel": "mask_attn_kernel<128, 2, 32, 1>", "bound": "hbm", "achieved": mask_gbs,
-                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": mask_gbs / HBM_PEAK_GBS,
-                          "traffic": TRAFFIC_BYTES["mask"]},
+        "config": {"workload": f"{c4.name} (B{c4.B} H{c4.H} d{c4.d} t{c4.t} c{c4.c} n{c4.n_chunks}, S={c4.S}) mask pass + "
+                               f"{c5.name} (B{c5.B} H{c5.H} d{c5.d} t{c5.t} c{c5.c}, {c5.prior_chunks * c5.t} memory KVs) "
+                               f"1 compress + {c5.steps} decode steps"},
+        "long_context_mask": {"workload": c4.name, "useful_tflops": mask_tf, "frac_of_mfma_peak": mask_tf / MFMA_BF16_PEAK_TF,
+                              "us_per_call": mask_ms * 1e3, "useful_flops": mask_flops, "bytes": mask_bytes,
+                              "algorithmic_GBps": mask_bytes / (mask_ms * 1e-3) / 1e9,
+                              "frac_of_hbm_peak": mask_bytes / (mask_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "high_ratio_decode": {"workload": c5.name, "value": dec_gbs, "unit": "GB/s (algorithmic)",
+                              "frac_of_hbm_peak": dec_gbs / HBM_PEAK_GBS, "ms_per_step": dec_ms, "bytes_per_step": dec_bytes,
+                              "keys": f"{nm5 * c5.t}+1..{nm5 * c5.t}+{c5.steps}", "calls": K * c5.steps,
+                              "compress_us": comp_ms * 1e3, "compress_GBps": comp_bytes / (comp_ms * 1e-3) / 1e9,
+                              "compress_useful_tflops": comp_flops / (comp_ms * 1e-3) / 1e12},
+        # the kernel the step spends its time in: the split-K decode kernel (HBM-bound); the figure includes the
+        # tiny combine kernel that follows every launch of it
+        "roofline": {"kernel": KDEC5, "bound": "hbm", "achieved": dec_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": dec_gbs / HBM_PEAK_GBS, "traffic": traffic_of(traffic, KDEC5, KCOMB5)},
+        "roofline_long_context_mask": {"kernel": KMASK4, "bound": "mfma", "achieved": mask_tf, "peak": MFMA_BF16_PEAK_TF,
+                                       "unit": "TFLOP/s", "frac": mask_tf / MFMA_BF16_PEAK_TF,
+                                       "traffic": traffic_of(traffic, KMASK4)},
+        "roofline_high_ratio_compress": {"kernel": KCOMP5, "bound": "hbm", "achieved": comp_bytes / (comp_ms * 1e-3) / 1e9,
+                                         "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                         "frac": comp_bytes / (comp_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                         "traffic": traffic_of(traffic, KCOMP5)},
     }
 
-    # ---- prompt form on the generation shape: a whole reading zone of new tokens per call --------------
-    if not args.no_extra:
-        pre = [tuple(randn_bf16((gc.B, gc.H, gc.R, gc.d), gen) for _ in range(3)) + (torch.empty((gc.B, gc.H, gc.R, gc.d), dtype=torch.bfloat16, device="cuda"),)
-               for _ in range(min(L, 8))]
-        pms = time_calls(lambda i: loma.loma_prefill_attn(pre[i % len(pre)][0], pre[i % len(pre)][1], pre[i % len(pre)][2],
-                                                          gen_layers[i % L]["k_mem"], gen_layers[i % L]["v_mem"],
-                                                          gen_layers[i % L]["k_read"], gen_layers[i % L]["v_read"],
-                                                          gc.t, gc.c, gc.prior_chunks + 1, 0, gc.scale, out=pre[i % len(pre)][3]), 4 * L)
-        nbh = gc.B * gc.H
-        pbytes = nbh * (2 * n_mem_keys * gc.d + 6 * gc.R * gc.d) * 2   # cache read once; q, k, v in, out and the appended K/V out
-        pflops = 4.0 * gc.d * nbh * (gc.R * n_mem_keys + gc.R * (gc.R + 1) / 2)
-        result["prefill"] = {"workload": f"{gc.name}: {gc.R} new tokens per sequence over {n_mem_keys} memory KVs",
-                             "us_per_call": pms * 1e3, "algorithmic_GBps": pbytes / (pms * 1e-3) / 1e9,
-                             "frac_of_hbm_peak": pbytes / (pms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                             "useful_tflops": pflops / (pms * 1e-3) / 1e12,
-                             "vs_token_by_token": gc.R * dec_ms / pms}   # time of the same tokens through loma_decode_attn / this
+    def roof_hbm(kernels, gbs):
+        return {"kernel": " + ".join(kernels), "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": gbs / HBM_PEAK_GBS, "traffic": traffic_of(traffic, *kernels)}
 
-    # ---- gradients of the mask pass (forward output and lse kept, as a training step would) --------------
-    def time_backward(cfg, q, k, v, o):
-        lse = torch.empty((cfg.B, cfg.H, cfg.S), dtype=torch.float32, device="cuda")
-        loma.loma_mask_attn_fwd(q, k, v, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, out=o, lse=lse)
-        g = randn_bf16(tuple(q.shape), gen)
-        grads = [torch.empty_like(q) for _ in range(3)]
+    def roof_mfma(kernels, tf):
+        return {"kernel": " + ".join(kernels), "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TF, "unit": "TFLOP/s",
+                "frac": tf / MFMA_BF16_PEAK_TF, "traffic": traffic_of(traffic, *kernels)}
+
+    def time_backward(cfg, sets):
+        """sets: (q, k, v, out) tuples; forward once per set for out and lse, then the gradients in rotation."""
+        packs = []
+        for (q, k, v, o) in sets:
+            lse = torch.empty((cfg.B, cfg.H, cfg.S), dtype=torch.float32, device="cuda")
+            loma.loma_mask_attn_fwd(q, k, v, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, out=o, lse=lse)
+            packs.append((q, k, v, o, lse, pool.tensor(tuple(q.shape)), [torch.empty_like(q) for _ in range(3)]))
         wsb = torch.empty(loma.loma_mask_attn_bwd_workspace_bytes(cfg.B, cfg.H, cfg.d, cfg.t, cfg.c, cfg.n_chunks),
                           dtype=torch.uint8, device="cuda")
-        ms = time_calls(lambda i: loma.loma_mask_attn_bwd(q, k, v, o, lse, g, cfg.t, cfg.c, cfg.n_chunks, cfg.scale,
-                                                          dq=grads[0], dk=grads[1], dv=grads[2], workspace=wsb), 10)
+
+        def call(i):
+            q, k, v, o, lse, g, gr = packs[i % len(packs)]
+            loma.loma_mask_attn_bwd(q, k, v, o, lse, g, cfg.t, cfg.c, cfg.n_chunks, cfg.scale, dq=gr[0], dk=gr[1], dv=gr[2],
+                                    workspace=wsb)
+        ms = time_median(call, len(packs), NS)
         fl = 2.5 * wl.mask_pass_useful_flops(cfg)      # five products per visible pair against the forward's two
         by = 2.0 * wl.mask_pass_bytes(cfg)             # q, k, v, out, dout in; dq, dk, dv out
         return {"workload": cfg.name, "us_per_call": ms * 1e3, "useful_tflops": fl / (ms * 1e-3) / 1e12,
                 "frac_of_mfma_peak": fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, "useful_flops": fl,
-                "algorithmic_GBps": by / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+                "algorithmic_GBps": by / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "tensor_sets": len(packs)}
 
     if not args.no_extra:
-        result["mask_bwd"] = time_backward(mc, *mask_layers[0])
-        b2 = result["mask_bwd"]
-        result["roofline_mask_bwd"] = {"kernel": "bwd_dkv_kernel<128, 2> (+ bwd_dq_kernel<128, 2>, bwd_reduce_kernel<128>)", "bound": "hbm",
-                                       "achieved": b2["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                       "frac": b2["frac_of_hbm_peak"], "traffic": TRAFFIC_BYTES["mask_bwd"]}
+        # ---- config 4 gradients (one set: 2.4 GB of tensors per call) -----------------------------------------------
+        bw = time_backward(c4, sets4[:1])
+        result["long_context_mask_bwd"] = bw
+        result["roofline_long_context_mask_bwd"] = roof_mfma(("bwd_dq_kernel<128, 4>", "bwd_dkv_kernel<128, 4>"), bw["useful_tflops"])
+        del sets4
+        torch.cuda.empty_cache()
 
-    # ---- the other single-GPU configurations, timed on their own ---------------------------------
-    if not args.no_extra:
-        del mask_layers
+        # ---- config 2: Llama-7B-shaped mask pass and its gradients, tensor sets in rotation --------------------------
+        shp2 = (c2.B, c2.H, c2.S, c2.d)
+        sets2 = [tuple(pool.tensor(shp2, c2.value_scale) for _ in range(3)) + (bf16_empty(shp2),) for _ in range(8)]
+        ms = time_median(lambda i: loma.loma_mask_attn_fwd(*sets2[i % 8][:3], c2.t, c2.c, c2.n_chunks, c2.scale, out=sets2[i % 8][3]), 8, NS)
+        fl2, by2 = wl.mask_pass_useful_flops(c2), wl.mask_pass_bytes(c2)
+        result["mask"] = {"workload": c2.name, "useful_tflops": fl2 / (ms * 1e-3) / 1e12,
+                          "frac_of_mfma_peak": fl2 / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, "us_per_call": ms * 1e3,
+                          "algorithmic_GBps": by2 / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": by2 / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                          "useful_flops": fl2, "bytes": by2, "tensor_sets": 8}
+        result["roofline_mask"] = roof_hbm(("mask_attn_kernel<128, 2, 32, 1>",), by2 / (ms * 1e-3) / 1e9)
+        b2 = time_backward(c2, sets2[:3])
+        result["mask_bwd"] = b2
+        result["roofline_mask_bwd"] = roof_hbm(("bwd_dq_kernel<128, 2>", "bwd_dkv_kernel<128, 2>", "bwd_reduce_kernel<128>"),
+                                               b2["algorithmic_GBps"])
+        del sets2
         torch.cuda.empty_cache()
-        c4 = wl.CONFIGS[3]
-        shp = (c4.B, c4.H, c4.S, c4.d)
-        sets = [tuple(randn_bf16(shp, gen, c4.value_scale) for _ in range(3)) + (torch.empty(shp, dtype=torch.bfloat16, device="cuda"),)
-                for _ in range(2)]
-        ms = time_calls(lambda i: loma.loma_mask_attn_fwd(*sets[i % 2][:3], c4.t, c4.c, c4.n_chunks, c4.scale, out=sets[i % 2][3]), 10)
-        fl = wl.mask_pass_useful_flops(c4)
-        result["long_context_mask"] = {"workload": c4.name, "us_per_call": ms * 1e3, "useful_tflops": fl / (ms * 1e-3) / 1e12,
-                                       "frac_of_mfma_peak": fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF,
-                                       "algorithmic_GBps": wl.mask_pass_bytes(c4) / (ms * 1e-3) / 1e9}
-        result["roofline_long_context_mask"] = {"kernel": "mask_attn_kernel<128, 4, 64, 1>", "bound": "mfma",
-                                                "achieved": fl / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TF,
-                                                "unit": "TFLOP/s", "frac": fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF,
-                                                "traffic": TRAFFIC_BYTES["long_context_mask"]}
-        result["long_context_mask_bwd"] = time_backward(c4, *sets[0])
-        bw = result["long_context_mask_bwd"]
-        # its dominant kernel: the dK/dV pass (four of the seven matrix products the two launches issue)
-        result["roofline_long_context_mask_bwd"] = {"kernel": "bwd_dkv_kernel<128, 4> (+ bwd_dq_kernel<128, 4>)",
-                                                    "bound": "mfma", "achieved": bw["useful_tflops"], "peak": MFMA_BF16_PEAK_TF,
-                                                    "unit": "TFLOP/s", "frac": bw["frac_of_mfma_peak"],
-                                                    "traffic": TRAFFIC_BYTES["long_context_mask_bwd"]}
-        del sets
-    if not args.no_extra and not args.no_high_ratio:
-        del gen_layers
-        torch.cuda.empty_cache()
-        c5 = wl.CONFIGS[4]
-        st = wl.gen_initial_state_device(c5)
-        qm, km, vm = (randn_bf16((c5.B, c5.H, c5.t, c5.d), gen) for _ in range(3))
-        om = torch.empty_like(qm)
-        q5 = randn_bf16((c5.B, c5.H, 1, c5.d), gen, c5.q_scale)
-        kn, vn = randn_bf16((c5.B, c5.H, 1, c5.d), gen), randn_bf16((c5.B, c5.H, 1, c5.d), gen)
-        o5 = torch.empty_like(q5)
-        ws5 = torch.empty(max(loma.loma_decode_workspace_bytes(c5.B, c5.H, c5.d, c5.t, c5.c, c5.prior_chunks + 1), 16),
+
+        # ---- config 3: generation with one cache per layer (32 x 151 MB), per-layer launches and one launch for all --
+        L = args.layers
+        cap3 = (c3.prior_chunks + 1) * c3.t
+        lay = []
+        for _ in range(L):
+            lay.append({"k_mem": pool.tensor((c3.B, c3.H, cap3, c3.d)), "v_mem": pool.tensor((c3.B, c3.H, cap3, c3.d)),
+                        "k_read": pool.tensor((c3.B, c3.H, c3.R, c3.d)), "v_read": pool.tensor((c3.B, c3.H, c3.R, c3.d)),
+                        "q_m": pool.tensor((c3.B, c3.H, c3.t, c3.d)), "k_m": pool.tensor((c3.B, c3.H, c3.t, c3.d)),
+                        "v_m": pool.tensor((c3.B, c3.H, c3.t, c3.d)), "q": pool.tensor((c3.B, c3.H, 1, c3.d)),
+                        "k_new": pool.tensor((c3.B, c3.H, 1, c3.d)), "v_new": pool.tensor((c3.B, c3.H, 1, c3.d)),
+                        "out_m": bf16_empty((c3.B, c3.H, c3.t, c3.d)), "out": bf16_empty((c3.B, c3.H, 1, c3.d))})
+        ws3 = torch.empty(max(loma.loma_decode_layers_workspace_bytes(L, c3.B, c3.H, c3.d, c3.t, c3.c, c3.prior_chunks + 1), 16),
                           dtype=torch.uint8, device="cuda")
-        cms = time_calls(lambda i: loma.loma_compress_step(qm, km, vm, st["k_read"], st["v_read"], st["k_mem"], st["v_mem"],
-                                                           c5.t, c5.c, c5.prior_chunks, c5.scale, out=om), 5)
-        nm = c5.prior_chunks + 1
-        dms = time_calls(lambda i: loma.loma_decode_attn(q5, kn, vn, st["k_mem"], st["v_mem"], st["k_read"], st["v_read"],
-                                                         c5.t, c5.c, nm, i % c5.steps, c5.scale, out=o5, workspace=ws5), c5.steps)
-        b5 = sum(wl.decode_bytes(c5.B, c5.H, c5.d, nm * c5.t + f + 1, c5.dtype) for f in range(c5.steps)) / c5.steps
-        result["high_ratio_decode"] = {"workload": c5.name, "ms_per_step": dms, "algorithmic_GBps": b5 / (dms * 1e-3) / 1e9,
-                                       "frac_of_hbm_peak": b5 / (dms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                       "compress_us": cms * 1e3,
-                                       "compress_GBps": wl.compress_bytes(c5.B, c5.H, c5.d, c5.t, c5.c, c5.dtype) / (cms * 1e-3) / 1e9}
+        nm3 = c3.prior_chunks + 1
+        nkeys3 = nm3 * c3.t
+
+        def dec_single(i):
+            g, f = lay[i % L], (i // L) % c3.R
+            loma.loma_decode_attn(g["q"], g["k_new"], g["v_new"], g["k_mem"], g["v_mem"], g["k_read"], g["v_read"],
+                                  c3.t, c3.c, nm3, f, c3.scale, out=g["out"], workspace=ws3)
+        dms = time_median(dec_single, L * c3.R, NS, warmup=2)      # a sample = 64 tokens through all layers
+        db3 = sum(wl.decode_bytes(c3.B, c3.H, c3.d, nkeys3 + f + 1, c3.dtype) for f in range(c3.R)) / c3.R
+        result["decode"] = {"workload": f"{c3.name}: {L} layer caches, one launch per layer and token", "value": db3 / (dms * 1e-3) / 1e9,
+                            "unit": "GB/s (algorithmic)", "frac_of_hbm_peak": db3 / (dms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "us_per_call": dms * 1e3, "bytes_per_call": db3, "keys": f"{nkeys3}+1..{nkeys3}+{c3.R}"}
+        result["roofline_decode"] = roof_hbm(("decode_split_kernel<128, 16, false, false>",), db3 / (dms * 1e-3) / 1e9)
+        tabs = {n: loma.pointer_table([g[n] for g in lay]) for n in ("q", "k_new", "v_new", "k_mem", "v_mem", "k_read", "v_read", "out")}
+
+        def dec_layers(i):
+            loma.loma_decode_attn_layers(tabs["q"], tabs["k_new"], tabs["v_new"], tabs["k_mem"], tabs["v_mem"], tabs["k_read"],
+                                         tabs["v_read"], tabs["out"], L, c3.B, c3.H, c3.d, c3.t, c3.c, nm3, cap3, i % c3.R, c3.scale,
+                                         workspace=ws3)
+        lms = time_median(dec_layers, c3.R, NS, warmup=2)          # a sample = 64 tokens, one launch per token
+        result["decode_layers"] = {"workload": f"{c3.name}: {L} layer caches, one launch per token for all layers",
+                                   "value": L * db3 / (lms * 1e-3) / 1e9, "unit": "GB/s (algorithmic)",
+                                   "frac_of_hbm_peak": L * db3 / (lms * 1e-3) / 1e9 / HBM_PEAK_GBS, "us_per_token": lms * 1e3,
+                                   "us_per_token_layer_by_layer": L * dms * 1e3, "speedup_vs_layer_by_layer": L * dms / lms}
+        result["roofline_decode_layers"] = roof_hbm(("decode_split_kernel<128, 16, true, false>",), L * db3 / (lms * 1e-3) / 1e9)
+        cms = time_median(lambda i: loma.loma_compress_step(lay[i % L]["q_m"], lay[i % L]["k_m"], lay[i % L]["v_m"], lay[i % L]["k_read"],
+                                                            lay[i % L]["v_read"], lay[i % L]["k_mem"], lay[i % L]["v_mem"], c3.t, c3.c,
+                                                            c3.prior_chunks, c3.scale, out=lay[i % L]["out_m"]), L, NS)
+        cb3 = wl.compress_bytes(c3.B, c3.H, c3.d, c3.t, c3.c, c3.dtype)
+        result["compress"] = {"workload": c3.name, "us_per_call": cms * 1e3, "algorithmic_GBps": cb3 / (cms * 1e-3) / 1e9,
+                              "useful_tflops": wl.compress_useful_flops(c3.B, c3.H, c3.d, c3.t, c3.c) / (cms * 1e-3) / 1e12}
+        # the prompt form on the same caches: a whole reading zone of new tokens per call
+        npre = min(L, 8)
+        pre = [tuple(pool.tensor((c3.B, c3.H, c3.R, c3.d)) for _ in range(3)) + (bf16_empty((c3.B, c3.H, c3.R, c3.d)),) for _ in range(npre)]
+        pms = time_median(lambda i: loma.loma_prefill_attn(pre[i % npre][0], pre[i % npre][1], pre[i % npre][2], lay[i % L]["k_mem"],
+                                                           lay[i % L]["v_mem"], lay[i % L]["k_read"], lay[i % L]["v_read"], c3.t, c3.c,
+                                                           nm3, 0, c3.scale, out=pre[i % npre][3]), L, NS)
+        nbh3 = c3.B * c3.H
+        pbytes = nbh3 * (2 * nkeys3 * c3.d + 6 * c3.R * c3.d) * 2   # cache read once; q, k, v in, out and the appended K/V out
+        pflops = 4.0 * c3.d * nbh3 * (c3.R * nkeys3 + c3.R * (c3.R + 1) / 2)
+        result["prefill"] = {"workload": f"{c3.name}: {c3.R} new tokens per sequence over {nkeys3} memory KVs",
+                             "us_per_call": pms * 1e3, "algorithmic_GBps": pbytes / (pms * 1e-3) / 1e9,
+                             "frac_of_hbm_peak": pbytes / (pms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             "useful_tflops": pflops / (pms * 1e-3) / 1e12, "vs_token_by_token": c3.R * dms / pms}
+        result["roofline_prefill"] = roof_hbm(("prefill_kernel<128, 4, 64, 2, 4>",), pbytes / (pms * 1e-3) / 1e9)
+        del lay, pre, tabs
+        torch.cuda.empty_cache()
+
+    if not args.no_peaks:
+        mp = measured_peaks(NS)
+        result["measured_peaks"] = mp
+        result["long_context_mask"]["frac_of_measured_mfma_loop"] = mask_tf / mp["mfma_loop_tflops"]
+        result["high_ratio_decode"]["frac_of_measured_stream_read"] = dec_gbs / mp["stream_read_GBps"]
 
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(wl, L)
+        result["cpu_baseline"] = cpu_baseline(wl)
 
     print(json.dumps(result))
 
