@@ -282,7 +282,7 @@ def main():
     dec_gbs = dec_bytes / (dec_ms * 1e-3) / 1e9
     comp_bytes = wl.compress_bytes(c5.B, c5.H, c5.d, c5.t, c5.c, c5.dtype)
     comp_flops = wl.compress_useful_flops(c5.B, c5.H, c5.d, c5.t, c5.c)
-    KMASK4, KDEC5, KCOMB5, KCOMP5 = ("mask_attn_kernel<128, 4, 64, 1>", "decode_split_kernel<128, 4, false, false>",
+    KMASK4, KDEC5, KCOMB5, KCOMP5 = ("mask_attn_kernel<128, 4, 64, true>", "decode_split_kernel<128, 4, false, false>",
                                      "decode_combine_kernel<128, false>", "compress_kernel<128, 1, 32, false>")
 
     result = {
@@ -362,7 +362,7 @@ def main():
                           "frac_of_mfma_peak": fl2 / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, "us_per_call": ms * 1e3,
                           "algorithmic_GBps": by2 / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": by2 / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                           "useful_flops": fl2, "bytes": by2, "tensor_sets": 8}
-        result["roofline_mask"] = roof_hbm(("mask_attn_kernel<128, 2, 32, 1>",), by2 / (ms * 1e-3) / 1e9)
+        result["roofline_mask"] = roof_hbm(("mask_attn_kernel<128, 2, 32, false>",), by2 / (ms * 1e-3) / 1e9)
         b2 = time_backward(c2, sets2[:3])
         result["mask_bwd"] = b2
         result["roofline_mask_bwd"] = roof_hbm(("bwd_dq_kernel<128, 2>", "bwd_dkv_kernel<128, 2>", "bwd_reduce_kernel<128>"),

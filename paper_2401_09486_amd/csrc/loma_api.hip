@@ -363,7 +363,7 @@ long long loma_mask_schedule_size(int B, int H, int head_dim, int t, int c, int 
     Geometry g;
     g.t = t; g.c = c; g.n = n_chunks; g.R = t * c; g.s = t * (2 * c + 1); g.S = (int)S;
     if (!loma::mask_attn_mfma_fits(g)) return 0;
-    return loma::MaskSchedule::make(B * H, t, c, n_chunks, loma::mask_block_rows(t * c)).size();
+    return loma::MaskSchedule::make(B * H, t, c, n_chunks, loma::mask_block_rows(t * c, t)).size();
 }
 
 int loma_mask_schedule_item(int B, int H, int head_dim, int t, int c, int n_chunks, int dtype,
@@ -371,7 +371,7 @@ int loma_mask_schedule_item(int B, int H, int head_dim, int t, int c, int n_chun
     if (int rc = check_common(B, H, head_dim, t, c, 1.f, dtype)) return rc;
     if (n_chunks < 1 || item == nullptr) return LOMA_ERR_INVALID_ARG;
     if (!loma::use_mfma_path(dtype, head_dim)) return LOMA_ERR_UNSUPPORTED;
-    const loma::MaskSchedule sch = loma::MaskSchedule::make(B * H, t, c, n_chunks, loma::mask_block_rows(t * c));
+    const loma::MaskSchedule sch = loma::MaskSchedule::make(B * H, t, c, n_chunks, loma::mask_block_rows(t * c, t));
     if (block < 0 || block >= sch.size()) return LOMA_ERR_INVALID_ARG;
     const loma::MaskJob j = sch.decode(block);
     item[0] = j.bh; item[1] = j.y; item[2] = j.zone; item[3] = j.o0; item[4] = j.rows; item[5] = j.nkeys;

@@ -110,7 +110,7 @@ bool mask_attn_bwd_mfma_fits(const Geometry& g) {
 // later chunk; when that one list is longer than what an average workgroup slot of the chip carries in the
 // whole pass, the pass takes as long as that block, and the lists are shared out over two workgroups.
 int mask_attn_bwd_stream_split(int nbh, const Geometry& g) {
-    const int bm = mask_block_rows(g.R), nw = bm / 32;
+    const int bm = mask_bwd_block_rows(g.R), nw = bm / 32;
     const long long slots = 256LL * (nw == 4 ? 1 : (nw == 2 ? 2 : 4));   // one wave per SIMD
     const long long nmk = (long long)g.n * g.t, nMK = (nmk + bm - 1) / bm;
     long long mem_tiles = 0, longest = 0;
@@ -144,7 +144,7 @@ int launch_mask_attn_bwd_mfma(const void* q, const void* k, const void* v, const
     P.T.out = (const bf16_t*)out; P.T.lse = lse;
     P.T.dq = (bf16_t*)dq; P.T.dk = (bf16_t*)dk; P.T.dv = (bf16_t*)dv;
     P.nbh = nbh; P.n = g.n; P.t = g.t; P.R = g.R; P.s = g.s;
-    P.bm = mask_block_rows(g.R);
+    P.bm = mask_bwd_block_rows(g.R);
     P.scale = scale; P.sc = scale * LOG2E;
     const long long rows = (long long)nbh * g.S;
     P.T.delta = workspace; P.T.nl = workspace + rows;   // two floats per row, then the partial sums

@@ -51,10 +51,10 @@ struct FlashJob {
     const bf16_t *k_self, *v_self;  // rows aligned with q (repetition zone) or nullptr
 };
 
-template <int D, int NW, int BN, int QT>
+template <int D, int NW, int BN>
 struct Cfg {
     static constexpr int NT = 64 * NW;
-    static constexpr int WROWS = 32 * QT;   // query rows per wave: QT tiles of 32
+    static constexpr int WROWS = 32;        // query rows per wave
     static constexpr int BM = WROWS * NW;
     static constexpr int CPR = D / 8;        // 16-byte pieces per row
     // Tiles are dense [BN][D] in LDS (the direct loads write 1 KB runs); instead of padding, the
@@ -70,7 +70,10 @@ struct Cfg {
     // repetition rows leave through an fp32 staging area (one per wave: 32 rows, padded, plus 32 row factors)
     static constexpr int FSTR = D + 4;
     static constexpr int REP_STAGE_BYTES = NW * (32 * FSTR + 32) * 4;
-    static constexpr int SMEM_BYTES = RING_BYTES > REP_STAGE_BYTES ? RING_BYTES : REP_STAGE_BYTES;
+    // what the repetition rows' job needs: one tile and every wave's queries, later the staging area
+    static constexpr int REP_LOAD_BYTES = (KBUF + VBUF + NW * 32 * D) * 2;
+    static constexpr int REP_BYTES = REP_LOAD_BYTES > REP_STAGE_BYTES ? REP_LOAD_BYTES : REP_STAGE_BYTES;
+    static constexpr int SMEM_BYTES = RING_BYTES > REP_BYTES ? RING_BYTES : REP_BYTES;
     static constexpr int OSTR = D + 8;                   // row stride of the output staging area
     static constexpr int RPI = 64 / CPR;                 // tile rows one wave-wide direct load covers
     static constexpr int IPW = BN / RPI / NW;            // direct loads per wave, per tensor, per tile
@@ -104,10 +107,10 @@ __device__ __forceinline__ void key_row(const FlashJob J, int j, const bf16_t*& 
 // belongs at its LDS position under the row's XOR permutation.  Keys past the end of the list
 // are clamped to the last key: their scores are masked and their probabilities are exactly 0,
 // so any finite row will do and no lane ever branches.
-template <int D, int NW, int BN, int QT>
+template <int D, int NW, int BN>
 __device__ __forceinline__ void load_tile_async(const FlashJob& J, int k0, int nkeys, int w, int lane,
                                                 bf16_t* Kb, bf16_t* Vb) {
-    using C = Cfg<D, NW, BN, QT>;
+    using C = Cfg<D, NW, BN>;
     const int p = lane % C::CPR;
 #pragma unroll
     for (int i = 0; i < C::IPW; ++i) {
@@ -125,9 +128,9 @@ __device__ __forceinline__ void load_tile_async(const FlashJob& J, int k0, int n
 // Where wave w keeps its 32 query rows in LDS: the last stage of the tile ring (free until the
 // first tile request inside the loop), laid out like a key tile, so the B-operand reads use the
 // same per-lane offsets as the K reads.
-template <int D, int NW, int BN, int QT, int NS = 2>
+template <int D, int NW, int BN, int NS = 2>
 __device__ __forceinline__ bf16_t* query_stage(bf16_t* smem, int w) {
-    using C = Cfg<D, NW, BN, QT>;
+    using C = Cfg<D, NW, BN>;
     static_assert(C::LOADABLE, "tile configuration");
     bf16_t* Ks = smem;
     bf16_t* Vt = smem + NS * C::KBUF;
@@ -135,9 +138,9 @@ __device__ __forceinline__ bf16_t* query_stage(bf16_t* smem, int w) {
 }
 // Direct HBM -> LDS copy of the wave's 32 query rows: whole 1 KB runs per instruction instead of
 // 32 scattered 32-byte pieces (rows past the block replay its last row, never stored).
-template <int D, int NW, int BN, int QT>
+template <int D, int NW, int BN>
 __device__ __forceinline__ void load_queries_async(const FlashJob& J, int row0, int lane, bf16_t* Qs) {
-    using C = Cfg<D, NW, BN, QT>;
+    using C = Cfg<D, NW, BN>;
     const int p = lane % C::CPR;
 #pragma unroll
     for (int i = 0; i < 32 / C::RPI; ++i) {
@@ -152,13 +155,13 @@ __device__ __forceinline__ void load_queries_async(const FlashJob& J, int row0, 
 // load and tile; every lane adds a loop-invariant offset.  No vector instruction is spent on
 // addresses.  (Possible when the range boundaries and the slab length are multiples of RPI --
 // the RPI rows of one load are then consecutive rows of one range -- and a tile covers whole slabs.)
-template <int D, int NW, int BN, int QT>
-__device__ __forceinline__ void load_tile_async_stream(const bf16_t* (&kptr)[Cfg<D, NW, BN, QT>::IPW],
-                                                       const bf16_t* (&vptr)[Cfg<D, NW, BN, QT>::IPW],
+template <int D, int NW, int BN>
+__device__ __forceinline__ void load_tile_async_stream(const bf16_t* (&kptr)[Cfg<D, NW, BN>::IPW],
+                                                       const bf16_t* (&vptr)[Cfg<D, NW, BN>::IPW],
                                                        long tile_stride, int w,
-                                                       const unsigned (&goffk)[Cfg<D, NW, BN, QT>::IPW],
+                                                       const unsigned (&goffk)[Cfg<D, NW, BN>::IPW],
                                                        unsigned goffv, bf16_t* Kb, bf16_t* Vb) {
-    using C = Cfg<D, NW, BN, QT>;
+    using C = Cfg<D, NW, BN>;
 #pragma unroll
     for (int i = 0; i < C::IPW; ++i) {
         const int rbase = (w * C::IPW + i) * C::RPI;   // wave-uniform
@@ -178,24 +181,22 @@ __device__ __forceinline__ void load_tile_async_stream(const bf16_t* (&kptr)[Cfg
 // One key tile for one wave: scores, online softmax, PV.  FULL = every key of the tile is visible
 // to every row of the wave (no mask, no sub-tile skipping): the hot path, written as straight-line
 // code with the LDS operand reads issued well ahead of the MFMAs that consume them.
-template <int D, int NW, int BN, int QT, bool FULL>
-__device__ __forceinline__ void score_phase(const bf16_t* Kb, const int (&koff)[Cfg<D, NW, BN, QT>::KSTEPS],
-                                            const bf16x8 (&qreg)[QT][Cfg<D, NW, BN, QT>::KSTEPS],
-                                            f32x16 (&S)[QT][Cfg<D, NW, BN, QT>::NSUB],
-                                            int k0, int nsub, const int (&my_lim)[QT], int lane) {
-    using C = Cfg<D, NW, BN, QT>;
+template <int D, int NW, int BN, bool FULL>
+__device__ __forceinline__ void score_phase(const bf16_t* Kb, const int (&koff)[Cfg<D, NW, BN>::KSTEPS],
+                                            const bf16x8 (&qreg)[Cfg<D, NW, BN>::KSTEPS],
+                                            f32x16 (&S)[Cfg<D, NW, BN>::NSUB],
+                                            int k0, int nsub, const int &my_lim, int lane) {
+    using C = Cfg<D, NW, BN>;
     const int g = lane >> 5;
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if constexpr (!FULL) {
 #pragma unroll
-        for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
             for (int sub = 0; sub < C::NSUB; ++sub)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) S[qt][sub][i] = 0.f;
+                for (int i = 0; i < 16; ++i) S[sub][i] = 0.f;
     }
 
-    // ---- S^T = K Q^T: one K operand read from LDS feeds the MFMAs of all QT query tiles ----------
+    // ---- S^T = K Q^T ----------------------------------------------------------------------------
     if constexpr (FULL) {
         // K operands are read AHEAD k-steps before the MFMAs that use them; the scheduling
         // barriers keep the compiler from sinking the reads back next to their uses.
@@ -211,14 +212,11 @@ __device__ __forceinline__ void score_phase(const bf16_t* Kb, const int (&koff)[
         for (int ks = 0; ks < C::KSTEPS; ++ks) {
 #pragma unroll
             for (int sub = 0; sub < C::NSUB; ++sub)
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt) {
-                    if (ks == 0)
-                        S[qt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][0], qreg[qt][0], zero16, 0, 0, 0);
-                    else
-                        S[qt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][ks % AHEAD], qreg[qt][ks],
-                                                                             S[qt][sub], 0, 0, 0);
-                }
+                if (ks == 0)
+                    S[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][0], qreg[0], zero16, 0, 0, 0);
+                else
+                    S[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][ks % AHEAD], qreg[ks],
+                                                                         S[sub], 0, 0, 0);
             if (ks + AHEAD < C::KSTEPS) {
 #pragma unroll
                 for (int sub = 0; sub < C::NSUB; ++sub)
@@ -234,98 +232,88 @@ __device__ __forceinline__ void score_phase(const bf16_t* Kb, const int (&koff)[
 #pragma unroll
                 for (int ks = 0; ks < C::KSTEPS; ++ks) {
                     const bf16x8 a = *reinterpret_cast<const bf16x8*>(Kb + koff[ks] + 32 * sub * D);
-#pragma unroll
-                    for (int qt = 0; qt < QT; ++qt)
-                        S[qt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qt][ks], S[qt][sub], 0, 0, 0);
+                        S[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], S[sub], 0, 0, 0);
                 }
             }
         // accumulator i of lane (l32, g) is key 8*(i/4) + 4*g + i%4 of the sub-tile
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
             for (int sub = 0; sub < C::NSUB; ++sub)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int j = k0 + 32 * sub + 8 * (i >> 2) + 4 * g + (i & 3);
-                    if (j > my_lim[qt]) S[qt][sub][i] = -INFINITY;
+                    if (j > my_lim) S[sub][i] = -INFINITY;
                 }
     }
 }
 
 // Largest score of every query over one fully visible tile, joined with the running reference m.
-template <int D, int NW, int BN, int QT>
-__device__ __forceinline__ void tile_row_max(const f32x16 (&S)[QT][Cfg<D, NW, BN, QT>::NSUB], const float (&m)[QT],
-                                             float (&mx)[QT]) {
-    using C = Cfg<D, NW, BN, QT>;
+template <int D, int NW, int BN>
+__device__ __forceinline__ void tile_row_max(const f32x16 (&S)[Cfg<D, NW, BN>::NSUB], const float &m,
+                                             float &mx) {
+    using C = Cfg<D, NW, BN>;
+    float x = m;
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        float x = m[qt];
+    for (int sub = 0; sub < C::NSUB; ++sub)
 #pragma unroll
-        for (int sub = 0; sub < C::NSUB; ++sub)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) x = fmaxf(x, S[qt][sub][i]);
-        mx[qt] = pair_max(x);
-    }
+        for (int i = 0; i < 16; ++i) x = fmaxf(x, S[sub][i]);
+    mx = pair_max(x);
 }
 
 // RESCALE = false: the caller has checked that no query's maximum exceeds its reference m by more
 // than LAZY_TAU (in exp2 units), so m, and with it the scale of O and of the running sum, stay as
 // they are: probabilities are at most 2^LAZY_TAU, harmless in fp32 and in bf16, and the 64
 // multiplies of O are saved.  The final normalisation divides by a sum taken in the same scale.
-template <int D, int NW, int BN, int QT, bool FULL, bool RESCALE = true, bool HAVE_MAX = false>
-__device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&voff)[Cfg<D, NW, BN, QT>::DT],
-                                                 f32x16 (&S)[QT][Cfg<D, NW, BN, QT>::NSUB],
-                                                 f32x16 (&O)[QT][Cfg<D, NW, BN, QT>::DT], float (&m)[QT],
-                                                 float (&lsum)[QT], float sc, int nsub, int lane,
+template <int D, int NW, int BN, bool FULL, bool RESCALE = true, bool HAVE_MAX = false>
+__device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&voff)[Cfg<D, NW, BN>::DT],
+                                                 f32x16 (&S)[Cfg<D, NW, BN>::NSUB],
+                                                 f32x16 (&O)[Cfg<D, NW, BN>::DT], float &m,
+                                                 float &lsum, float sc, int nsub, int lane,
                                                  const float* mx_in = nullptr) {
-    using C = Cfg<D, NW, BN, QT>;
+    using C = Cfg<D, NW, BN>;
     // ---- online softmax (per query: lanes l and l^32) ---------------------------------------------
+    float mx = m;
+    if constexpr (RESCALE) {
+        if constexpr (HAVE_MAX) {
+            mx = *mx_in;
+        } else {
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        float mx = m[qt];
-        if constexpr (RESCALE) {
-            if constexpr (HAVE_MAX) {
-                mx = mx_in[qt];
-            } else {
+            for (int sub = 0; sub < C::NSUB; ++sub)
+                if (FULL || sub < nsub) {
 #pragma unroll
-                for (int sub = 0; sub < C::NSUB; ++sub)
-                    if (FULL || sub < nsub) {
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[qt][sub][i]);
-                    }
-                mx = pair_max(mx);
-            }
-            // rescale by exp2((m_old - m_new) * sc): exactly 1 for the rows whose maximum did not move.
-            // (No branch around it here: a branch makes the compiler keep two copies of O.)
-            // A row that has seen no key yet and sees none in a cut tile (possible when the keys of a tile are
-            // split over wave groups) keeps m = -inf; the arithmetic then runs against 0 instead: factor 0 on
-            // an O that is 0, probabilities exp2(-inf) = 0.
-            const float mref = (!FULL && mx == -INFINITY) ? 0.f : mx;
-            const float alpha = __builtin_amdgcn_exp2f((m[qt] - mref) * sc);
-            lsum[qt] *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) O[qt][dt][i] *= alpha;
-            m[qt] = mx;
-            mx = mref;
-        }
-        const float mc = mx * sc;
-        float ps = 0.f;
-#pragma unroll
-        for (int sub = 0; sub < C::NSUB; ++sub)
-            if (FULL || sub < nsub) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(S[qt][sub][i] * sc - mc);
-                    ps += p;
-                    S[qt][sub][i] = p;
+                    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[sub][i]);
                 }
-            }
-        lsum[qt] += ps;
+            mx = pair_max(mx);
+        }
+        // rescale by exp2((m_old - m_new) * sc): exactly 1 for the rows whose maximum did not move.
+        // (No branch around it here: a branch makes the compiler keep two copies of O.)
+        // A row that has seen no key yet and sees none in a cut tile (possible when the keys of a tile are
+        // split over wave groups) keeps m = -inf; the arithmetic then runs against 0 instead: factor 0 on
+        // an O that is 0, probabilities exp2(-inf) = 0.
+        const float mref = (!FULL && mx == -INFINITY) ? 0.f : mx;
+        const float alpha = __builtin_amdgcn_exp2f((m - mref) * sc);
+        lsum *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[dt][i] *= alpha;
+        m = mx;
+        mx = mref;
     }
+    const float mc = mx * sc;
+    float ps = 0.f;
+#pragma unroll
+    for (int sub = 0; sub < C::NSUB; ++sub)
+        if (FULL || sub < nsub) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float p = __builtin_amdgcn_exp2f(S[sub][i] * sc - mc);
+                ps += p;
+                S[sub][i] = p;
+            }
+        }
+    lsum += ps;
 
-    // ---- O^T += V^T P^T: one V^T operand read feeds the MFMAs of all QT query tiles --------------------
+    // ---- O^T += V^T P^T ---------------------------------------------------------------------------------
     // V^T operand: lane (d = 32*dt + l32, half g) needs keys 16*step + 8*a + 4*g + 0..3, a = 0,1
     auto read_v = [&](int step, int dt) -> bf16x8 {
         const bf16_t* vp = Vb + voff[dt] + 16 * step * D;
@@ -333,13 +321,13 @@ __device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&v
         const s16x4 hi = lds_read_tr(vp + 8 * D);
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    auto pack_p = [&](int qt, int step) -> bf16x8 {
+    auto pack_p = [&](int step) -> bf16x8 {
         const int sub = step >> 1, jj = step & 1;
         uint4 pw;
-        pw.x = pack_bf16(S[qt][sub][8 * jj + 0], S[qt][sub][8 * jj + 1]);
-        pw.y = pack_bf16(S[qt][sub][8 * jj + 2], S[qt][sub][8 * jj + 3]);
-        pw.z = pack_bf16(S[qt][sub][8 * jj + 4], S[qt][sub][8 * jj + 5]);
-        pw.w = pack_bf16(S[qt][sub][8 * jj + 6], S[qt][sub][8 * jj + 7]);
+        pw.x = pack_bf16(S[sub][8 * jj + 0], S[sub][8 * jj + 1]);
+        pw.y = pack_bf16(S[sub][8 * jj + 2], S[sub][8 * jj + 3]);
+        pw.z = pack_bf16(S[sub][8 * jj + 4], S[sub][8 * jj + 5]);
+        pw.w = pack_bf16(S[sub][8 * jj + 6], S[sub][8 * jj + 7]);
         return __builtin_bit_cast(bf16x8, pw);
     };
     constexpr int NSTEP = 2 * C::NSUB;
@@ -354,29 +342,23 @@ __device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&v
 #pragma unroll
                 for (int dt = 0; dt < C::DT; ++dt) va[(step + 1) & 1][dt] = read_v(step + 1, dt);
             }
-            bf16x8 pb[QT];
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt) pb[qt] = pack_p(qt, step);
+            bf16x8 pb;
+            pb = pack_p(step);
 #pragma unroll
             for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-                    O[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[step & 1][dt], pb[qt], O[qt][dt], 0, 0, 0);
+                    O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[step & 1][dt], pb, O[dt], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     } else {
 #pragma unroll
         for (int step = 0; step < NSTEP; ++step)
             if ((step >> 1) < nsub) {
-                bf16x8 pb[QT];
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt) pb[qt] = pack_p(qt, step);
+                bf16x8 pb;
+                pb = pack_p(step);
 #pragma unroll
                 for (int dt = 0; dt < C::DT; ++dt) {
                     const bf16x8 a = read_v(step, dt);
-#pragma unroll
-                    for (int qt = 0; qt < QT; ++qt)
-                        O[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt], O[qt][dt], 0, 0, 0);
+                        O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, O[dt], 0, 0, 0);
                 }
             }
     }
@@ -384,11 +366,11 @@ __device__ __forceinline__ void softmax_pv_phase(const bf16_t* Vb, const int (&v
 
 // The query row's own K and V rows, in the register layouts of the Q operand (K) and of the O
 // accumulators (V): lane (row l32, half g) holds head-dim 16*ks + 8*g.. of K and 32*dt + 8*i4 + 4*g.. of V.
-template <int D, int NW, int BN, int QT>
+template <int D, int NW, int BN>
 __device__ __forceinline__ void load_self_rows(const FlashJob& J, int r, int g,
-                                               bf16x8 (&kself)[Cfg<D, NW, BN, QT>::KSTEPS],
-                                               uint2 (&vself)[Cfg<D, NW, BN, QT>::DT][4]) {
-    using C = Cfg<D, NW, BN, QT>;
+                                               bf16x8 (&kself)[Cfg<D, NW, BN>::KSTEPS],
+                                               uint2 (&vself)[Cfg<D, NW, BN>::DT][4]) {
+    using C = Cfg<D, NW, BN>;
     const int rc = min(r, J.q_rows - 1);   // lanes past the block replay its last row (never stored)
     const bf16_t* kp = J.k_self + (long)rc * D + 8 * g;
     const bf16_t* vp = J.v_self + (long)rc * D + 4 * g;
@@ -403,12 +385,12 @@ __device__ __forceinline__ void load_self_rows(const FlashJob& J, int r, int g,
 
 // One more key for every query, its own (identity block of Eq. 1, second term of Eq. 9): a dot
 // product and an axpy per row on the vector ALU -- a diagonal is no MFMA tile.
-template <int D, int NW, int BN, int QT>
-__device__ __forceinline__ void self_term(const bf16x8 (&qreg)[Cfg<D, NW, BN, QT>::KSTEPS],
-                                          const bf16x8 (&kself)[Cfg<D, NW, BN, QT>::KSTEPS],
-                                          const uint2 (&vself)[Cfg<D, NW, BN, QT>::DT][4],
-                                          f32x16 (&O)[Cfg<D, NW, BN, QT>::DT], float& m, float& lsum, float sc, int g) {
-    using C = Cfg<D, NW, BN, QT>;
+template <int D, int NW, int BN>
+__device__ __forceinline__ void self_term(const bf16x8 (&qreg)[Cfg<D, NW, BN>::KSTEPS],
+                                          const bf16x8 (&kself)[Cfg<D, NW, BN>::KSTEPS],
+                                          const uint2 (&vself)[Cfg<D, NW, BN>::DT][4],
+                                          f32x16 (&O)[Cfg<D, NW, BN>::DT], float& m, float& lsum, float sc, int g) {
+    using C = Cfg<D, NW, BN>;
     float part = 0.f;
 #pragma unroll
     for (int ks = 0; ks < C::KSTEPS; ++ks) {
@@ -440,43 +422,39 @@ __device__ __forceinline__ void self_term(const bf16x8 (&qreg)[Cfg<D, NW, BN, QT
 
 // Normalise, transpose through LDS (the tile buffers are free by now), store rows as 16-byte
 // pieces; one query tile at a time through the wave's own 32-row staging area.
-template <int D, int NW, int BN, int QT>
-__device__ __forceinline__ void store_rows(const FlashJob& J, f32x16 (&O)[QT][Cfg<D, NW, BN, QT>::DT],
-                                           const float (&m)[QT], const float (&lsum)[QT], float sc, bf16_t* smem,
+template <int D, int NW, int BN>
+__device__ __forceinline__ void store_rows(const FlashJob& J, f32x16 (&O)[Cfg<D, NW, BN>::DT],
+                                           const float &m, const float &lsum, float sc, bf16_t* smem,
                                            int w, int lane, int row0, bool has_rows) {
-    using C = Cfg<D, NW, BN, QT>;
+    using C = Cfg<D, NW, BN>;
     const int g = lane >> 5, l32 = lane & 31;
     bf16_t* Os = smem + w * 32 * C::OSTR;
+    const int rbase = row0;
+    const float ltot = pair_sum(lsum);
+    const float inv = 1.f / ltot;
+    if (has_rows) {
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        const int rbase = row0 + 32 * qt;
-        const float ltot = pair_sum(lsum[qt]);
-        const float inv = 1.f / ltot;
-        if (has_rows) {
+        for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-            for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    uint2 x;
-                    x.x = pack_bf16(O[qt][dt][4 * i4 + 0] * inv, O[qt][dt][4 * i4 + 1] * inv);
-                    x.y = pack_bf16(O[qt][dt][4 * i4 + 2] * inv, O[qt][dt][4 * i4 + 3] * inv);
-                    *reinterpret_cast<uint2*>(Os + l32 * C::OSTR + 32 * dt + 8 * i4 + 4 * g) = x;
-                }
-            if (J.lse != nullptr && g == 0 && rbase + l32 < J.q_rows)
-                J.lse[rbase + l32] = (m[qt] * sc + __builtin_amdgcn_logf(ltot)) * LN2;
-        }
-        __syncthreads();
-        if (has_rows) {
-#pragma unroll
-            for (int it = 0; it < 32 * C::CPR / 64; ++it) {
-                const int idx = it * 64 + lane;
-                const int r = idx / C::CPR, ch = idx % C::CPR;
-                if (rbase + r < J.q_rows)
-                    *reinterpret_cast<uint4*>(J.out + (long)(rbase + r) * D + ch * 8) =
-                        *reinterpret_cast<const uint4*>(Os + r * C::OSTR + ch * 8);
+            for (int i4 = 0; i4 < 4; ++i4) {
+                uint2 x;
+                x.x = pack_bf16(O[dt][4 * i4 + 0] * inv, O[dt][4 * i4 + 1] * inv);
+                x.y = pack_bf16(O[dt][4 * i4 + 2] * inv, O[dt][4 * i4 + 3] * inv);
+                *reinterpret_cast<uint2*>(Os + l32 * C::OSTR + 32 * dt + 8 * i4 + 4 * g) = x;
             }
+        if (J.lse != nullptr && g == 0 && rbase + l32 < J.q_rows)
+            J.lse[rbase + l32] = (m * sc + __builtin_amdgcn_logf(ltot)) * LN2;
+    }
+    __syncthreads();
+    if (has_rows) {
+#pragma unroll
+        for (int it = 0; it < 32 * C::CPR / 64; ++it) {
+            const int idx = it * 64 + lane;
+            const int r = idx / C::CPR, ch = idx % C::CPR;
+            if (rbase + r < J.q_rows)
+                *reinterpret_cast<uint4*>(J.out + (long)(rbase + r) * D + ch * 8) =
+                    *reinterpret_cast<const uint4*>(Os + r * C::OSTR + ch * 8);
         }
-        if (qt + 1 < QT) __syncthreads();
     }
 }
 
@@ -485,11 +463,11 @@ __device__ __forceinline__ void store_rows(const FlashJob& J, f32x16 (&O)[QT][Cf
 // w % (NW / KS) and, of every tile of BN keys, the BN / KS keys of key group w / (NW / KS).  All waves
 // share the loads; the groups' partial results (same register layout in every wave) meet in LDS at
 // the end.
-template <int D, int NW, int BN, int QT, int KS = 1, int NS = 2>
+template <int D, int NW, int BN, int KS = 1, int NS = 2>
 __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* smem) {
-    using C = Cfg<D, NW, BN, QT>;            // tiles as they are loaded (the ring has NS stages)
+    using C = Cfg<D, NW, BN>;            // tiles as they are loaded (the ring has NS stages)
     constexpr int BNC = BN / KS;             // keys of a tile one wave works on
-    using CC = Cfg<D, NW, BNC, QT>;
+    using CC = Cfg<D, NW, BNC>;
     constexpr int RG = NW / KS;              // row groups
     static_assert(NW % KS == 0 && BN % (32 * KS) == 0, "key split");
     const int tid = threadIdx.x, lane = tid & 63;
@@ -507,28 +485,22 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     const bool has_rows = row0 < J.q_rows;
     const int row_hi = min(row0 + C::WROWS, J.q_rows);    // exclusive
     const int kend_w = has_rows ? min(nkeys, J.causal_base + row_hi) : 0;
-    int my_lim[QT];                                       // last key each of this lane's queries sees
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt)                       // padded lanes replay the last row
-        my_lim[qt] = min(J.causal_base + min(row0 + 32 * qt + l32, J.q_rows - 1), nkeys - 1);
+    int my_lim;                                       // last key each of this lane's queries sees
+        my_lim = min(J.causal_base + min(row0 + l32, J.q_rows - 1), nkeys - 1);
 
     // Q^T as the B operand: lane (query l32, half g) holds head-dim 16*ks + 8*g .. +7; it arrives through LDS
-    static_assert(QT == 1, "one 32-row query tile per wave");
-    bf16x8 qreg[QT][C::KSTEPS];
-    bf16_t* Qs = query_stage<D, NW, BN, QT, NS>(smem, w);
-    load_queries_async<D, NW, BN, QT>(J, row0, lane, Qs);
+    bf16x8 qreg[C::KSTEPS];
+    bf16_t* Qs = query_stage<D, NW, BN, NS>(smem, w);
+    load_queries_async<D, NW, BN>(J, row0, lane, Qs);
 
-    f32x16 O[QT][C::DT];
-    float m[QT], lsum[QT];
+    f32x16 O[C::DT];
+    float m, lsum;
+    m = -INFINITY;
+    lsum = 0.f;
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        m[qt] = -INFINITY;
-        lsum[qt] = 0.f;
+    for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-        for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) O[qt][dt][i] = 0.f;
-    }
+        for (int i = 0; i < 16; ++i) O[dt][i] = 0.f;
 
     // per-lane LDS offsets (elements) of the operand reads, under the tiles' XOR permutations
     int koff[C::KSTEPS], voff[C::DT];
@@ -583,9 +555,9 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
         bf16_t* Kd = Ks + (t % NS) * C::KBUF;
         bf16_t* Vd = Vt + (t % NS) * C::VBUF;
         if (t >= AHEAD && t < nstream)
-            load_tile_async_stream<D, NW, BN, QT>(kptr, vptr, tile_stride, w, goffk, goffv, Kd, Vd);
+            load_tile_async_stream<D, NW, BN>(kptr, vptr, tile_stride, w, goffk, goffv, Kd, Vd);
         else
-            load_tile_async<D, NW, BN, QT>(J, t * BN, nkeys, w, lane, Kd, Vd);
+            load_tile_async<D, NW, BN>(J, t * BN, nkeys, w, lane, Kd, Vd);
     };
 #pragma unroll
     for (int t = 0; t < AHEAD; ++t)
@@ -593,7 +565,7 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     wait_next_tile<LPT, AHEAD - 1>(min(AHEAD, ntiles) - 1);   // tile 0 and the queries are in
     __syncthreads();
 #pragma unroll
-    for (int ks = 0; ks < C::KSTEPS; ++ks) qreg[0][ks] = *reinterpret_cast<const bf16x8*>(Qs + koff[ks]);
+    for (int ks = 0; ks < C::KSTEPS; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(Qs + koff[ks]);
     __syncthreads();   // ring stage 1 belongs to the tiles from here on
 
     // The fast loop keeps the softmax reference m (and so the scale of O) while no query's maximum
@@ -602,26 +574,26 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     {
         int kt = 0;
         while (kt < nfull) {
-            f32x16 S[QT][CC::NSUB];
-            float mx[QT];
+            f32x16 S[CC::NSUB];
+            float mx;
             bool moved = false;
             for (; kt < nfull; ++kt) {
                 const int st = kt % NS;
                 if (kt + AHEAD < ntiles) request_tile(kt + AHEAD);
                 if (has_rows) {
-                    score_phase<D, NW, BNC, QT, true>(Ks + st * C::KBUF + wk0 * D, koff, qreg, S, kt * BN + wk0, CC::NSUB,
+                    score_phase<D, NW, BNC, true>(Ks + st * C::KBUF + wk0 * D, koff, qreg, S, kt * BN + wk0, CC::NSUB,
                                                       my_lim, lane);
-                    tile_row_max<D, NW, BNC, QT>(S, m, mx);
-                    if (__builtin_amdgcn_ballot_w64((mx[0] - m[0]) * sc > LAZY_TAU) != 0) { moved = true; break; }
-                    softmax_pv_phase<D, NW, BNC, QT, true, false>(Vt + st * C::VBUF + wk0 * D, voff, S, O, m, lsum, sc,
+                    tile_row_max<D, NW, BNC>(S, m, mx);
+                    if (__builtin_amdgcn_ballot_w64((mx - m) * sc > LAZY_TAU) != 0) { moved = true; break; }
+                    softmax_pv_phase<D, NW, BNC, true, false>(Vt + st * C::VBUF + wk0 * D, voff, S, O, m, lsum, sc,
                                                                   CC::NSUB, lane);
                 }
                 wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
                 __syncthreads();
             }
             if (moved) {
-                softmax_pv_phase<D, NW, BNC, QT, true, true, true>(Vt + (kt % NS) * C::VBUF + wk0 * D, voff, S, O, m, lsum,
-                                                                    sc, CC::NSUB, lane, mx);
+                softmax_pv_phase<D, NW, BNC, true, true, true>(Vt + (kt % NS) * C::VBUF + wk0 * D, voff, S, O, m, lsum,
+                                                                    sc, CC::NSUB, lane, &mx);
                 wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
                 __syncthreads();
                 ++kt;
@@ -636,9 +608,9 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
         if (kt + AHEAD < ntiles) request_tile(kt + AHEAD);
         if (k0 < kend_w) {
             const int nsub = min(CC::NSUB, (kend_w - k0 + 31) >> 5);
-            f32x16 S[QT][CC::NSUB];
-            score_phase<D, NW, BNC, QT, false>(Ks + st * C::KBUF + wk0 * D, koff, qreg, S, k0, nsub, my_lim, lane);
-            softmax_pv_phase<D, NW, BNC, QT, false>(Vt + st * C::VBUF + wk0 * D, voff, S, O, m, lsum, sc, nsub, lane);
+            f32x16 S[CC::NSUB];
+            score_phase<D, NW, BNC, false>(Ks + st * C::KBUF + wk0 * D, koff, qreg, S, k0, nsub, my_lim, lane);
+            softmax_pv_phase<D, NW, BNC, false>(Vt + st * C::VBUF + wk0 * D, voff, S, O, m, lsum, sc, nsub, lane);
         }
         wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
         __syncthreads();
@@ -654,9 +626,9 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
 #pragma unroll
             for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) dst[(16 * dt + i) * 64] = O[0][dt][i];
-            dst[16 * C::DT * 64] = m[0];
-            dst[(16 * C::DT + 1) * 64] = lsum[0];
+                for (int i = 0; i < 16; ++i) dst[(16 * dt + i) * 64] = O[dt][i];
+            dst[16 * C::DT * 64] = m;
+            dst[(16 * C::DT + 1) * 64] = lsum;
         }
         __syncthreads();
         if (kg == 0 && has_rows) {
@@ -664,15 +636,15 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
             for (int k = 1; k < KS; ++k) {
                 const float* src = xs + (size_t)(w + (k - 1) * RG) * PER_WAVE + lane;
                 const float mb = src[16 * C::DT * 64], lb = src[(16 * C::DT + 1) * 64];
-                const float mx = fmaxf(m[0], mb);
+                const float mx = fmaxf(m, mb);
                 // a group that saw no key has m = -inf, sum 0 and O = 0: its factor is exp2(-inf) = 0
-                const float fa = __builtin_amdgcn_exp2f((m[0] - mx) * sc), fb = __builtin_amdgcn_exp2f((mb - mx) * sc);
-                lsum[0] = lsum[0] * fa + lb * fb;
-                m[0] = mx;
+                const float fa = __builtin_amdgcn_exp2f((m - mx) * sc), fb = __builtin_amdgcn_exp2f((mb - mx) * sc);
+                lsum = lsum * fa + lb * fb;
+                m = mx;
 #pragma unroll
                 for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) O[0][dt][i] = O[0][dt][i] * fa + src[(16 * dt + i) * 64] * fb;
+                    for (int i = 0; i < 16; ++i) O[dt][i] = O[dt][i] * fa + src[(16 * dt + i) * 64] * fb;
             }
         }
         __syncthreads();   // the exchange area becomes the staging area of store_rows
@@ -680,15 +652,314 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
     const bool owns_rows = has_rows && kg == 0;
     // the row's own key (identity block of Eq. 1, second term of Eq. 9), on the vector ALU
     if (J.k_self != nullptr && owns_rows) {
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt) {
-            bf16x8 kself[C::KSTEPS];
-            uint2 vself[C::DT][4];
-            load_self_rows<D, NW, BN, QT>(J, row0 + 32 * qt + l32, g, kself, vself);
-            self_term<D, NW, BN, QT>(qreg[qt], kself, vself, O[qt], m[qt], lsum[qt], sc, g);
+        bf16x8 kself[C::KSTEPS];
+        uint2 vself[C::DT][4];
+        load_self_rows<D, NW, BN>(J, row0 + l32, g, kself, vself);
+        self_term<D, NW, BN>(qreg, kself, vself, O, m, lsum, sc, g);
+    }
+    store_rows<D, NW, BN>(J, O, m, lsum, sc, smem, w, lane, row0, owns_rows);
+}
+
+// ---- the pipelined job ----------------------------------------------------------------------------------
+// For blocks with long key lists (reading rows behind many memory zones) the matrix pipe and the vector ALU have
+// about the same amount of work per tile (32 MFMAs of 32 cycles against ~800 cycles of exponentials, packing and
+// sums), and a wave that does them one after the other leaves each unit idle half of the time.  Here the loop
+// over fully visible tiles is software-pipelined over HALF tiles of 32 keys: while the vector ALU turns the
+// scores of half h into probabilities, the matrix pipe multiplies the scores of half h+1 and the P.V product of
+// half h-1, one MFMA every few vector instructions, in one instruction stream.  Half h-1's V rows must stay
+// while half h+1's K rows are read, so the ring holds two K stages and three V stages of 64 keys (80 KB at
+// head_dim 128: two workgroups per CU); one barrier per tile, between its two halves.
+//
+// The softmax reference m is taken from the first half tile and kept while no probability leaves the range
+// [0, 2^PIPE_TAU]: the test is one compare per half on the lane's partial sum (a probability cannot exceed a sum
+// it is part of); when it trips, the wave leaves the pipelined loop and finishes its tiles one by one, moving
+// the reference as it goes.
+constexpr float PIPE_TAU = 40.f;
+
+// Ring of the pipelined job: NSK stages of K and NSK + 1 stages of V tiles of 64 keys (a V tile is needed one half
+// tile longer than its K tile), loads running NSK - 1 tiles ahead.  Queries are staged in the last QP K stages and
+// the last QP V stages (two waves per stage), which are free until tile NSK - QP is requested.
+template <int D, int NW, int NSK>
+struct PipeCfg {
+    using C = Cfg<D, NW, 64>;
+    static constexpr int NSV = NSK + 1;
+    static constexpr int QP = (NW + 3) / 4;                                     // stage pairs holding the queries
+    static constexpr int RING = NSK * C::KBUF + NSV * C::VBUF;                  // elements
+    static constexpr int SMEM_BYTES = RING * 2;
+    static_assert(RING >= NW * 32 * C::OSTR, "output staging fits in the ring");
+    static_assert(NSK >= 2 && NSK <= 4 && QP < NSK, "ring depth");
+};
+
+// Issue order of one pipeline step, as scheduling groups (sizes must be compile-time constants, hence the recursion
+// over slots; SLOT -1 is the leading group of operand reads).
+template <int D, bool HAVE_S, bool HAVE_PV, bool HAVE_P, int RA, int SLOT>
+__device__ __forceinline__ void pipe_issue_order() {
+    constexpr int KSTEPS = D / 16, NPV = 2 * (D / 32), NSLOT = 2 * KSTEPS, EPS = 16 / NSLOT;
+    constexpr int VALU = 0x2, MFMA = 0x8, DS_READ = 0x100;
+    if constexpr (SLOT < 0) {
+        __builtin_amdgcn_sched_group_barrier(DS_READ, RA * ((HAVE_S ? 1 : 0) + (HAVE_PV ? 2 : 0)), 0);
+    } else {
+        constexpr int j = SLOT >> 1;
+        constexpr bool is_s = (SLOT & 1) == 0;
+        // per score: multiply-add, exponential, sum; per pair of scores: the packing
+        if constexpr (HAVE_P) __builtin_amdgcn_sched_group_barrier(VALU, 3 * EPS + (EPS == 1 ? (SLOT & 1) : EPS / 2), 0);
+        if constexpr (is_s ? HAVE_S : HAVE_PV) {
+            __builtin_amdgcn_sched_group_barrier(MFMA, 1, 0);
+            if constexpr (is_s && j + RA < KSTEPS) __builtin_amdgcn_sched_group_barrier(DS_READ, 1, 0);
+            if constexpr (!is_s && j + RA < NPV) __builtin_amdgcn_sched_group_barrier(DS_READ, 2, 0);
         }
     }
-    store_rows<D, NW, BN, QT>(J, O, m, lsum, sc, smem, w, lane, row0, owns_rows);
+    if constexpr (SLOT + 1 < NSLOT) pipe_issue_order<D, HAVE_S, HAVE_PV, HAVE_P, RA, SLOT + 1>();
+}
+
+// One step of the pipeline.  Matrix pipe: Sn = K rows of half h+1 times Q (HAVE_S), O += V^T of half h-1 times
+// Pp (HAVE_PV), alternating; vector ALU, between them: probabilities Pc of the scores Sc of half h (HAVE_P).
+// Kh / Vh point at the first of the 32 rows of the respective half inside its ring stage.
+template <int D, bool HAVE_S, bool HAVE_PV, bool HAVE_P = true>
+__device__ __forceinline__ float pipe_half(const bf16_t* Kh, const bf16_t* Vh, const int (&koff)[D / 16], const int (&voff)[D / 32],
+                                           const bf16x8 (&qreg)[D / 16], const f32x16& Sc, f32x16& Sn,
+                                           const bf16x8 (&Pp)[2], bf16x8 (&Pc)[2], f32x16 (&O)[D / 32], float sc, float mc) {
+    constexpr int KSTEPS = D / 16, DT = D / 32, NPV = 2 * DT;
+    static_assert(NPV == KSTEPS, "as many P.V products as score products per half tile");
+    constexpr int NSLOT = 2 * KSTEPS, EPS = 16 / NSLOT;      // slots of one MFMA each; scores handled per slot
+    constexpr int RA = 2;                                   // operand reads run this many products of their kind ahead
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    auto read_k = [&](int ks) -> bf16x8 { return *reinterpret_cast<const bf16x8*>(Kh + koff[ks]); };
+    auto read_v = [&](int idx) -> bf16x8 {      // product idx: 16-key step idx / DT, head-dim block idx % DT
+        const bf16_t* vp = Vh + voff[idx % DT] + 16 * (idx / DT) * D;
+        const s16x4 lo = lds_read_tr(vp);
+        const s16x4 hi = lds_read_tr(vp + 8 * D);
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    bf16x8 ka[KSTEPS], va[NPV];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < RA; ++i) {
+        if constexpr (HAVE_S) ka[i] = read_k(i);
+        if constexpr (HAVE_PV) va[i] = read_v(i);
+    }
+    uint32_t pw[8];
+    float pe[2];
+    float ps = 0.f;
+#pragma unroll
+    for (int slot = 0; slot < NSLOT; ++slot) {
+        const int j = slot >> 1;
+        if constexpr (HAVE_P) {
+#pragma unroll
+            for (int e = slot * EPS; e < (slot + 1) * EPS; ++e) {
+                pe[e & 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(Sc[e], sc, -mc));
+                ps += pe[e & 1];
+                if (e & 1) pw[e >> 1] = pack_bf16(pe[0], pe[1]);
+            }
+        }
+        if ((slot & 1) == 0) {
+            if constexpr (HAVE_S) {
+                Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[j], qreg[j], j == 0 ? zero16 : Sn, 0, 0, 0);
+                if (j + RA < KSTEPS) ka[j + RA] = read_k(j + RA);
+            }
+        } else {
+            if constexpr (HAVE_PV) {
+                O[j % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[j], Pp[j / DT], O[j % DT], 0, 0, 0);
+                if (j + RA < NPV) va[j + RA] = read_v(j + RA);
+            }
+        }
+    }
+    // The order the instructions of this step are issued in (the code above only says what is computed: pure
+    // arithmetic is moved around freely before scheduling): the first operand reads, then per slot the slot's share
+    // of the vector work, its MFMA, and the operand read that runs RA products ahead.
+    pipe_issue_order<D, HAVE_S, HAVE_PV, HAVE_P, RA, -1>();
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (!HAVE_P) return 0.f;
+    Pc[0] = __builtin_bit_cast(bf16x8, uint4{pw[0], pw[1], pw[2], pw[3]});
+    Pc[1] = __builtin_bit_cast(bf16x8, uint4{pw[4], pw[5], pw[6], pw[7]});
+    return ps;
+}
+
+template <int D, int NW, int NSK>
+__device__ __forceinline__ void flash_job_pipe(const FlashJob& J, float sc, bf16_t* smem) {
+    constexpr int BN = 64;
+    using C = Cfg<D, NW, BN>;
+    using PC = PipeCfg<D, NW, NSK>;
+    constexpr int NSV = PC::NSV;
+    constexpr int LPT = 2 * C::IPW;        // direct loads per wave and tile
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 5, l32 = lane & 31;
+    bf16_t* Ks = smem;
+    bf16_t* Vt = smem + NSK * C::KBUF;
+    auto kstage = [&](int t) { return Ks + (t % NSK) * C::KBUF; };
+    auto vstage = [&](int t) { return Vt + (t % NSV) * C::VBUF; };
+
+    const int nkeys = J.n0 + J.n1 + J.n2;
+    const int kend_wg = min(nkeys, J.causal_base + J.q_rows);
+    const int ntiles = (kend_wg + BN - 1) / BN;
+    const int row0 = 32 * w;
+    const bool has_rows = row0 < J.q_rows;
+    const int row_hi = min(row0 + 32, J.q_rows);
+    const int kend_w = has_rows ? min(nkeys, J.causal_base + row_hi) : 0;
+    const int my_lim = min(J.causal_base + min(row0 + l32, J.q_rows - 1), nkeys - 1);
+
+    // queries: staged like key tiles in the last QP stages of K and of V, two waves per stage
+    bf16x8 qreg[C::KSTEPS];
+    bf16_t* Qs = (w & 2) ? Vt + (NSV - 1 - (w >> 2)) * C::VBUF + (w & 1) * 32 * D
+                         : Ks + (NSK - 1 - (w >> 2)) * C::KBUF + (w & 1) * 32 * D;
+    load_queries_async<D, NW, BN>(J, row0, lane, Qs);
+
+    f32x16 O[C::DT];
+    float m = -INFINITY, lsum = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[dt][i] = 0.f;
+
+    int koff[C::KSTEPS], voff[C::DT];
+#pragma unroll
+    for (int ks = 0; ks < C::KSTEPS; ++ks) koff[ks] = l32 * D + (((2 * ks + g) ^ (l32 % C::CPR)) * 8);
+    {
+        const int i = lane & 15, q = i >> 2;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+            voff[dt] = (4 * g + q) * D + (4 * (dt ^ (q % (C::CPR / 4))) + 2 * ((lane >> 4) & 1) + ((i & 3) >> 1)) * 8 +
+                       4 * (i & 1);
+    }
+    unsigned goffk[C::IPW], goffv;
+    {
+        const int rl = lane / C::CPR, pc = lane % C::CPR;
+#pragma unroll
+        for (int i = 0; i < C::IPW; ++i)
+            goffk[i] = 2u * (rl * D + ((pc ^ (((w * C::IPW + i) * C::RPI + rl) % C::CPR)) * 8));
+        goffv = 2u * (rl * D + ((pc ^ ((4 * (rl % 4)) % C::CPR)) * 8));
+    }
+
+    // tiles every row of the block sees in full, and tiles every row of THIS WAVE sees in full: the pipelined loop
+    // runs over the latter (a wave-dependent count: the barriers and requests per tile are the same on every path)
+    const int nfull_wg = min(ntiles, (min(J.causal_base, nkeys - 1) + 1) / BN);
+    const int nfull = has_rows ? min(ntiles, (min(J.causal_base + row0, nkeys - 1) + 1) / BN) : 0;
+    int nstream = 0;
+    long tile_stride = 0;
+    if (J.rows_grouped) {
+        if (J.n0 > 0) {
+            if (BN % J.slab == 0) { nstream = min(nfull_wg, J.n0 / BN); tile_stride = (long)(BN / J.slab) * J.slab_stride; }
+        } else {
+            nstream = min(nfull_wg, J.n1 / BN);
+            tile_stride = (long)BN * D;
+        }
+    }
+    constexpr int FIRST_STREAMED = NSK;    // tiles 0 .. NSK-1 are requested in the prologue, with per-lane addresses
+    const bf16_t *kptr[C::IPW], *vptr[C::IPW];
+#pragma unroll
+    for (int i = 0; i < C::IPW; ++i) {
+        const bf16_t *kp, *vp;
+        key_row<D>(J, min((w * C::IPW + i) * C::RPI, nkeys - 1), kp, vp);
+        kptr[i] = uniform_ptr(kp) + FIRST_STREAMED * tile_stride;
+        vptr[i] = uniform_ptr(vp) + FIRST_STREAMED * tile_stride;
+    }
+    int next_req = 0;                      // tiles are requested in order; this is the next one
+    auto request_next = [&]() {
+        const int t = next_req++;
+        if (t >= FIRST_STREAMED && t < nstream)
+            load_tile_async_stream<D, NW, BN>(kptr, vptr, tile_stride, w, goffk, goffv, kstage(t), vstage(t));
+        else
+            load_tile_async<D, NW, BN>(J, t * BN, nkeys, w, lane, kstage(t), vstage(t));
+    };
+    // the wave's loads of every tile up to `upto` have landed (younger requested tiles may still be in flight)
+    auto wait_tile = [&](int upto) { wait_next_tile<LPT, NSK - 1>(max(0, next_req - 1 - upto)); };
+#pragma unroll
+    for (int t = 0; t < NSK - PC::QP; ++t)
+        if (t < ntiles) request_next();    // the tiles whose stages the queries do not occupy
+    wait_direct_loads();
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < C::KSTEPS; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(Qs + koff[ks]);
+    __syncthreads();                       // all stages belong to the tiles from here on
+#pragma unroll
+    for (int t = 0; t < PC::QP; ++t)
+        if (next_req < ntiles) request_next();   // tiles up to NSK-1
+
+    // Pipelined loop over the fully visible tiles.  It runs while every probability stays in range; a half
+    // that leaves the range ends it (wave by wave: the barrier count per tile is the same on both paths), and the
+    // tile-by-tile loop below, which moves the reference as it goes, takes over at `resume`, after redoing the
+    // half in question (`redo_half`) if the tile's first half had already been accumulated.
+    int resume = 0;          // first tile the tile-by-tile loop has to do
+    int redo_half = -1;      // tile whose second half it has to do first, from the scores kept in `Sredo`
+    f32x16 Sredo[1];
+    if (nfull > 0) {
+        resume = nfull;
+        if (has_rows) {
+            f32x16 Sa, Sb;
+            bf16x8 Pa[2], Pb[2];
+            const float range = __builtin_amdgcn_exp2f(PIPE_TAU);
+            // scores of the first half tile, alone; the reference is their maximum
+            {
+                const bf16_t* K0 = kstage(0);
+                const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < C::KSTEPS; ++ks) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(K0 + koff[ks]);
+                    Sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], ks == 0 ? zero16 : Sa, 0, 0, 0);
+                }
+                float mx = Sa[0];
+#pragma unroll
+                for (int i = 1; i < 16; ++i) mx = fmaxf(mx, Sa[i]);
+                m = pair_max(mx);
+            }
+            const float mc = m * sc;
+            // first half of tile 0: nothing to multiply by V yet (no probability exceeds 1 here)
+            lsum += pipe_half<D, true, false>(kstage(0) + 32 * D, nullptr, koff, voff, qreg, Sa, Sb, Pb, Pa, O, sc, mc);
+            int t = 0;
+            for (; t + 1 < nfull; ++t) {
+                // every wave is done with K stage t and V stage t-1, and everybody's part of tile t+1 is in
+                wait_tile(t + 1);
+                __syncthreads();
+                if (next_req < ntiles) request_next();      // tile t + NSK
+                // second half of tile t: its probabilities; scores of (t+1, 0); P.V of (t, 0)
+                const float psb = pipe_half<D, true, true>(kstage(t + 1), vstage(t), koff, voff, qreg, Sb, Sa, Pa, Pb, O, sc, mc);
+                if (__builtin_amdgcn_ballot_w64(!(psb <= range)) != 0) { redo_half = t; resume = t + 1; Sredo[0] = Sb; break; }
+                lsum += psb;
+                // first half of tile t+1: its probabilities; scores of (t+1, 1); P.V of (t, 1)
+                const float psa = pipe_half<D, true, true>(kstage(t + 1) + 32 * D, vstage(t) + 32 * D, koff, voff, qreg, Sa, Sb, Pb, Pa, O,
+                                                           sc, mc);
+                if (__builtin_amdgcn_ballot_w64(!(psa <= range)) != 0) { resume = t + 1; break; }
+                lsum += psa;
+            }
+            if (t + 1 == nfull) {       // the loop ran to its end: second half of the last full tile, then its P.V
+                wait_tile(t + 1);
+                __syncthreads();
+                if (next_req < ntiles) request_next();
+                const float psb = pipe_half<D, false, true>(nullptr, vstage(t), koff, voff, qreg, Sb, Sa, Pa, Pb, O, sc, mc);
+                if (__builtin_amdgcn_ballot_w64(!(psb <= range)) != 0) {
+                    redo_half = t;
+                    Sredo[0] = Sb;
+                } else {
+                    lsum += psb;
+                    f32x16 none;
+                    bf16x8 unused[2];
+                    (void)pipe_half<D, false, true, false>(nullptr, vstage(t) + 32 * D, koff, voff, qreg, Sb, none, Pb, unused, O, sc, mc);
+                }
+            }
+        }
+    }
+    if (redo_half >= 0) {
+        // second half of tile `redo_half` with a moving reference, from its scores (every key of a full tile is
+        // visible: nothing to mask; its K rows may be gone by now, its V rows stay until tile redo_half + 3 is requested)
+        softmax_pv_phase<D, NW, 32, false>(vstage(redo_half) + 32 * D, voff, Sredo, O, m, lsum, sc, 1, lane);
+    }
+    // Tile by tile: what the pipelined loop left, and the tiles cut by the causal diagonal or by the end of the key
+    // list, differently for every wave.  Tile kt is in (everybody's part: the barrier that ended the previous tile
+    // came after the wait for it).
+    for (int kt = resume; kt < ntiles; ++kt) {
+        if (next_req <= kt + NSK - 1 && next_req < ntiles) request_next();
+        const int k0 = kt * BN;
+        if (k0 < kend_w) {
+            const int nsub = min(C::NSUB, (kend_w - k0 + 31) >> 5);
+            f32x16 S[C::NSUB];
+            score_phase<D, NW, BN, false>(kstage(kt), koff, qreg, S, k0, nsub, my_lim, lane);
+            softmax_pv_phase<D, NW, BN, false>(vstage(kt), voff, S, O, m, lsum, sc, nsub, lane);
+        }
+        wait_tile(kt + 1);
+        __syncthreads();
+    }
+    store_rows<D, NW, BN>(J, O, m, lsum, sc, smem, w, lane, row0, has_rows);
 }
 
 // Repetition rows when the memory zone fits one tile: t memory keys plus the row's own key
@@ -702,22 +973,21 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
 // output is rounded once.
 template <int D, int NW, int BN>
 __device__ __forceinline__ void rep_job(const FlashJob& J, float sc, bf16_t* smem) {
-    constexpr int QT = 1;
-    using C = Cfg<D, NW, BN, QT>;
+    using C = Cfg<D, NW, BN>;
     constexpr int NR = 32 / C::RPI;             // wave-wide row-layout accesses that cover 32 rows
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, l32 = lane & 31;
-    bf16_t* Ks = smem;
-    bf16_t* Vt = smem + C::NS * C::KBUF;
+    bf16_t* Ks = smem;                          // LDS: the memory-zone tile (K, V), then the queries of every wave
+    bf16_t* Vt = smem + C::KBUF;
     const int nkeys = J.n1;                     // <= BN
     const int row0 = 32 * w;
     const bool has_rows = row0 < J.q_rows;
     const int rl = lane / C::CPR, pc = lane % C::CPR;   // row-layout role: row rl of each group of RPI rows, piece pc
 
-    bf16_t* Qs = query_stage<D, NW, BN, QT>(smem, w);
-    load_queries_async<D, NW, BN, QT>(J, row0, lane, Qs);
-    load_tile_async<D, NW, BN, QT>(J, 0, nkeys, w, lane, Ks, Vt);
+    bf16_t* Qs = smem + C::KBUF + C::VBUF + w * 32 * D;
+    load_queries_async<D, NW, BN>(J, row0, lane, Qs);
+    load_tile_async<D, NW, BN>(J, 0, nkeys, w, lane, Ks, Vt);
     u32x4 kc[NR], vc[NR];
 #pragma unroll
     for (int i = 0; i < NR; ++i) {
@@ -736,20 +1006,20 @@ __device__ __forceinline__ void rep_job(const FlashJob& J, float sc, bf16_t* sme
             voff[dt] = (4 * g + q) * D + (4 * (dt ^ (q % (C::CPR / 4))) + 2 * ((lane >> 4) & 1) + ((i & 3) >> 1)) * 8 +
                        4 * (i & 1);
     }
-    f32x16 O[QT][C::DT];
-    float m[QT] = {-INFINITY}, lsum[QT] = {0.f};
+    f32x16 O[C::DT];
+    float m = -INFINITY, lsum = 0.f;
 #pragma unroll
     for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) O[0][dt][i] = 0.f;
+        for (int i = 0; i < 16; ++i) O[dt][i] = 0.f;
 
     wait_direct_loads();
     __syncthreads();
     float inv = 0.f;
     if (has_rows) {
-        bf16x8 qreg[QT][C::KSTEPS];
+        bf16x8 qreg[C::KSTEPS];
 #pragma unroll
-        for (int ks = 0; ks < C::KSTEPS; ++ks) qreg[0][ks] = *reinterpret_cast<const bf16x8*>(Qs + koff[ks]);
+        for (int ks = 0; ks < C::KSTEPS; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(Qs + koff[ks]);
         // the own key's score: q . k in the row layout, summed over the lanes of a row
         float ss[NR];
 #pragma unroll
@@ -775,24 +1045,24 @@ __device__ __forceinline__ void rep_job(const FlashJob& J, float sc, bf16_t* sme
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         const float sself = xs[l32];
 
-        const int my_lim[QT] = {nkeys - 1};
+        const int my_lim = nkeys - 1;
         const int nsub = min(C::NSUB, (nkeys + 31) >> 5);
-        f32x16 S[QT][C::NSUB];
-        score_phase<D, NW, BN, QT, false>(Ks, koff, qreg, S, 0, nsub, my_lim, lane);
-        softmax_pv_phase<D, NW, BN, QT, false>(Vt, voff, S, O, m, lsum, sc, nsub, lane);
+        f32x16 S[C::NSUB];
+        score_phase<D, NW, BN, false>(Ks, koff, qreg, S, 0, nsub, my_lim, lane);
+        softmax_pv_phase<D, NW, BN, false>(Vt, voff, S, O, m, lsum, sc, nsub, lane);
         // one more key: the row itself
-        const float mx = fmaxf(m[0], sself);
-        const float alpha = __builtin_amdgcn_exp2f((m[0] - mx) * sc);
+        const float mx = fmaxf(m, sself);
+        const float alpha = __builtin_amdgcn_exp2f((m - mx) * sc);
         const float p = __builtin_amdgcn_exp2f((sself - mx) * sc);
-        lsum[0] = lsum[0] * alpha + (g == 0 ? p : 0.f);
-        m[0] = mx;
-        const float ltot = pair_sum(lsum[0]);
+        lsum = lsum * alpha + (g == 0 ? p : 0.f);
+        m = mx;
+        const float ltot = pair_sum(lsum);
         inv = 1.f / ltot;
         const float oscale = alpha * inv;
 #pragma unroll
         for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) O[0][dt][i] *= oscale;
+            for (int i = 0; i < 16; ++i) O[dt][i] *= oscale;
         if (J.lse != nullptr && g == 0 && row0 + l32 < J.q_rows)
             J.lse[row0 + l32] = (mx * sc + __builtin_amdgcn_logf(ltot)) * LN2;
         inv *= p;   // weight of the row's own V in the output
@@ -806,7 +1076,7 @@ __device__ __forceinline__ void rep_job(const FlashJob& J, float sc, bf16_t* sme
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
                 float4 x;
-                x.x = O[0][dt][4 * i4 + 0]; x.y = O[0][dt][4 * i4 + 1]; x.z = O[0][dt][4 * i4 + 2]; x.w = O[0][dt][4 * i4 + 3];
+                x.x = O[dt][4 * i4 + 0]; x.y = O[dt][4 * i4 + 1]; x.z = O[dt][4 * i4 + 2]; x.w = O[dt][4 * i4 + 3];
                 *reinterpret_cast<float4*>(Of + l32 * C::FSTR + 32 * dt + 8 * i4 + 4 * g) = x;
             }
         if (g == 0) wf[l32] = inv;
@@ -838,8 +1108,9 @@ struct MaskParams {
     float sc;             // scale * log2(e)
 };
 
-template <int D, int NW, int BN, int QT>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(QT == 2 ? 1 : 2))) void mask_attn_kernel(
+// PIPE: reading and memory rows take the pipelined job (long key lists), repetition rows the single-trip job.
+template <int D, int NW, int BN, bool PIPE>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void mask_attn_kernel(
     MaskParams P) {
     extern __shared__ __align__(16) bf16_t smem[];
     const MaskSchedule& sch = P.sched;
@@ -876,10 +1147,18 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(QT == 2
     J.q = P.q + qrow * D;
     J.out = P.out + qrow * D;
     J.lse = P.lse ? P.lse + qrow : nullptr;
-    if (QT == 1 && mj.zone == ZONE_REP && sch.t <= BN)
+    if (mj.zone == ZONE_REP && sch.t <= BN) {
         rep_job<D, NW, BN>(J, P.sc, smem);
-    else
-        flash_job<D, NW, BN, QT>(J, P.sc, smem);
+    } else if constexpr (PIPE) {
+        static_assert(BN == 64, "the pipelined job walks tiles of 64 keys");
+        if constexpr (NW <= 4) {
+            if (mj.zone == ZONE_REP) { flash_job<D, NW, BN>(J, P.sc, smem); return; }
+        }
+        // (with eight waves the host only picks this kernel when the memory zone fits one tile: no such rows here)
+        flash_job_pipe<D, NW, (NW > 4 ? 4 : 2)>(J, P.sc, smem);
+    } else {
+        flash_job<D, NW, BN>(J, P.sc, smem);
+    }
 }
 
 // ---- compression pass ----------------------------------------------------------------------------
@@ -900,7 +1179,6 @@ struct NoRopeArg {};
 template <int D, int NW, int BN, bool ROPE>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void compress_kernel(
     CompressParams P, std::conditional_t<ROPE, RopeTable, NoRopeArg> RT) {
-    constexpr int QT = 1;
     extern __shared__ __align__(16) bf16_t smem[];
     constexpr int BM = 32 * NW;
     constexpr int CPR = D / 8;
@@ -935,7 +1213,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
         J.k2 = kd;
         J.q = J.out;
     }
-    flash_job<D, NW, BN, QT>(J, P.sc, smem);
+    flash_job<D, NW, BN>(J, P.sc, smem);
     // splice: the t new memory KVs join the compressed cache (Sec. 3.1 step 3)
     if (blk == 0) {
         const int pieces = P.t * D / 8;
@@ -966,7 +1244,6 @@ struct PrefillParams {
 // diagonal -- a reading-zone block of the mask pass whose earlier memory zones sit in one piece.
 template <int D, int NW, int BN, int KS, int NS>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void prefill_kernel(PrefillParams P) {
-    constexpr int QT = 1;
     extern __shared__ __align__(16) bf16_t smem[];
     constexpr int BM = 32 * NW / KS;
     const int bh = blockIdx.x / P.nblk;
@@ -986,7 +1263,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
     J.q = P.q + (new0 + o0) * D;
     J.out = P.out + (new0 + o0) * D;
     J.lse = P.lse ? P.lse + new0 + o0 : nullptr;
-    flash_job<D, NW, BN, QT, KS, NS>(J, P.sc, smem);
+    flash_job<D, NW, BN, KS, NS>(J, P.sc, smem);
     // the new tokens join the reading zone (rows no block of this launch reads)
     if (blk == 0) {
         const int pieces = P.n_new * D / 8;
@@ -1023,23 +1300,24 @@ int launch(K kernel, long long grid, int threads, int smem_bytes, hipStream_t st
 template <int D>
 int launch_mask_d(const MaskParams& P, int bm, hipStream_t st) {
     const long long grid = P.sched.size();
-    if (bm == 128) return launch(mask_attn_kernel<D, 4, 64, 1>, grid, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, st, P);
-    if (bm == 64) return launch(mask_attn_kernel<D, 2, 32, 1>, grid, 128, Cfg<D, 2, 32, 1>::SMEM_BYTES, st, P);
-    return launch(mask_attn_kernel<D, 1, 32, 1>, grid, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, st, P);
+    constexpr int PIPE4 = PipeCfg<D, 4, 2>::SMEM_BYTES > Cfg<D, 4, 64>::REP_BYTES ? PipeCfg<D, 4, 2>::SMEM_BYTES : Cfg<D, 4, 64>::REP_BYTES;
+    if (bm == 128) return launch(mask_attn_kernel<D, 4, 64, true>, grid, 256, PIPE4, st, P);
+    if (bm == 64) return launch(mask_attn_kernel<D, 2, 32, false>, grid, 128, Cfg<D, 2, 32>::SMEM_BYTES, st, P);
+    return launch(mask_attn_kernel<D, 1, 32, false>, grid, 64, Cfg<D, 1, 32>::SMEM_BYTES, st, P);
 }
 
 template <int D, bool ROPE>
 int launch_compress_d(CompressParams& P, int nbh, hipStream_t st, std::conditional_t<ROPE, RopeTable, NoRopeArg> RT) {
     if (P.t > 64) {
         P.nblk = (P.t + 127) / 128;
-        return launch(compress_kernel<D, 4, 64, ROPE>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, st, P, RT);
+        return launch(compress_kernel<D, 4, 64, ROPE>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64>::SMEM_BYTES, st, P, RT);
     }
     if (P.t > 32) {
         P.nblk = 1;
-        return launch(compress_kernel<D, 2, 32, ROPE>, nbh, 128, Cfg<D, 2, 32, 1>::SMEM_BYTES, st, P, RT);
+        return launch(compress_kernel<D, 2, 32, ROPE>, nbh, 128, Cfg<D, 2, 32>::SMEM_BYTES, st, P, RT);
     }
     P.nblk = 1;
-    return launch(compress_kernel<D, 1, 32, ROPE>, nbh, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, st, P, RT);
+    return launch(compress_kernel<D, 1, 32, ROPE>, nbh, 64, Cfg<D, 1, 32>::SMEM_BYTES, st, P, RT);
 }
 
 template <int D>
@@ -1049,7 +1327,7 @@ int launch_prefill_d(PrefillParams& P, int nbh, hipStream_t st) {
     // (three tiles requested ahead) and the keys of every tile split over two groups of waves.
     // Many workgroups: the plain variants, more of which fit a CU.
     const bool few = (long long)nbh * ((P.n_new + 63) / 64) < 1024;
-    constexpr int RING4 = 2 * Cfg<D, 4, 64, 1>::RING_BYTES;   // 4 stages of 64 keys
+    constexpr int RING4 = 2 * Cfg<D, 4, 64>::RING_BYTES;   // 4 stages of 64 keys
     if (few && P.n_new <= 32) {
         P.nblk = 1;
         return launch(prefill_kernel<D, 2, 64, 2, 4>, nbh, 128, RING4, st, P);
@@ -1060,11 +1338,11 @@ int launch_prefill_d(PrefillParams& P, int nbh, hipStream_t st) {
     }
     if (P.n_new > 64) {
         P.nblk = (P.n_new + 127) / 128;
-        return launch(prefill_kernel<D, 4, 64, 1, 2>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64, 1>::SMEM_BYTES, st, P);
+        return launch(prefill_kernel<D, 4, 64, 1, 2>, (long long)nbh * P.nblk, 256, Cfg<D, 4, 64>::SMEM_BYTES, st, P);
     }
     P.nblk = 1;
-    if (P.n_new > 32) return launch(prefill_kernel<D, 2, 64, 1, 2>, nbh, 128, Cfg<D, 2, 64, 1>::SMEM_BYTES, st, P);
-    return launch(prefill_kernel<D, 1, 32, 1, 2>, nbh, 64, Cfg<D, 1, 32, 1>::SMEM_BYTES, st, P);
+    if (P.n_new > 32) return launch(prefill_kernel<D, 2, 64, 1, 2>, nbh, 128, Cfg<D, 2, 64>::SMEM_BYTES, st, P);
+    return launch(prefill_kernel<D, 1, 32, 1, 2>, nbh, 64, Cfg<D, 1, 32>::SMEM_BYTES, st, P);
 }
 
 }  // namespace
@@ -1090,7 +1368,7 @@ int launch_mask_attn_mfma(const void* q, const void* k, const void* v, void* out
     MaskParams P;
     P.q = static_cast<const bf16_t*>(q); P.k = static_cast<const bf16_t*>(k); P.v = static_cast<const bf16_t*>(v);
     P.out = static_cast<bf16_t*>(out); P.lse = lse;
-    const int bm = mask_block_rows(g.R);
+    const int bm = mask_block_rows(g.R, g.t);
     P.sched = MaskSchedule::make(nbh, g.t, g.c, g.n, bm);
     P.slab_magic = g.t > 1 ? (unsigned)((1ULL << 32) / (unsigned)g.t) + 1u : 0u;
     P.sc = scale * LOG2E;

@@ -88,8 +88,10 @@ struct MaskSchedule {
     }
 };
 
-// Rows per workgroup of the MFMA mask-pass kernel for a reading-zone length R.
-inline int mask_block_rows(int R) { return R >= 128 ? 128 : (R >= 64 ? 64 : 32); }
+// Rows per workgroup of the MFMA mask-pass kernels for a reading zone of R rows and a memory zone of t rows.
+inline int mask_block_rows(int R, int t) { (void)t; return R >= 128 ? 128 : (R >= 64 ? 64 : 32); }
+// Rows per workgroup of the gradient kernels.
+inline int mask_bwd_block_rows(int R) { return R >= 128 ? 128 : (R >= 64 ? 64 : 32); }
 
 inline bool use_mfma_path(int dtype, int head_dim) {
     return dtype == LOMA_BF16 && (head_dim == 64 || head_dim == 128);
