@@ -959,6 +959,7 @@ __device__ __forceinline__ void flash_job_pipe(const FlashJob& J, float sc, bf16
         wait_tile(kt + 1);
         __syncthreads();
     }
+    __syncthreads();   // a wave whose tiles were all full ones comes straight from reads of the ring the staging overlaps
     store_rows<D, NW, BN>(J, O, m, lsum, sc, smem, w, lane, row0, has_rows);
 }
 

@@ -2,6 +2,8 @@
 // half-wave and row reductions, direct HBM -> LDS loads with hand-placed waits, the transposing
 // LDS read.  Not part of the ABI.
 #pragma once
+#include <type_traits>
+
 #include "loma_internal.h"
 
 namespace loma {
@@ -96,6 +98,48 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 __device__ __forceinline__ s16x4 lds_read_tr(const bf16_t* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
         (__attribute__((address_space(3))) s16x4*)(const_cast<bf16_t*>(p)));
+}
+
+// ---- accumulators that live in the accumulation registers a0..a127 BY NAME ------------------------------------
+// For kernels whose MFMA accumulators do not fit the 256 ordinary registers of a lane next to everything else
+// (as C++ values the compiler copies them between the register files on every tile).  Every statement names all
+// 128 registers as clobbered, so the compiler keeps nothing of its own there across them.  The instructions are
+// opaque to the compiler's hazard bookkeeping: consecutive MFMAs must name different accumulators, and
+// settle_acc() comes before the first read of one.
+#define LOMA_ACC_REGS "a0","a1","a2","a3","a4","a5","a6","a7","a8","a9","a10","a11","a12","a13","a14","a15","a16","a17","a18","a19","a20","a21","a22","a23","a24","a25","a26","a27","a28","a29","a30","a31","a32","a33","a34","a35","a36","a37","a38","a39","a40","a41","a42","a43","a44","a45","a46","a47","a48","a49","a50","a51","a52","a53","a54","a55","a56","a57","a58","a59","a60","a61","a62","a63","a64","a65","a66","a67","a68","a69","a70","a71","a72","a73","a74","a75","a76","a77","a78","a79","a80","a81","a82","a83","a84","a85","a86","a87","a88","a89","a90","a91","a92","a93","a94","a95","a96","a97","a98","a99","a100","a101","a102","a103","a104","a105","a106","a107","a108","a109","a110","a111","a112","a113","a114","a115","a116","a117","a118","a119","a120","a121","a122","a123","a124","a125","a126","a127"
+template <int BASE>
+__device__ __forceinline__ void mfma_named(bf16x8 a, bf16x8 b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 a[%2:%3], %0, %1, a[%2:%3]" ::"v"(a), "v"(b), "n"(BASE), "n"(BASE + 15)
+                 : LOMA_ACC_REGS);
+}
+template <int I>
+__device__ __forceinline__ void zero_named() {
+    asm volatile("v_accvgpr_write_b32 a[%0], 0" ::"n"(I) : LOMA_ACC_REGS);
+}
+template <int I>
+__device__ __forceinline__ float read_named() {
+    float x;
+    asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(x) : "n"(I) : LOMA_ACC_REGS);
+    return x;
+}
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+// the last MFMA (16 passes of 4 cycles) has written its accumulator
+__device__ __forceinline__ void settle_acc() { asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory"); }
+// a[BASE .. BASE + 16 DT) -> accumulator values in the layout of the MFMA result
+template <int BASE, int DT>
+__device__ __forceinline__ void fetch_named(f32x16 (&acc)[DT]) {
+    static_for<0, 16 * DT>([&](auto i) { acc[i.value / 16][i.value % 16] = read_named<BASE + i.value>(); });
+}
+
+template <int I>
+__device__ __forceinline__ void write_named(float x) {
+    asm volatile("v_accvgpr_write_b32 a[%0], %1" ::"n"(I), "v"(x) : LOMA_ACC_REGS);
 }
 
 }  // namespace mfma
