@@ -6,7 +6,8 @@ namespace loma {
 namespace {
 
 // dK/dV pass: per (b,h) the blocks of memory keys (longest first: the first block is seen by every later
-// chunk), then the reading-zone key blocks of every chunk.  Repetition-zone keys belong to the dQ pass.
+// chunk; each streams the later chunks' reading rows from the last chunk backwards), then the reading-zone key
+// blocks of every chunk.  Repetition-zone keys belong to the dQ pass.
 // With P.split == 2 every block of memory keys is worked on by two workgroups: the first takes the block's own
 // memory and repetition rows and the reading rows of the nearer later chunks, the second the reading rows of
 // the farther ones (about half the rows each); both leave fp32 partial sums that bwd_reduce_kernel adds.
@@ -21,6 +22,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_dkv_kernel(BwdParams P) {
     BwdJob J;
     J.rep = 0; J.t = P.t; J.magic_t = magic_of(P.t); J.z0 = J.z1 = 0; J.cb = 0;
     J.part_k = J.part_v = nullptr;
+    J.pipe0 = J.pipe1 = 0;
     if (u < nMK * P.split) {
         const int part = u % P.split;
         const int mk0 = (u / P.split) * P.bm;
@@ -38,9 +40,12 @@ __global__ __launch_bounds__(64 * NW) void bwd_dkv_kernel(BwdParams P) {
             float* base = P.partials + ((long)(bh * P.split + part) * 2) * nmk * D;
             J.part_k = base; J.part_v = base + (long)nmk * D;
         }
-        J.z0 = y_first + 1 + a_lo; J.z1 = y_first;
-        J.str.base0 = (y_first + 1 + a_lo) * P.s; J.str.n0 = (a_hi - a_lo) * P.R;
-        J.str.slab0 = P.R; J.str.stride0 = P.s; J.str.magic0 = magic_of(P.R);
+        // reading rows of the later chunks, the farthest chunk first: the blocks of one (b,h) that run side by side
+        // then stream the same rows at about the same time, and the tiles every key of the block sees come first
+        J.z0 = y_first + a_hi; J.z1 = y_first;
+        J.str.base0 = (y_first + a_hi) * P.s; J.str.n0 = (a_hi - a_lo) * P.R;
+        J.str.slab0 = P.R; J.str.stride0 = -P.s; J.str.magic0 = magic_of(P.R);
+        if (P.R % 32 == 0) J.pipe1 = min(a_hi - a_lo, max(0, J.z0 - y_last)) * (P.R / 32);   // chunks past the block's last one
         J.str.base1 = y_first * P.s + P.R; J.str.n1 = part == 0 ? own_rows : 0;
         J.str.slab1 = P.s - P.R; J.str.stride1 = P.s; J.str.magic1 = magic_of(P.s - P.R);
     } else {
@@ -50,6 +55,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_dkv_kernel(BwdParams P) {
         J.ooff = 0; J.orows = min(P.bm, P.R - o0);
         J.own = owner_range(y * P.s + o0);
         J.str = one_range(y * P.s + o0, P.R + P.t - o0);
+        J.pipe0 = (J.orows + 30) / 32; J.pipe1 = (P.R + P.t - o0) / 32;   // rows from the block's last one on, whole tiles
     }
     J.nstr = J.str.n0 + J.str.n1;
     const BwdTensors T = at_sequence(P.T, (long)bh * P.n * P.s, D);

@@ -111,10 +111,11 @@ struct BwdJob {
     int vis;       // which rule decides whether streamed row j and owner row r interact
     int cb;        // VIS_CAUSAL: j <= cb + r.   VIS_FROM_ROW: j >= r.
     // VIS_MEMKEYS: owner r is memory key ooff + r of chunk yk = (ooff + r) / t; streamed row j of range 0
-    // is a reading row of chunk z0 + slab index (visible iff yk < that chunk), of range 1 a memory
-    // or repetition row of chunk z1 + slab index (visible iff yk == that chunk)
+    // is a reading row of chunk z0 - slab index (the farthest chunk comes first; visible iff yk < that
+    // chunk), of range 1 a memory or repetition row of chunk z1 + slab index (visible iff yk == that chunk)
     int t, z0, z1;
     unsigned magic_t;
+    int pipe0, pipe1;   // dK/dV pass: tiles [pipe0, pipe1) of the stream hold only visible pairs, whichever the owner row
     int rep;       // dQ pass on repetition rows: add the rows' own-key terms when they leave
     // dK/dV pass of a block whose stream is shared out over several workgroups: fp32 partial sums, row
     // `ooff + r` of each (nullptr: the block is whole and writes dk, dv itself)
@@ -137,13 +138,15 @@ struct BCfg {
         return ns * STAGE_BYTES > nw * WAVE_STAGING_BYTES ? ns * STAGE_BYTES : nw * WAVE_STAGING_BYTES;
     }
 };
-// Tile stages: the loads run NS - 1 tiles ahead of the arithmetic.  Four stages cost nothing where the
-// rows' staging area is as large anyway (4 waves) and where one workgroup per SIMD pair is all the
-// registers allow (dK/dV pass); the dQ pass with fewer waves walks short lists and would rather fit
-// more workgroups on a CU.
+// Tile stages and how far the loads run ahead of the arithmetic.  The dQ pass reads one tile at a time and
+// reuses a stage as soon as the barrier after its tile has passed (AHEAD = NS - 1); with fewer than four waves it
+// walks short lists and would rather fit more workgroups on a CU.  The dK/dV pass runs one workgroup per SIMD set
+// anyway (its registers allow no more) and, in its pipelined loop, reads three consecutive tiles in one
+// iteration: a stage is reused two barriers after its tile's first use (AHEAD = NS - 2).
 template <int PASS, int NW>
 struct Stages {
-    static constexpr int NS = (PASS == 1 || NW == 4) ? 4 : 2;
+    static constexpr int NS = PASS == 1 ? (NW == 4 ? 6 : 4) : (NW == 4 ? 4 : 2);
+    static constexpr int AHEAD = PASS == 1 ? NS - 2 : NS - 1;
 };
 
 // position of 16-byte piece c of tile row r: c ^ swz(r).  16 consecutive rows give 16 different values
@@ -331,6 +334,136 @@ __device__ __forceinline__ void store_staged_rep(const float* Of, const BwdTenso
     }
 }
 
+// v_exp_f32 and the bf16 packing AT THEIR PLACE in the instruction stream: the compiler orders volatile statements
+// among themselves and against the scheduling fences, so these two pin a score's arithmetic (which hangs between
+// them by its data dependences) to the slot of the pipelined loop it is written in.
+__device__ __forceinline__ float exp2_at(float x) {
+    float y;
+    asm volatile("v_exp_f32 %0, %1" : "=v"(y) : "v"(x));
+    return y;
+}
+__device__ __forceinline__ uint32_t pack_bf16_at(float a, float b) {
+    uint32_t r;
+    asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// S' / dP' MFMAs of the dK/dV pass: the owner rows' operand comes from the accumulation registers (constraint "a";
+// that is where the 64 registers of k and v live for the whole kernel, past a127), the result goes to ordinary
+// registers.  Opaque to the compiler's hazard bookkeeping: settle_scores() comes between the last of them and the
+// first read of the result unless other work of at least that length does.
+__device__ __forceinline__ void mfma_owner_first(f32x16& acc, bf16x8 a, bf16x8 owner) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(owner));
+}
+__device__ __forceinline__ void mfma_owner(f32x16& acc, bf16x8 a, bf16x8 owner) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(owner));
+}
+__device__ __forceinline__ void settle_scores() { asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory"); }
+
+// One step of the pipelined loop over tiles whose pairs are all visible.  Three tiles are at work:
+//     DO_A: S' and dP' of the tile in stage stA into (Sn, dPn)                         -- 2 KSTEPS MFMAs
+//     DO_B: P and dS of the tile whose S', dP' are (Sc, dPc), packed to bf16 in pk_out  -- exponentials and vector ALU
+//     DO_C: acc^T += X^T dS (and Y^T P) of the tile in stage stC, packed in pk_in      -- the other MFMAs
+// cut into 2 KSTEPS slots of one MFMA of A, one of C (dQ pass: every other slot) and a sixteenth of B, with the
+// LDS reads of a slot's operands two slots ahead of it.  A scheduling fence ends every slot: the matrix pipe
+// runs under the vector arithmetic of ONE instruction stream (one wave per SIMD is all the registers allow).
+// stB is the stage that holds B's tile (its rows' -lse log2(e) and delta, dK/dV pass).  pk[0] = P, pk[1] = dS,
+// element pairs in accumulator order.
+template <int D, int PASS, bool DO_A, bool DO_B, bool DO_C>
+__device__ __forceinline__ void pipe_step(const bf16_t* stA, const bf16_t* stB, const bf16_t* stC,
+                                          const int (&poff)[BCfg<D>::KSTEPS], const int (&toff)[2][BCfg<D>::DT],
+                                          const bf16x8 (&xo)[BCfg<D>::KSTEPS], const bf16x8 (&yo)[BCfg<D>::KSTEPS],
+                                          f32x16& Sn, f32x16& dPn, const f32x16& Sc, const f32x16& dPc,
+                                          uint32_t (&pk_out)[2][8], const uint32_t (&pk_in)[2][8],
+                                          f32x16 (&accX)[BCfg<D>::DT], float sc, float nl_own, float dl_own, int g) {
+    using C = BCfg<D>;
+    constexpr int NSLOT = 2 * C::KSTEPS, EPS = 16 / NSLOT, RA = 2;
+    constexpr int CSTRIDE = PASS == PASS_DKV ? 1 : 2;          // a C MFMA every CSTRIDE slots (the odd ones in the dQ pass)
+    constexpr int NC = NSLOT / CSTRIDE;
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    bf16x8 aop[NSLOT], cop[NC];
+    float4 nlv[4], dlv[4];
+    auto read_a = [&](auto jc) {
+        constexpr int j = jc.value;
+        aop[j] = *reinterpret_cast<const bf16x8*>(stA + ((j & 1) ? C::TILE : 0) + poff[j >> 1]);
+    };
+    // C MFMA c: dK/dV pass (step, dt, dK or dV) = (c / (2 DT), (c / 2) % DT, c % 2); dQ pass (step, dt) = (c / DT, c % DT)
+    auto read_c = [&](auto cc) {
+        constexpr int c = cc.value;
+        constexpr int step = PASS == PASS_DKV ? c / (2 * C::DT) : c / C::DT;
+        constexpr int dt = PASS == PASS_DKV ? (c / 2) % C::DT : c % C::DT;
+        const bf16_t* base = stC + ((PASS == PASS_DKV && (c & 1)) ? C::TILE : 0) + 16 * step * D;
+        const s16x4 lo = lds_read_tr(base + toff[0][dt]);
+        const s16x4 hi = lds_read_tr(base + toff[1][dt]);
+        cop[c] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    auto read_rows = [&](auto ac) {   // -lse log2(e) and delta of the four streamed rows of elements 4a .. 4a + 3
+        constexpr int a = ac.value;
+        const float4* ld = reinterpret_cast<const float4*>(stB + 2 * C::TILE);
+        nlv[a] = ld[2 * a + g];
+        dlv[a] = ld[8 + 2 * a + g];
+    };
+    // what the first slots need
+    if constexpr (DO_A) static_for<0, RA>(read_a);
+    if constexpr (DO_C) static_for<0, (RA + CSTRIDE - 1) / CSTRIDE>(read_c);
+    if constexpr (DO_B && PASS == PASS_DKV) static_for<0, 4>([&](auto ac) { if constexpr (4 * ac.value / EPS < RA) read_rows(ac); });
+    __builtin_amdgcn_sched_barrier(0);
+    float p_even = 0.f, ds_even = 0.f;
+    static_for<0, NSLOT>([&](auto jc) {
+        constexpr int j = jc.value;
+        if constexpr (DO_A && PASS == PASS_DKV) {
+            if constexpr (j == 0) mfma_owner_first(Sn, aop[j], xo[0]);
+            else if constexpr (j == 1) mfma_owner_first(dPn, aop[j], yo[0]);
+            else if constexpr ((j & 1) == 0) mfma_owner(Sn, aop[j], xo[j >> 1]);
+            else mfma_owner(dPn, aop[j], yo[j >> 1]);
+        } else if constexpr (DO_A) {
+            if constexpr ((j & 1) == 0) Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[j], xo[j >> 1], j == 0 ? zero16 : Sn, 0, 0, 0);
+            else dPn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[j], yo[j >> 1], j == 1 ? zero16 : dPn, 0, 0, 0);
+        }
+        if constexpr (DO_B) {
+            static_for<j * EPS, (j + 1) * EPS>([&](auto ec) {
+                constexpr int e = ec.value;
+                float nl = nl_own, dl = dl_own;
+                if constexpr (PASS == PASS_DKV) {
+                    const float nl4[4] = {nlv[e / 4].x, nlv[e / 4].y, nlv[e / 4].z, nlv[e / 4].w};
+                    const float dl4[4] = {dlv[e / 4].x, dlv[e / 4].y, dlv[e / 4].z, dlv[e / 4].w};
+                    nl = nl4[e % 4];
+                    dl = dl4[e % 4];
+                }
+                const float pr = exp2_at(fmaf(Sc[e], sc, nl));
+                const float ds = pr * (dPc[e] - dl);
+                if constexpr ((e & 1) == 0) {
+                    p_even = pr;
+                    ds_even = ds;
+                } else {
+                    pk_out[0][e >> 1] = pack_bf16_at(p_even, pr);
+                    pk_out[1][e >> 1] = pack_bf16_at(ds_even, ds);
+                }
+            });
+        }
+        if constexpr (DO_C && (j % CSTRIDE) == CSTRIDE - 1) {
+            constexpr int c = j / CSTRIDE;
+            constexpr int step = PASS == PASS_DKV ? c / (2 * C::DT) : c / C::DT;
+            constexpr int dt = PASS == PASS_DKV ? (c / 2) % C::DT : c % C::DT;
+            const uint4 wp = {pk_in[0][4 * step], pk_in[0][4 * step + 1], pk_in[0][4 * step + 2], pk_in[0][4 * step + 3]};
+            const uint4 wds = {pk_in[1][4 * step], pk_in[1][4 * step + 1], pk_in[1][4 * step + 2], pk_in[1][4 * step + 3]};
+            if constexpr (PASS == PASS_DKV) {
+                if constexpr ((c & 1) == 0) mfma_named<16 * dt>(cop[c], __builtin_bit_cast(bf16x8, wds));
+                else mfma_named<64 + 16 * dt>(cop[c], __builtin_bit_cast(bf16x8, wp));
+            } else {
+                accX[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cop[c], __builtin_bit_cast(bf16x8, wds), accX[dt], 0, 0, 0);
+            }
+        }
+        // reads for the slots two ahead
+        if constexpr (DO_A && j + RA < NSLOT) read_a(std::integral_constant<int, j + RA>{});
+        if constexpr (DO_C && ((j + RA) % CSTRIDE) == CSTRIDE - 1 && (j + RA) / CSTRIDE < NC && (j + RA) / CSTRIDE >= (RA + CSTRIDE - 1) / CSTRIDE)
+            read_c(std::integral_constant<int, (j + RA) / CSTRIDE>{});
+        if constexpr (DO_B && PASS == PASS_DKV)
+            static_for<1, 4>([&](auto ac) { if constexpr (4 * ac.value / EPS - RA == j) read_rows(ac); });
+        __builtin_amdgcn_sched_barrier(0);
+    });
+}
+
 template <int D, int NW, int PASS>
 __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, float scale, float sc, bf16_t* smem) {
     using C = BCfg<D>;
@@ -359,13 +492,20 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
     LL.ld = (lane < 32 ? T.nl : T.delta) + (lane & 31);
 
     const unsigned smem_addr = lds_address(smem);
-    // the loads run AHEAD tiles ahead of the arithmetic
+    // the loads run AHEAD tiles ahead of the arithmetic; tile kt lives in stage kt % NS
     constexpr int NS = Stages<PASS, NW>::NS;
-    constexpr int AHEAD = NS - 1;
+    constexpr int AHEAD = Stages<PASS, NW>::AHEAD;
     constexpr int LPT = 2 * (C::BN / C::RPI / NW) + (PASS == PASS_DKV ? 1 : 0);   // direct loads per wave and tile
-#pragma unroll
-    for (int t = 0; t < AHEAD; ++t)
-        if (t < ntiles) request_tile<D, NW, PASS>(J, X, Y, LL, t * C::BN, w, lane, smem_addr + t * C::STAGE_BYTES);
+    int next_req = 0;   // tiles [0, next_req) have been requested
+    auto request_upto = [&](int last) {
+        while (next_req <= last && next_req < ntiles) {
+            request_tile<D, NW, PASS>(J, X, Y, LL, next_req * C::BN, w, lane, smem_addr + (next_req % NS) * C::STAGE_BYTES);
+            ++next_req;
+        }
+    };
+    // this wave's loads of tile `tile` (or of the last one, past the end) have landed; younger tiles stay in flight
+    auto wait_for = [&](int tile) { wait_next_tile<LPT, AHEAD - 1>(next_req - 1 - min(tile, ntiles - 1)); };
+    request_upto(AHEAD - 1);
 
     // owner rows as B operands: lane (row l32, half g) holds head-dim 16*ks + 8*g .. +7
     bf16x8 xo[C::KSTEPS], yo[C::KSTEPS];
@@ -429,11 +569,9 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
     // phases fall into the others' arithmetic.  Either way the stage a request overwrites was last read
     // in the iteration before the barrier this wave has passed, and the same loads are in flight at the wait.
     const bool late_request = (w & 1) != 0;
-    for (int kt = 0; kt < ntiles; ++kt) {
+    auto tile_by_tile = [&](int kt) {
         bf16_t* stage = smem + (kt % NS) * (C::STAGE_BYTES / 2);
-        if (!late_request && kt + AHEAD < ntiles)
-            request_tile<D, NW, PASS>(J, X, Y, LL, (kt + AHEAD) * C::BN, w, lane,
-                                      smem_addr + ((kt + AHEAD) % NS) * C::STAGE_BYTES);
+        if (!late_request) request_upto(kt + AHEAD);
         const int j0 = kt * C::BN, j1 = min(j0 + C::BN, J.nstr) - 1;   // first and last live streamed row
         // does this wave's 32 x 32 block hold no visible pair, only visible pairs, or both?
         bool none = !has_rows, cut = j0 + C::BN > J.nstr;
@@ -446,7 +584,7 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
             cut = cut || j0 < r_hi;
         } else {
             const TileInfo ti = tile_info(J.str, J.nstr, j0);
-            const int z = (ti.in0 ? J.z0 : J.z1) + ti.slab_index;   // chunk of the tile's rows, if it has just one
+            const int z = ti.in0 ? J.z0 - ti.slab_index : J.z1 + ti.slab_index;   // chunk of the tile's rows, if it has just one
             if (!ti.contig) cut = true;
             else {
                 if (ti.in0) { none = none || yk_lo >= z; cut = cut || yk_hi >= z; }
@@ -484,8 +622,13 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int ks = 0; ks < C::KSTEPS; ++ks) {
-                    S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax[ks % PF], xo[ks], S, 0, 0, 0);
-                    dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ay[ks % PF], yo[ks], dP, 0, 0, 0);
+                    if constexpr (PASS == PASS_DKV) {
+                        if (ks == 0) { mfma_owner_first(S, ax[0], xo[0]); mfma_owner_first(dP, ay[0], yo[0]); }
+                        else { mfma_owner(S, ax[ks % PF], xo[ks]); mfma_owner(dP, ay[ks % PF], yo[ks]); }
+                    } else {
+                        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax[ks % PF], xo[ks], S, 0, 0, 0);
+                        dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ay[ks % PF], yo[ks], dP, 0, 0, 0);
+                    }
                     if (ks + PF < C::KSTEPS) {
                         ax[ks % PF] = *reinterpret_cast<const bf16x8*>(Xs + poff[ks + PF]);
                         ay[ks % PF] = *reinterpret_cast<const bf16x8*>(Ys + poff[ks + PF]);
@@ -500,6 +643,7 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
                 tx[0][dt] = read_t(Xs, 0, dt);
                 if constexpr (PASS == PASS_DKV) ty[0][dt] = read_t(Ys, 0, dt);
             }
+            if constexpr (PASS == PASS_DKV) settle_scores();
             __builtin_amdgcn_sched_barrier(0);
             // ---- P = exp2(S' sc + nl), dS = P (dP' - delta) ----------------------------------------------
             if constexpr (PASS == PASS_DQ) {
@@ -539,7 +683,7 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
                     else {
                         int a;
                         list_row(J.str, min(j, J.nstr - 1), &a);
-                        vis = vis && (j < J.str.n0 ? yk < J.z0 + a : yk == J.z1 + a);
+                        vis = vis && (j < J.str.n0 ? yk < J.z0 - a : yk == J.z1 + a);
                     }
                     S[i] = vis ? S[i] : 0.f;
                     dP[i] = vis ? dP[i] : 0.f;
@@ -579,12 +723,72 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        if (late_request && kt + AHEAD < ntiles)
-            request_tile<D, NW, PASS>(J, X, Y, LL, (kt + AHEAD) * C::BN, w, lane,
-                                      smem_addr + ((kt + AHEAD) % NS) * C::STAGE_BYTES);
-        wait_next_tile<LPT, AHEAD - 1>(min(kt + AHEAD, ntiles - 1) - (kt + 1));
+        if (late_request) request_upto(kt + AHEAD);
+        wait_for(kt + 1);
         __syncthreads();
+    };
+
+    // Tiles [p0, p1) hold only visible pairs for every wave: they go through the pipelined loop.
+    int p0 = 0, p1 = 0;
+    if constexpr (PASS == PASS_DKV) {
+        p0 = J.pipe0; p1 = J.pipe1;
+        if (p1 - p0 < 3) p0 = p1 = 0;
     }
+    for (int kt = 0; kt < p0; ++kt) tile_by_tile(kt);
+    if constexpr (PASS == PASS_DKV) {
+        if (p1 > p0) {
+            // In iteration i: S', dP' of tile i + 1 and the accumulation of tile i - 1 on the matrix pipe between the
+            // exponentials of tile i.  Two sets of score registers and of packed operands take turns.
+            f32x16 Sa, dPa, Sb, dPb;
+            uint32_t pka[2][8], pkb[2][8];
+            auto stage_of = [&](int kt) -> const bf16_t* { return smem + (kt % NS) * (C::STAGE_BYTES / 2); };
+            request_upto(p0 + AHEAD);
+            pipe_step<D, PASS, true, false, false>(stage_of(p0), nullptr, nullptr, poff, toff, xo, yo, Sa, dPa, Sa, dPa, pka, pkb,
+                                                  accX, sc, nl_own, dl_own, g);
+            wait_for(p0 + 1);
+            __syncthreads();
+            // even steps (counted from p0) read (Sa, dPa) and the packed operands in pkb and write (Sb, dPb) and pka;
+            // odd steps the other way round.  The steady loop takes an odd and an even step per trip, in straight-line
+            // code, so that no register moves between the sets.
+            auto sync_after = [&](int i) {
+                wait_for(i + 2);
+                __syncthreads();
+            };
+#define LOMA_STEP(A_, B_, C_, I_, SN, DPN, SC, DPC, PKO, PKI)                                                                  \
+    pipe_step<D, PASS, A_, B_, C_>(stage_of((I_) + 1), stage_of(I_), stage_of((I_)-1), poff, toff, xo, yo, SN, DPN, SC, DPC, PKO, \
+                                   PKI, accX, sc, nl_own, dl_own, g)
+            int i = p0;
+            request_upto(i + AHEAD);
+            LOMA_STEP(true, true, false, i, Sb, dPb, Sa, dPa, pka, pkb);
+            sync_after(i);
+            ++i;
+            for (; i + 2 < p1; i += 2) {
+                request_upto(i + AHEAD);
+                LOMA_STEP(true, true, true, i, Sa, dPa, Sb, dPb, pkb, pka);
+                sync_after(i);
+                request_upto(i + 1 + AHEAD);
+                LOMA_STEP(true, true, true, i + 1, Sb, dPb, Sa, dPa, pka, pkb);
+                sync_after(i + 1);
+            }
+            // one or two steps are left (p1 - p0 >= 3): the last one starts no new tile
+            if (i + 2 == p1) {
+                request_upto(i + AHEAD);
+                LOMA_STEP(true, true, true, i, Sa, dPa, Sb, dPb, pkb, pka);
+                sync_after(i);
+                request_upto(i + 1 + AHEAD);
+                LOMA_STEP(false, true, true, i + 1, Sb, dPb, Sa, dPa, pka, pkb);
+                sync_after(i + 1);
+                LOMA_STEP(false, false, true, p1, Sa, dPa, Sb, dPb, pkb, pka);
+            } else {
+                request_upto(i + AHEAD);
+                LOMA_STEP(false, true, true, i, Sa, dPa, Sb, dPb, pkb, pka);
+                sync_after(i);
+                LOMA_STEP(false, false, true, p1, Sb, dPb, Sa, dPa, pka, pkb);
+            }
+#undef LOMA_STEP
+        }
+    }
+    for (int kt = p1; kt < ntiles; ++kt) tile_by_tile(kt);
 
     // rows leave through the wave's own fp32 staging area (the tile stages are free: the loop ended on a barrier)
     float* Of = reinterpret_cast<float*>(smem) + w * (C::WAVE_STAGING_BYTES / 4);

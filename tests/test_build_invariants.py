@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 @pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"), reason="hipcc not available")
-def test_dkv_kernels_use_only_the_named_accumulation_registers(tmp_path):
+def test_dkv_kernels_keep_only_accumulators_and_owner_rows_in_accumulation_registers(tmp_path):
     from paper_2401_09486_amd import build as hip_build
     src = os.path.join(hip_build.CSRC, "loma_bwd_dkv.hip")
     out = str(tmp_path / "dkv.s")
@@ -30,7 +30,9 @@ def test_dkv_kernels_use_only_the_named_accumulation_registers(tmp_path):
            for agpr, name, scratch, sspill, vgpr, vspill in kernels if "bwd_dkv_kernel" in name]
     assert len(dkv) == 6, [k[0] for k in dkv]           # head_dim 64 and 128, 1, 2 and 4 waves
     for name, agpr, scratch, sspill, vgpr, vspill in dkv:
-        assert agpr == 128, f"{name}: {agpr} accumulation registers allocated; the kernel names a0..a127 and relies on no others"
+        head_dim = 128 if "ILi128E" in name else 64
+        # a0..a127 by name, and past them the owner rows' k and v (operands of the S' and dP' MFMAs, head_dim / 2 registers)
+        assert agpr == 128 + head_dim // 2, f"{name}: {agpr} accumulation registers allocated"
         assert scratch == 0, f"{name}: {scratch} bytes of scratch memory"
         # a value the compiler parks in an accumulation register between two assembly statements would be a spill
         # copy: none may exist, and the ordinary registers must not be exhausted (256 is the file's limit per wave)
@@ -40,7 +42,6 @@ def test_dkv_kernels_use_only_the_named_accumulation_registers(tmp_path):
         # every access to an accumulation register outside the MFMAs is one of the kernel's own 128 clears or of its
         # final reads (one per accumulator: 2 * head_dim / 2); a copy the compiler parked there would add to these
         body = re.search(re.escape(name) + r":.*?\.Lfunc_end", text, flags=re.S).group(0)
-        head_dim = 128 if "ILi128E" in name else 64
         assert body.count("v_accvgpr_write") == 128, f"{name}: {body.count('v_accvgpr_write')} writes to accumulation registers"
         assert body.count("v_accvgpr_read") == head_dim, f"{name}: {body.count('v_accvgpr_read')} reads of accumulation registers"
         assert "v_accvgpr_mov" not in body
