@@ -54,16 +54,36 @@ def profile_traffic(path=TRAFFIC_PROFILE):
             return {}
         factor[name] = float(m.group(1))
     out = {}
-    for m in re.finditer(r"^\|\s*`([^`]+)`\s*\|[^|]*\|\s*\d+\s*\|\s*([0-9.]+)\s*\|\s*([0-9.]+)\s*\|", text, flags=re.M):
-        out[m.group(1)] = (factor["FETCH_SIZE"] * float(m.group(2)) + factor["WRITE_SIZE"] * float(m.group(3))) * 1024.0
+    # rows: | `kernel` | config N ... | dispatches | FETCH_SIZE | WRITE_SIZE | ...   keyed "kernel @cN" ("@cNxL": L layers per launch)
+    for m in re.finditer(r"^\|\s*`([^`]+)`\s*\|\s*config (\d+)(?: \((\d+) layers per launch\))?[^|]*\|\s*\d+\s*\|\s*([0-9.]+)\s*\|\s*([0-9.]+)\s*\|",
+                         text, flags=re.M):
+        key = "%s @c%s%s" % (m.group(1), m.group(2), ("x" + m.group(3)) if m.group(3) else "")
+        out[key] = (factor["FETCH_SIZE"] * float(m.group(4)) + factor["WRITE_SIZE"] * float(m.group(5))) * 1024.0
     return out
 
 
-def traffic_of(table, *kernels):
-    """Sum of the profile's traffic over the kernels of one call, or None if one of them is missing."""
-    if not all(k in table for k in kernels):
+# Kernels behind every roofline object of the output line, with the configuration tag the committed counter profile
+# lists them under ("c3x{L}": L layer caches per launch).
+ROOFLINE_KERNELS = {
+    "roofline": ("c5", ("decode_split_kernel<128, 4, false, false>", "decode_combine_kernel<128, false>")),
+    "roofline_long_context_mask": ("c4", ("mask_attn_kernel<128, 4, 64, true>",)),
+    "roofline_high_ratio_compress": ("c5", ("compress_kernel<128, 1, 32, false>",)),
+    "roofline_long_context_mask_bwd": ("c4", ("bwd_dq_kernel<128, 4>", "bwd_dkv_kernel<128, 4>")),
+    "roofline_mask": ("c2", ("mask_attn_kernel<128, 2, 32, false>",)),
+    "roofline_mask_bwd": ("c2", ("bwd_dq_kernel<128, 2>", "bwd_dkv_kernel<128, 2>", "bwd_reduce_kernel<128>")),
+    "roofline_decode": ("c3", ("decode_split_kernel<128, 16, false, false>",)),
+    "roofline_decode_layers": ("c3x{L}", ("decode_split_kernel<128, 16, true, false>",)),
+    "roofline_prefill": ("c3", ("prefill_kernel<128, 4, 64, 2, 4>",)),
+}
+
+
+def traffic_of(table, config, *kernels):
+    """Sum of the profile's traffic over the kernels of one call on one configuration ("c4", "c3x32": 32 layers per
+    launch), or None if one of them is missing."""
+    keys = ["%s @%s" % (k, config) for k in kernels]
+    if not all(k in table for k in keys):
         return None
-    return sum(table[k] for k in kernels)
+    return sum(table[k] for k in keys)
 
 
 def parse():
@@ -282,8 +302,8 @@ def main():
     dec_gbs = dec_bytes / (dec_ms * 1e-3) / 1e9
     comp_bytes = wl.compress_bytes(c5.B, c5.H, c5.d, c5.t, c5.c, c5.dtype)
     comp_flops = wl.compress_useful_flops(c5.B, c5.H, c5.d, c5.t, c5.c)
-    KMASK4, KDEC5, KCOMB5, KCOMP5 = ("mask_attn_kernel<128, 4, 64, true>", "decode_split_kernel<128, 4, false, false>",
-                                     "decode_combine_kernel<128, false>", "compress_kernel<128, 1, 32, false>")
+    (KDEC5, KCOMB5), (KMASK4,), (KCOMP5,) = (ROOFLINE_KERNELS[k][1] for k in ("roofline", "roofline_long_context_mask",
+                                                                                 "roofline_high_ratio_compress"))
 
     result = {
         "metric": "LoMA-mask attn useful TFLOP/s + decode GB/s (frac of MI355X roofline)",
@@ -305,23 +325,26 @@ def main():
         # the kernel the step spends its time in: the split-K decode kernel (HBM-bound); the figure includes the
         # tiny combine kernel that follows every launch of it
         "roofline": {"kernel": KDEC5, "bound": "hbm", "achieved": dec_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": dec_gbs / HBM_PEAK_GBS, "traffic": traffic_of(traffic, KDEC5, KCOMB5)},
+                     "frac": dec_gbs / HBM_PEAK_GBS, "traffic": traffic_of(traffic, "c5", KDEC5, KCOMB5)},
         "roofline_long_context_mask": {"kernel": KMASK4, "bound": "mfma", "achieved": mask_tf, "peak": MFMA_BF16_PEAK_TF,
                                        "unit": "TFLOP/s", "frac": mask_tf / MFMA_BF16_PEAK_TF,
-                                       "traffic": traffic_of(traffic, KMASK4)},
+                                       "traffic": traffic_of(traffic, "c4", KMASK4)},
         "roofline_high_ratio_compress": {"kernel": KCOMP5, "bound": "hbm", "achieved": comp_bytes / (comp_ms * 1e-3) / 1e9,
                                          "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                          "frac": comp_bytes / (comp_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                         "traffic": traffic_of(traffic, KCOMP5)},
+                                         "traffic": traffic_of(traffic, "c5", KCOMP5)},
     }
 
-    def roof_hbm(kernels, gbs):
+    def roof_hbm(which, gbs, **fmt):
+        config, kernels = ROOFLINE_KERNELS[which]
+        config = config.format(**fmt)
         return {"kernel": " + ".join(kernels), "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": gbs / HBM_PEAK_GBS, "traffic": traffic_of(traffic, *kernels)}
+                "frac": gbs / HBM_PEAK_GBS, "traffic": traffic_of(traffic, config, *kernels)}
 
-    def roof_mfma(kernels, tf):
+    def roof_mfma(which, tf):
+        config, kernels = ROOFLINE_KERNELS[which]
         return {"kernel": " + ".join(kernels), "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TF, "unit": "TFLOP/s",
-                "frac": tf / MFMA_BF16_PEAK_TF, "traffic": traffic_of(traffic, *kernels)}
+                "frac": tf / MFMA_BF16_PEAK_TF, "traffic": traffic_of(traffic, config, *kernels)}
 
     def time_backward(cfg, sets):
         """sets: (q, k, v, out) tuples; forward once per set for out and lse, then the gradients in rotation."""
@@ -349,7 +372,7 @@ def main():
         # ---- config 4 gradients (one set: 2.4 GB of tensors per call) -----------------------------------------------
         bw = time_backward(c4, sets4[:1])
         result["long_context_mask_bwd"] = bw
-        result["roofline_long_context_mask_bwd"] = roof_mfma(("bwd_dq_kernel<128, 4>", "bwd_dkv_kernel<128, 4>"), bw["useful_tflops"])
+        result["roofline_long_context_mask_bwd"] = roof_mfma("roofline_long_context_mask_bwd", bw["useful_tflops"])
         del sets4
         torch.cuda.empty_cache()
 
@@ -362,11 +385,10 @@ def main():
                           "frac_of_mfma_peak": fl2 / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, "us_per_call": ms * 1e3,
                           "algorithmic_GBps": by2 / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": by2 / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                           "useful_flops": fl2, "bytes": by2, "tensor_sets": 8}
-        result["roofline_mask"] = roof_hbm(("mask_attn_kernel<128, 2, 32, false>",), by2 / (ms * 1e-3) / 1e9)
+        result["roofline_mask"] = roof_hbm("roofline_mask", by2 / (ms * 1e-3) / 1e9)
         b2 = time_backward(c2, sets2[:3])
         result["mask_bwd"] = b2
-        result["roofline_mask_bwd"] = roof_hbm(("bwd_dq_kernel<128, 2>", "bwd_dkv_kernel<128, 2>", "bwd_reduce_kernel<128>"),
-                                               b2["algorithmic_GBps"])
+        result["roofline_mask_bwd"] = roof_hbm("roofline_mask_bwd", b2["algorithmic_GBps"])
         del sets2
         torch.cuda.empty_cache()
 
@@ -395,7 +417,7 @@ def main():
         result["decode"] = {"workload": f"{c3.name}: {L} layer caches, one launch per layer and token", "value": db3 / (dms * 1e-3) / 1e9,
                             "unit": "GB/s (algorithmic)", "frac_of_hbm_peak": db3 / (dms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                             "us_per_call": dms * 1e3, "bytes_per_call": db3, "keys": f"{nkeys3}+1..{nkeys3}+{c3.R}"}
-        result["roofline_decode"] = roof_hbm(("decode_split_kernel<128, 16, false, false>",), db3 / (dms * 1e-3) / 1e9)
+        result["roofline_decode"] = roof_hbm("roofline_decode", db3 / (dms * 1e-3) / 1e9)
         tabs = {n: loma.pointer_table([g[n] for g in lay]) for n in ("q", "k_new", "v_new", "k_mem", "v_mem", "k_read", "v_read", "out")}
 
         def dec_layers(i):
@@ -407,7 +429,7 @@ def main():
                                    "value": L * db3 / (lms * 1e-3) / 1e9, "unit": "GB/s (algorithmic)",
                                    "frac_of_hbm_peak": L * db3 / (lms * 1e-3) / 1e9 / HBM_PEAK_GBS, "us_per_token": lms * 1e3,
                                    "us_per_token_layer_by_layer": L * dms * 1e3, "speedup_vs_layer_by_layer": L * dms / lms}
-        result["roofline_decode_layers"] = roof_hbm(("decode_split_kernel<128, 16, true, false>",), L * db3 / (lms * 1e-3) / 1e9)
+        result["roofline_decode_layers"] = roof_hbm("roofline_decode_layers", L * db3 / (lms * 1e-3) / 1e9, L=L)
         cms = time_median(lambda i: loma.loma_compress_step(lay[i % L]["q_m"], lay[i % L]["k_m"], lay[i % L]["v_m"], lay[i % L]["k_read"],
                                                             lay[i % L]["v_read"], lay[i % L]["k_mem"], lay[i % L]["v_mem"], c3.t, c3.c,
                                                             c3.prior_chunks, c3.scale, out=lay[i % L]["out_m"]), L, NS)
@@ -427,7 +449,7 @@ def main():
                              "us_per_call": pms * 1e3, "algorithmic_GBps": pbytes / (pms * 1e-3) / 1e9,
                              "frac_of_hbm_peak": pbytes / (pms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                              "useful_tflops": pflops / (pms * 1e-3) / 1e12, "vs_token_by_token": c3.R * dms / pms}
-        result["roofline_prefill"] = roof_hbm(("prefill_kernel<128, 4, 64, 2, 4>",), pbytes / (pms * 1e-3) / 1e9)
+        result["roofline_prefill"] = roof_hbm("roofline_prefill", pbytes / (pms * 1e-3) / 1e9)
         del lay, pre, tabs
         torch.cuda.empty_cache()
 
