@@ -100,35 +100,6 @@ def parse():
     return ap.parse_args()
 
 
-class Pool:
-    """Seeded unit-normal bf16 values drawn once on the host; device tensors are tiled from it at offsets a host
-    generator picks.  (No GPU random-number kernel: those fault under rocprofv3 counter collection on this stack.)"""
-
-    def __init__(self, wl, seed, n=1 << 23):
-        import numpy as np
-        import torch
-        rng = np.random.default_rng(seed)
-        bits = wl.f32_to_bf16_bits(rng.standard_normal(n, dtype=np.float32))
-        self.torch = torch
-        self.unit = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
-        self.half = (self.unit.float() * 0.5).to(torch.bfloat16)      # exact: a power of two
-        self.rng = rng
-        self.n = n
-
-    def tensor(self, shape, scale=1.0):
-        torch = self.torch
-        src = self.unit if scale == 1.0 else self.half
-        assert scale in (1.0, 0.5)
-        out = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
-        flat = out.view(-1)
-        piece = self.n // 2
-        for i in range(0, flat.numel(), piece):
-            m = min(piece, flat.numel() - i)
-            off = int(self.rng.integers(0, self.n - m + 1))
-            flat[i:i + m] = src[off:off + m]
-        return out
-
-
 def time_median(fn, calls, samples=20, warmup=5):
     """Median over `samples` samples of the milliseconds per call; a sample is `calls` back-to-back calls fn(i)
     bracketed by HIP events on the current stream.  `warmup` untimed samples come first."""
@@ -239,7 +210,7 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read_per_copy": 1 << 30, "bytes_written_per_copy": 1 << 30, "copies": 3}}))
         return
-    pool = Pool(wl, wl.SEED_BASE)
+    pool = wl.TiledPool(wl.SEED_BASE)
     traffic = profile_traffic()
     K, NS = args.steps, args.samples
     c2, c3, c4, c5 = wl.CONFIGS[1], wl.CONFIGS[2], wl.CONFIGS[3], wl.CONFIGS[4]

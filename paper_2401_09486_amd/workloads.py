@@ -218,29 +218,52 @@ def compress_useful_flops(B, H, d, t, c) -> int:
     return 4 * d * t * (t * c + t) * B * H
 
 
-# ---- device-side generation for the large generation configurations -------------------------
-def gen_initial_state_device(cfg: GenConfig, device="cuda"):
-    """Same layout as gen_initial_state, drawn on the GPU (torch generator, seed = cfg.seed):
-    the 9 GB caches of the largest configuration are not worth a trip through host memory.
-    Returns torch tensors in the storage dtype."""
-    import torch
-    g = torch.Generator(device=device)
-    g.manual_seed(cfg.seed)
-    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
-    Lm = cfg.prior_chunks * cfg.t
+# ---- device-side tensors for the large configurations ---------------------------------------
+class TiledPool:
+    """Seeded unit-normal bf16 values drawn once on the host (numpy default_rng); device tensors are filled with
+    runs of the pool at offsets the same host generator picks.  Stands in for fresh draws where a tensor set is too
+    large for a trip through host memory (the 9 GB caches of the largest generation configuration, the rotating
+    tensor sets of the benchmark); no GPU random-number kernel is involved.  Scales are powers of two (exact)."""
 
-    def draw(shape, scale):
-        out = torch.empty(shape, dtype=dt, device=device)
-        flat = out.view(shape[0] * shape[1], -1)
-        for i in range(flat.shape[0]):   # one (b,h) slab at a time keeps the fp32 temporary small
-            flat[i] = (torch.randn(flat.shape[1], generator=g, device=device, dtype=torch.float32) * scale).to(dt)
+    def __init__(self, seed, n=1 << 23, device="cuda"):
+        import torch
+        rng = np.random.default_rng(seed)
+        bits = f32_to_bf16_bits(rng.standard_normal(n, dtype=np.float32))
+        self.torch = torch
+        self.unit = torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+        self.scaled = {1.0: self.unit}
+        self.rng = rng
+        self.n = n
+        self.device = device
+
+    def tensor(self, shape, scale=1.0):
+        torch = self.torch
+        if scale not in self.scaled:
+            assert np.log2(scale) == int(np.log2(scale)), "scales are powers of two"
+            self.scaled[scale] = (self.unit.float() * scale).to(torch.bfloat16)
+        src = self.scaled[scale]
+        out = torch.empty(shape, dtype=torch.bfloat16, device=self.device)
+        flat = out.view(-1)
+        piece = self.n // 2
+        for i in range(0, flat.numel(), piece):
+            m = min(piece, flat.numel() - i)
+            off = int(self.rng.integers(0, self.n - m + 1))
+            flat[i:i + m] = src[off:off + m]
         return out
 
+
+def gen_initial_state_device(cfg: GenConfig, device="cuda", pool=None):
+    """Same layout as gen_initial_state, filled on the GPU from a TiledPool seeded with cfg.seed (bf16 only).
+    Returns torch tensors in the storage dtype."""
+    import torch
+    assert cfg.dtype == "bf16"
+    pool = pool or TiledPool(cfg.seed, device=device)
+    Lm = cfg.prior_chunks * cfg.t
     state = {}
     for name in ("k_mem", "v_mem"):
-        buf = torch.zeros((cfg.B, cfg.H, cfg.mem_capacity, cfg.d), dtype=dt, device=device)
-        buf[:, :, :Lm] = draw((cfg.B, cfg.H, Lm, cfg.d), cfg.kv_scale)
+        buf = torch.zeros((cfg.B, cfg.H, cfg.mem_capacity, cfg.d), dtype=torch.bfloat16, device=device)
+        buf[:, :, :Lm] = pool.tensor((cfg.B, cfg.H, Lm, cfg.d), cfg.kv_scale)
         state[name] = buf
     for name in ("k_read", "v_read"):
-        state[name] = draw((cfg.B, cfg.H, cfg.R, cfg.d), cfg.kv_scale)
+        state[name] = pool.tensor((cfg.B, cfg.H, cfg.R, cfg.d), cfg.kv_scale)
     return state

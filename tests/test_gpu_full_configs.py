@@ -78,11 +78,13 @@ def test_prefill_config3_shape_full(loma, c_oracle):
 
 
 def test_generation_config5_full(loma, c_oracle):
-    """B64 H32, 8192 memory KVs + 256-token reading zone, 128 steps; the caches are drawn on the
-    device (9 GB); the oracle follows 24 sampled (b,h) pairs through every step."""
+    """B64 H32, 8192 memory KVs + 256-token reading zone, 128 steps; the 9 GB caches and the step inputs are filled
+    on the device from a host-drawn numpy pool (workloads.TiledPool); the oracle follows 24 sampled (b,h) pairs
+    through every step on the same bits."""
     cfg = wl.CONFIGS[4]
     print(f"[case] full-size generation {cfg}", flush=True)
-    st = wl.gen_initial_state_device(cfg)
+    pool = wl.TiledPool(cfg.seed)
+    st = wl.gen_initial_state_device(cfg, pool=pool)
     nbh = cfg.B * cfg.H
     sel = np.array(sorted(set(np.linspace(0, nbh - 1, 24).astype(int))), dtype=np.int64)
     tsel = torch.from_numpy(sel).cuda()
@@ -93,11 +95,9 @@ def test_generation_config5_full(loma, c_oracle):
 
     orc = c_oracle.GenerationCache(pick(st["k_mem"]), pick(st["v_mem"]), cfg.prior_chunks,
                                    pick(st["k_read"]), pick(st["v_read"]), cfg.R, cfg.t, cfg.c, cfg.scale)
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(cfg.seed + 1000)
 
     def draw(L, scale):
-        return (torch.randn((cfg.B, cfg.H, L, cfg.d), generator=gen, device="cuda") * scale).to(torch.bfloat16)
+        return pool.tensor((cfg.B, cfg.H, L, cfg.d), scale)
 
     ws = torch.empty(max(loma.loma_decode_workspace_bytes(cfg.B, cfg.H, cfg.d, cfg.t, cfg.c, cfg.prior_chunks + 1), 16),
                      dtype=torch.uint8, device="cuda")
