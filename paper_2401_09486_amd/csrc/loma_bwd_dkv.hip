@@ -18,7 +18,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_dkv_kernel(BwdParams P) {
     const int nMK = (nmk + P.bm - 1) / P.bm;          // blocks of memory keys
     const int nRB = (P.R + P.bm - 1) / P.bm;          // reading-zone key blocks per chunk
     int bh, u;
-    split_block(blockIdx.x, P.nbh, nMK * P.split + P.n * nRB, bh, u);
+    split_block(blockIdx.x, P.nbh, nMK * P.split + P.n * nRB, nMK * P.split, bh, u);
     BwdJob J;
     J.rep = 0; J.t = P.t; J.magic_t = magic_of(P.t); J.z0 = J.z1 = 0; J.cb = 0;
     J.part_k = J.part_v = nullptr;

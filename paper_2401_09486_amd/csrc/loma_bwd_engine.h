@@ -307,29 +307,45 @@ __device__ __forceinline__ void store_staged_rep(const float* Of, const BwdTenso
                                                  float scale, float sc, int lane) {
     using C = BCfg<D>;
     const int rl = lane / C::CPR, pc = lane % C::CPR;
+    // Four row groups at a time: all their loads first, then the arithmetic and the stores.  (Written as one loop
+    // the stores of a group, which may alias the next group's loads for all the compiler knows, keep every group's
+    // loads behind them: eight dependent memory round trips per block.)
+    constexpr int NG = 32 / C::RPI, GB = NG < 4 ? NG : 4;
 #pragma unroll
-    for (int i = 0; i < 32 / C::RPI; ++i) {
-        const int r = i * C::RPI + rl;
-        const bool live = row0 + r < J.orows;
-        const long row = list_row(J.own, J.ooff + min(row0 + r, J.orows - 1));   // rows past the block replay its last row
-        const long at = row * D + pc * 8;
-        const u32x4 qq = *reinterpret_cast<const u32x4*>(T.q + at);
-        const u32x4 kk = *reinterpret_cast<const u32x4*>(T.k + at);
-        const u32x4 vv = *reinterpret_cast<const u32x4*>(T.v + at);
-        const u32x4 gg = *reinterpret_cast<const u32x4*>(T.dout + at);
-        const u32x4 oo = *reinterpret_cast<const u32x4*>(T.out + at);
-        const float s = row_sum<C::CPR>(dot8(qq, kk));
-        const float dw = row_sum<C::CPR>(dot8(gg, vv));
-        const float delta = row_sum<C::CPR>(dot8(gg, oo));   // (formed again here: other lanes hold the prologue's copy)
-        const float wgt = __builtin_amdgcn_exp2f(fmaf(s, sc, -T.lse[row] * LOG2E));
-        const float da = wgt * (dw - delta);
-        const float4 a = *reinterpret_cast<const float4*>(Of + r * C::FSTR + pc * 8);
-        const float4 b = *reinterpret_cast<const float4*>(Of + r * C::FSTR + pc * 8 + 4);
-        const float4 z = {0.f, 0.f, 0.f, 0.f};
-        if (live) {
-            *reinterpret_cast<uint4*>(T.dq + at) = axpb8(scale * da, kk, a, b);
-            *reinterpret_cast<uint4*>(T.dk + at) = axpb8(scale * da, qq, z, z);
-            *reinterpret_cast<uint4*>(T.dv + at) = axpb8(wgt, gg, z, z);
+    for (int i0 = 0; i0 < NG; i0 += GB) {
+        u32x4 qq[GB], kk[GB], vv[GB], gg[GB], oo[GB];
+        float ls[GB];
+        long at[GB];
+        bool live[GB];
+#pragma unroll
+        for (int b = 0; b < GB; ++b) {
+            const int r = (i0 + b) * C::RPI + rl;
+            live[b] = row0 + r < J.orows;
+            const long row = list_row(J.own, J.ooff + min(row0 + r, J.orows - 1));   // rows past the block replay its last row
+            at[b] = row * D + pc * 8;
+            qq[b] = *reinterpret_cast<const u32x4*>(T.q + at[b]);
+            kk[b] = *reinterpret_cast<const u32x4*>(T.k + at[b]);
+            vv[b] = *reinterpret_cast<const u32x4*>(T.v + at[b]);
+            gg[b] = *reinterpret_cast<const u32x4*>(T.dout + at[b]);
+            oo[b] = *reinterpret_cast<const u32x4*>(T.out + at[b]);
+            ls[b] = T.lse[row];
+        }
+#pragma unroll
+        for (int b = 0; b < GB; ++b) {
+            const int r = (i0 + b) * C::RPI + rl;
+            const float s = row_sum<C::CPR>(dot8(qq[b], kk[b]));
+            const float dw = row_sum<C::CPR>(dot8(gg[b], vv[b]));
+            const float delta = row_sum<C::CPR>(dot8(gg[b], oo[b]));   // (formed again here: other lanes hold the prologue's copy)
+            const float wgt = __builtin_amdgcn_exp2f(fmaf(s, sc, -ls[b] * LOG2E));
+            const float da = wgt * (dw - delta);
+            const float4 a = *reinterpret_cast<const float4*>(Of + r * C::FSTR + pc * 8);
+            const float4 c = *reinterpret_cast<const float4*>(Of + r * C::FSTR + pc * 8 + 4);
+            const float4 z = {0.f, 0.f, 0.f, 0.f};
+            if (live[b]) {
+                *reinterpret_cast<uint4*>(T.dq + at[b]) = axpb8(scale * da, kk[b], a, c);
+                *reinterpret_cast<uint4*>(T.dk + at[b]) = axpb8(scale * da, qq[b], z, z);
+                *reinterpret_cast<uint4*>(T.dv + at[b]) = axpb8(wgt, gg[b], z, z);
+            }
         }
     }
 }
@@ -815,13 +831,23 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
     }
 }
 
-__device__ __forceinline__ void split_block(long long id, int nbh, int jobs_per_bh, int& bh, int& u) {
-    // (b,h) pairs are dealt to the 8 XCDs (workgroup id % 8) so that one pair's rows stay in one L2
+__device__ __forceinline__ void split_block(long long id, int nbh, int jobs_per_bh, int nlong, int& bh, int& u) {
+    // (b,h) pairs are dealt to the 8 XCDs (workgroup id % 8) so that one pair's rows stay in one L2.  Jobs
+    // 0 .. nlong-1 of a pair are its long ones, longest first: an XCD starts with job 0 of each of its pairs, then
+    // job 1 of each, ... (workgroups are handed out in id order as slots come free, so this is longest-first list
+    // scheduling over the XCD's CUs), and only then walks the short jobs pair by pair.
     if (nbh % 8 == 0) {
-        const int xcd = (int)(id % 8);
+        const int xcd = (int)(id % 8), pairs = nbh / 8;
         const long long k = id / 8;
-        bh = xcd + 8 * (int)(k / jobs_per_bh);
-        u = (int)(k % jobs_per_bh);
+        if (k < (long long)pairs * nlong) {
+            bh = xcd + 8 * (int)(k % pairs);
+            u = (int)(k / pairs);
+        } else {
+            const long long k2 = k - (long long)pairs * nlong;
+            const int nshort = jobs_per_bh - nlong;
+            bh = xcd + 8 * (int)(k2 / nshort);
+            u = nlong + (int)(k2 % nshort);
+        }
     } else {
         bh = (int)(id % nbh);
         u = (int)(id / nbh);
