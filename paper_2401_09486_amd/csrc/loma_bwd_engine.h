@@ -834,8 +834,12 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
 __device__ __forceinline__ void split_block(long long id, int nbh, int jobs_per_bh, int nlong, int& bh, int& u) {
     // (b,h) pairs are dealt to the 8 XCDs (workgroup id % 8) so that one pair's rows stay in one L2.  Jobs
     // 0 .. nlong-1 of a pair are its long ones, longest first: an XCD starts with job 0 of each of its pairs, then
-    // job 1 of each, ... (workgroups are handed out in id order as slots come free, so this is longest-first list
-    // scheduling over the XCD's CUs), and only then walks the short jobs pair by pair.
+    // job 1 of each, ..., and only then walks the short jobs pair by pair.  Workgroups are handed out in id order as
+    // slots come free, so this is longest-first list scheduling over the XCD's CUs: the launch ends within a percent
+    // of the even split (simulated for the long-context shape; walking the pairs one after the other, long and short
+    // jobs together, started the last pair's longest job at three quarters of the launch and ended 30 % late).
+    // Measured alternative: the long jobs pair by pair (a pair's jobs, which stream the same rows, start together)
+    // moves 9 % fewer bytes at the same time at the long-context shape and is 10 % slower at the Llama-7B shape.
     if (nbh % 8 == 0) {
         const int xcd = (int)(id % 8), pairs = nbh / 8;
         const long long k = id / 8;
