@@ -350,20 +350,6 @@ __device__ __forceinline__ void store_staged_rep(const float* Of, const BwdTenso
     }
 }
 
-// v_exp_f32 and the bf16 packing AT THEIR PLACE in the instruction stream: the compiler orders volatile statements
-// among themselves and against the scheduling fences, so these two pin a score's arithmetic (which hangs between
-// them by its data dependences) to the slot of the pipelined loop it is written in.
-__device__ __forceinline__ float exp2_at(float x) {
-    float y;
-    asm volatile("v_exp_f32 %0, %1" : "=v"(y) : "v"(x));
-    return y;
-}
-__device__ __forceinline__ uint32_t pack_bf16_at(float a, float b) {
-    uint32_t r;
-    asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
-
 // S' / dP' MFMAs of the dK/dV pass: the owner rows' operand comes from the accumulation registers (constraint "a";
 // that is where the 64 registers of k and v live for the whole kernel, past a127), the result goes to ordinary
 // registers.  Opaque to the compiler's hazard bookkeeping: settle_scores() comes between the last of them and the

@@ -690,31 +690,14 @@ struct PipeCfg {
     static_assert(NSK >= 2 && NSK <= 4 && QP < NSK, "ring depth");
 };
 
-// Issue order of one pipeline step, as scheduling groups (sizes must be compile-time constants, hence the recursion
-// over slots; SLOT -1 is the leading group of operand reads).
-template <int D, bool HAVE_S, bool HAVE_PV, bool HAVE_P, int RA, int SLOT>
-__device__ __forceinline__ void pipe_issue_order() {
-    constexpr int KSTEPS = D / 16, NPV = 2 * (D / 32), NSLOT = 2 * KSTEPS, EPS = 16 / NSLOT;
-    constexpr int VALU = 0x2, MFMA = 0x8, DS_READ = 0x100;
-    if constexpr (SLOT < 0) {
-        __builtin_amdgcn_sched_group_barrier(DS_READ, RA * ((HAVE_S ? 1 : 0) + (HAVE_PV ? 2 : 0)), 0);
-    } else {
-        constexpr int j = SLOT >> 1;
-        constexpr bool is_s = (SLOT & 1) == 0;
-        // per score: multiply-add, exponential, sum; per pair of scores: the packing
-        if constexpr (HAVE_P) __builtin_amdgcn_sched_group_barrier(VALU, 3 * EPS + (EPS == 1 ? (SLOT & 1) : EPS / 2), 0);
-        if constexpr (is_s ? HAVE_S : HAVE_PV) {
-            __builtin_amdgcn_sched_group_barrier(MFMA, 1, 0);
-            if constexpr (is_s && j + RA < KSTEPS) __builtin_amdgcn_sched_group_barrier(DS_READ, 1, 0);
-            if constexpr (!is_s && j + RA < NPV) __builtin_amdgcn_sched_group_barrier(DS_READ, 2, 0);
-        }
-    }
-    if constexpr (SLOT + 1 < NSLOT) pipe_issue_order<D, HAVE_S, HAVE_PV, HAVE_P, RA, SLOT + 1>();
-}
-
 // One step of the pipeline.  Matrix pipe: Sn = K rows of half h+1 times Q (HAVE_S), O += V^T of half h-1 times
 // Pp (HAVE_PV), alternating; vector ALU, between them: probabilities Pc of the scores Sc of half h (HAVE_P).
 // Kh / Vh point at the first of the 32 rows of the respective half inside its ring stage.
+// The step is cut into slots of one MFMA, the slot's share of the scores and the operand read that runs RA products
+// ahead, with a scheduling fence after every slot; the exponentials, the packing and the MFMAs are volatile
+// statements, which the compiler keeps in source order among themselves and against the fences (written as plain
+// arithmetic it sank every exponential behind the MFMAs; given as scheduling groups the order held but ran 2-3 %
+// slower than this).  Nothing reads an MFMA's result before the next step.
 template <int D, bool HAVE_S, bool HAVE_PV, bool HAVE_P = true>
 __device__ __forceinline__ float pipe_half(const bf16_t* Kh, const bf16_t* Vh, const int (&koff)[D / 16], const int (&voff)[D / 32],
                                            const bf16x8 (&qreg)[D / 16], const f32x16& Sc, f32x16& Sn,
@@ -738,37 +721,35 @@ __device__ __forceinline__ float pipe_half(const bf16_t* Kh, const bf16_t* Vh, c
         if constexpr (HAVE_S) ka[i] = read_k(i);
         if constexpr (HAVE_PV) va[i] = read_v(i);
     }
+    __builtin_amdgcn_sched_barrier(0);
     uint32_t pw[8];
     float pe[2];
     float ps = 0.f;
-#pragma unroll
-    for (int slot = 0; slot < NSLOT; ++slot) {
-        const int j = slot >> 1;
+    static_for<0, NSLOT>([&](auto sc_) {
+        constexpr int slot = sc_.value, j = slot >> 1;
         if constexpr (HAVE_P) {
-#pragma unroll
-            for (int e = slot * EPS; e < (slot + 1) * EPS; ++e) {
-                pe[e & 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(Sc[e], sc, -mc));
-                ps += pe[e & 1];
-                if (e & 1) pw[e >> 1] = pack_bf16(pe[0], pe[1]);
-            }
+            static_for<slot * EPS, (slot + 1) * EPS>([&](auto ec) {
+                constexpr int e = ec.value;
+                const float y = exp2_at(__builtin_fmaf(Sc[e], sc, -mc));
+                pe[e & 1] = y;
+                ps += y;
+                if constexpr (e & 1) pw[e >> 1] = pack_bf16_at(pe[0], pe[1]);
+            });
         }
-        if ((slot & 1) == 0) {
+        if constexpr ((slot & 1) == 0) {
             if constexpr (HAVE_S) {
-                Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[j], qreg[j], j == 0 ? zero16 : Sn, 0, 0, 0);
-                if (j + RA < KSTEPS) ka[j + RA] = read_k(j + RA);
+                if constexpr (j == 0) mfma_first_at(Sn, ka[0], qreg[0]);
+                else mfma_at(Sn, ka[j], qreg[j]);
+                if constexpr (j + RA < KSTEPS) ka[j + RA] = read_k(j + RA);
             }
         } else {
             if constexpr (HAVE_PV) {
-                O[j % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[j], Pp[j / DT], O[j % DT], 0, 0, 0);
-                if (j + RA < NPV) va[j + RA] = read_v(j + RA);
+                mfma_at(O[j % DT], va[j], Pp[j / DT]);
+                if constexpr (j + RA < NPV) va[j + RA] = read_v(j + RA);
             }
         }
-    }
-    // The order the instructions of this step are issued in (the code above only says what is computed: pure
-    // arithmetic is moved around freely before scheduling): the first operand reads, then per slot the slot's share
-    // of the vector work, its MFMA, and the operand read that runs RA products ahead.
-    pipe_issue_order<D, HAVE_S, HAVE_PV, HAVE_P, RA, -1>();
-    __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_sched_barrier(0);
+    });
     if constexpr (!HAVE_P) return 0.f;
     Pc[0] = __builtin_bit_cast(bf16x8, uint4{pw[0], pw[1], pw[2], pw[3]});
     Pc[1] = __builtin_bit_cast(bf16x8, uint4{pw[4], pw[5], pw[6], pw[7]});
@@ -939,6 +920,9 @@ __device__ __forceinline__ void flash_job_pipe(const FlashJob& J, float sc, bf16
             }
         }
     }
+    // the pipelined loop's MFMAs are invisible to the compiler's hazard bookkeeping: let the last of them write its
+    // accumulator before ordinary code reads the scores or the output accumulators
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
     if (redo_half >= 0) {
         // second half of tile `redo_half` with a moving reference, from its scores (every key of a full tile is
         // visible: nothing to mask; its K rows may be gone by now, its V rows stay until tile redo_half + 3 is requested)

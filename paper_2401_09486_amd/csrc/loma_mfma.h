@@ -100,6 +100,30 @@ __device__ __forceinline__ s16x4 lds_read_tr(const bf16_t* p) {
         (__attribute__((address_space(3))) s16x4*)(const_cast<bf16_t*>(p)));
 }
 
+// ---- instructions pinned to their place in the instruction stream --------------------------------------------
+// v_exp_f32 and the bf16 packing AT THEIR PLACE in the instruction stream: the compiler orders volatile statements
+// among themselves and against the scheduling fences, so these two pin a score's arithmetic (which hangs between
+// them by its data dependences) to the slot of the pipelined loop it is written in.
+__device__ __forceinline__ float exp2_at(float x) {
+    float y;
+    asm volatile("v_exp_f32 %0, %1" : "=v"(y) : "v"(x));
+    return y;
+}
+__device__ __forceinline__ uint32_t pack_bf16_at(float a, float b) {
+    uint32_t r;
+    asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// MFMA with its accumulator in ordinary registers, as a volatile statement (same ordering guarantee).  Opaque to
+// the compiler's hazard bookkeeping: the result is read by other code only many instructions later.
+__device__ __forceinline__ void mfma_at(f32x16& acc, bf16x8 a, bf16x8 b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_first_at(f32x16& acc, bf16x8 a, bf16x8 b) {   // accumulator starts at zero
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+}
+
 // ---- accumulators that live in the accumulation registers a0..a127 BY NAME ------------------------------------
 // For kernels whose MFMA accumulators do not fit the 256 ordinary registers of a lane next to everything else
 // (as C++ values the compiler copies them between the register files on every tile).  Every statement names all
