@@ -11,18 +11,17 @@ namespace {
 // With P.split == 2 every block of memory keys is worked on by two workgroups: the first takes the block's own
 // memory and repetition rows and the reading rows of the nearer later chunks, the second the reading rows of
 // the farther ones (about half the rows each); both leave fp32 partial sums that bwd_reduce_kernel adds.
-template <int D, int NW>
-__global__ __launch_bounds__(64 * NW) void bwd_dkv_kernel(BwdParams P) {
-    extern __shared__ __align__(16) bf16_t smem[];
+// the job of workgroup `id` of the dK/dV pass and the (b,h) pair it belongs to
+template <int D>
+__device__ __forceinline__ int dkv_job_of(const BwdParams& P, long long id, BwdJob& J) {
     const int nmk = P.n * P.t;
     const int nMK = (nmk + P.bm - 1) / P.bm;          // blocks of memory keys
     const int nRB = (P.R + P.bm - 1) / P.bm;          // reading-zone key blocks per chunk
     int bh, u;
-    split_block(blockIdx.x, P.nbh, nMK * P.split + P.n * nRB, nMK * P.split, bh, u);
-    BwdJob J;
+    split_block(id, P.nbh, nMK * P.split + P.n * nRB, nMK * P.split, bh, u);
     J.rep = 0; J.t = P.t; J.magic_t = magic_of(P.t); J.z0 = J.z1 = 0; J.cb = 0;
     J.part_k = J.part_v = nullptr;
-    J.pipe0 = J.pipe1 = 0;
+    J.pipe0 = J.pipe1 = J.pipe_end = 0;
     if (u < nMK * P.split) {
         const int part = u % P.split;
         const int mk0 = (u / P.split) * P.bm;
@@ -45,9 +44,13 @@ __global__ __launch_bounds__(64 * NW) void bwd_dkv_kernel(BwdParams P) {
         J.z0 = y_first + a_hi; J.z1 = y_first;
         J.str.base0 = (y_first + a_hi) * P.s; J.str.n0 = (a_hi - a_lo) * P.R;
         J.str.slab0 = P.R; J.str.stride0 = -P.s; J.str.magic0 = magic_of(P.R);
-        if (P.R % 32 == 0) J.pipe1 = min(a_hi - a_lo, max(0, J.z0 - y_last)) * (P.R / 32);   // chunks past the block's last one
         J.str.base1 = y_first * P.s + P.R; J.str.n1 = part == 0 ? own_rows : 0;
         J.str.slab1 = P.s - P.R; J.str.stride1 = P.s; J.str.magic1 = magic_of(P.s - P.R);
+        if (P.R % 32 == 0) {
+            J.pipe1 = min(a_hi - a_lo, max(0, J.z0 - y_last)) * (P.R / 32);   // chunks past the block's last one
+            // whole tiles of one chunk: the reading rows, and the memory and repetition rows too when their slabs are tiled
+            J.pipe_end = J.str.n0 / 32 + ((P.s - P.R) % 32 == 0 ? J.str.n1 / 32 : 0);
+        }
     } else {
         u -= nMK * P.split;
         const int y = u / nRB, o0 = (u % nRB) * P.bm;
@@ -56,8 +59,18 @@ __global__ __launch_bounds__(64 * NW) void bwd_dkv_kernel(BwdParams P) {
         J.own = owner_range(y * P.s + o0);
         J.str = one_range(y * P.s + o0, P.R + P.t - o0);
         J.pipe0 = (J.orows + 30) / 32; J.pipe1 = (P.R + P.t - o0) / 32;   // rows from the block's last one on, whole tiles
+        J.pipe_end = J.pipe1;
+        J.pipe0 = min(J.pipe0, J.pipe1);
     }
     J.nstr = J.str.n0 + J.str.n1;
+    return bh;
+}
+
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void bwd_dkv_kernel(BwdParams P) {
+    extern __shared__ __align__(16) bf16_t smem[];
+    BwdJob J;
+    const int bh = dkv_job_of<D>(P, blockIdx.x, J);
     const BwdTensors T = at_sequence(P.T, (long)bh * P.n * P.s, D);
     bwd_job<D, NW, PASS_DKV>(J, T, P.scale, P.sc, smem);
 }

@@ -15,7 +15,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(BwdParams P) {
     J.ooff = 0; J.orows = mj.rows;
     J.vis = VIS_CAUSAL; J.cb = NO_CAUSAL; J.t = P.t; J.z0 = J.z1 = 0; J.magic_t = 0; J.rep = 0;
     J.part_k = J.part_v = nullptr;
-    J.pipe0 = J.pipe1 = 0;
+    J.pipe0 = J.pipe1 = J.pipe_end = 0;
     if (mj.zone == ZONE_READ) {
         J.own = owner_range(chunk + mj.o0);
         J.str = one_range(chunk, mj.o0 + mj.rows);

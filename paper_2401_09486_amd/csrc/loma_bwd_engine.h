@@ -116,6 +116,7 @@ struct BwdJob {
     int t, z0, z1;
     unsigned magic_t;
     int pipe0, pipe1;   // dK/dV pass: tiles [pipe0, pipe1) of the stream hold only visible pairs, whichever the owner row
+    int pipe_end;       // ... and tiles [0, pipe_end) are whole tiles of 32 consecutive rows (pipe1 <= pipe_end)
     int rep;       // dQ pass on repetition rows: add the rows' own-key terms when they leave
     // dK/dV pass of a block whose stream is shared out over several workgroups: fp32 partial sums, row
     // `ooff + r` of each (nullptr: the block is whole and writes dk, dv itself)
@@ -370,14 +371,18 @@ __device__ __forceinline__ void settle_scores() { asm volatile("s_nop 15\n\ts_no
 // LDS reads of a slot's operands two slots ahead of it.  A scheduling fence ends every slot: the matrix pipe
 // runs under the vector arithmetic of ONE instruction stream (one wave per SIMD is all the registers allow).
 // stB is the stage that holds B's tile (its rows' -lse log2(e) and delta, dK/dV pass).  pk[0] = P, pk[1] = dS,
-// element pairs in accumulator order.
-template <int D, int PASS, bool DO_A, bool DO_B, bool DO_C>
+// element pairs in accumulator order.  MASKED: B's tile is not fully visible; `thr` says, per lane, from which of
+// the tile's rows on the lane's owner row interacts with them (P and dS of the others are zero, and so is what
+// their MFMAs add: a wave none of whose rows sees the tile multiplies zeros, where the tile-by-tile path would
+// wait at the barrier).
+template <int D, int PASS, bool DO_A, bool DO_B, bool DO_C, bool MASKED = false>
 __device__ __forceinline__ void pipe_step(const bf16_t* stA, const bf16_t* stB, const bf16_t* stC,
                                           const int (&poff)[BCfg<D>::KSTEPS], const int (&toff)[2][BCfg<D>::DT],
                                           const bf16x8 (&xo)[BCfg<D>::KSTEPS], const bf16x8 (&yo)[BCfg<D>::KSTEPS],
                                           f32x16& Sn, f32x16& dPn, const f32x16& Sc, const f32x16& dPc,
                                           uint32_t (&pk_out)[2][8], const uint32_t (&pk_in)[2][8],
-                                          f32x16 (&accX)[BCfg<D>::DT], float sc, float nl_own, float dl_own, int g) {
+                                          f32x16 (&accX)[BCfg<D>::DT], float sc, float nl_own, float dl_own, int g,
+                                          int thr = 0) {
     using C = BCfg<D>;
     constexpr int NSLOT = 2 * C::KSTEPS, EPS = 16 / NSLOT, RA = 2;
     constexpr int CSTRIDE = PASS == PASS_DKV ? 1 : 2;          // a C MFMA every CSTRIDE slots (the odd ones in the dQ pass)
@@ -432,7 +437,10 @@ __device__ __forceinline__ void pipe_step(const bf16_t* stA, const bf16_t* stB, 
                     nl = nl4[e % 4];
                     dl = dl4[e % 4];
                 }
-                const float pr = exp2_at(fmaf(Sc[e], sc, nl));
+                float pr = exp2_at(fmaf(Sc[e], sc, nl));
+                // MASKED: element e is streamed row 8 (e / 4) + e % 4 (+ 4 g, folded into thr) of the tile; the lane's
+                // owner row interacts with it iff that number reaches the lane's threshold
+                if constexpr (MASKED) pr = (8 * (e / 4) + e % 4 >= thr) ? pr : 0.f;
                 const float ds = pr * (dPc[e] - dl);
                 if constexpr ((e & 1) == 0) {
                     p_even = pr;
@@ -730,67 +738,79 @@ __device__ __forceinline__ void bwd_job(const BwdJob& J, const BwdTensors& T, fl
         __syncthreads();
     };
 
-    // Tiles [p0, p1) hold only visible pairs for every wave: they go through the pipelined loop.
-    int p0 = 0, p1 = 0;
+    // Tiles [0, q1) are whole tiles of 32 consecutive rows: they go through the pipelined loop, those outside
+    // [p0, p1) -- where not every pair is visible -- with its masked steps.  The rest goes tile by tile.
+    int p0 = 0, p1 = 0, q1 = 0;
     if constexpr (PASS == PASS_DKV) {
-        p0 = J.pipe0; p1 = J.pipe1;
-        if (p1 - p0 < 3) p0 = p1 = 0;
+        p0 = J.pipe0; p1 = J.pipe1; q1 = J.pipe_end;
+        if (q1 < 3) p0 = p1 = q1 = 0;
     }
-    for (int kt = 0; kt < p0; ++kt) tile_by_tile(kt);
     if constexpr (PASS == PASS_DKV) {
-        if (p1 > p0) {
+        if (q1 > 0) {
             // In iteration i: S', dP' of tile i + 1 and the accumulation of tile i - 1 on the matrix pipe between the
             // exponentials of tile i.  Two sets of score registers and of packed operands take turns.
             f32x16 Sa, dPa, Sb, dPb;
             uint32_t pka[2][8], pkb[2][8];
             auto stage_of = [&](int kt) -> const bf16_t* { return smem + (kt % NS) * (C::STAGE_BYTES / 2); };
-            request_upto(p0 + AHEAD);
-            pipe_step<D, PASS, true, false, false>(stage_of(p0), nullptr, nullptr, poff, toff, xo, yo, Sa, dPa, Sa, dPa, pka, pkb,
+            // per-lane threshold of a tile that is not fully visible (see pipe_step)
+            auto threshold = [&](int i) -> int {
+                if (J.vis == VIS_FROM_ROW) return r_own - C::BN * i - 4 * g;
+                const TileInfo ti = tile_info(J.str, J.nstr, i * C::BN);
+                const bool vis = ti.in0 ? yk < J.z0 - ti.slab_index : yk == J.z1 + ti.slab_index;
+                return vis ? -1 : 64;
+            };
+            request_upto(AHEAD);
+            pipe_step<D, PASS, true, false, false>(stage_of(0), nullptr, nullptr, poff, toff, xo, yo, Sa, dPa, Sa, dPa, pka, pkb,
                                                   accX, sc, nl_own, dl_own, g);
-            wait_for(p0 + 1);
+            wait_for(1);
             __syncthreads();
-            // even steps (counted from p0) read (Sa, dPa) and the packed operands in pkb and write (Sb, dPb) and pka;
-            // odd steps the other way round.  The steady loop takes an odd and an even step per trip, in straight-line
-            // code, so that no register moves between the sets.
+            // even steps read (Sa, dPa) and the packed operands in pkb and write (Sb, dPb) and pka; odd steps the
+            // other way round.  The steady loop takes an odd and an even step per trip, in straight-line code, so
+            // that no register moves between the sets.
             auto sync_after = [&](int i) {
                 wait_for(i + 2);
                 __syncthreads();
             };
-#define LOMA_STEP(A_, B_, C_, I_, SN, DPN, SC, DPC, PKO, PKI)                                                                  \
-    pipe_step<D, PASS, A_, B_, C_>(stage_of((I_) + 1), stage_of(I_), stage_of((I_)-1), poff, toff, xo, yo, SN, DPN, SC, DPC, PKO, \
-                                   PKI, accX, sc, nl_own, dl_own, g)
-            int i = p0;
+#define LOMA_STEP_ARGS(I_, SN, DPN, SC, DPC, PKO, PKI) \
+    stage_of((I_) + 1), stage_of(I_), stage_of((I_)-1), poff, toff, xo, yo, SN, DPN, SC, DPC, PKO, PKI, accX, sc, nl_own, dl_own, g
+#define LOMA_STEP(A_, C_, I_, SN, DPN, SC, DPC, PKO, PKI)                                                             \
+    do {                                                                                                              \
+        if ((I_) >= p0 && (I_) < p1) pipe_step<D, PASS, A_, true, C_, false>(LOMA_STEP_ARGS(I_, SN, DPN, SC, DPC, PKO, PKI)); \
+        else pipe_step<D, PASS, A_, true, C_, true>(LOMA_STEP_ARGS(I_, SN, DPN, SC, DPC, PKO, PKI), threshold(I_));  \
+    } while (0)
+            int i = 0;
             request_upto(i + AHEAD);
-            LOMA_STEP(true, true, false, i, Sb, dPb, Sa, dPa, pka, pkb);
+            LOMA_STEP(true, false, i, Sb, dPb, Sa, dPa, pka, pkb);
             sync_after(i);
             ++i;
-            for (; i + 2 < p1; i += 2) {
+            for (; i + 2 < q1; i += 2) {
                 request_upto(i + AHEAD);
-                LOMA_STEP(true, true, true, i, Sa, dPa, Sb, dPb, pkb, pka);
+                LOMA_STEP(true, true, i, Sa, dPa, Sb, dPb, pkb, pka);
                 sync_after(i);
                 request_upto(i + 1 + AHEAD);
-                LOMA_STEP(true, true, true, i + 1, Sb, dPb, Sa, dPa, pka, pkb);
+                LOMA_STEP(true, true, i + 1, Sb, dPb, Sa, dPa, pka, pkb);
                 sync_after(i + 1);
             }
-            // one or two steps are left (p1 - p0 >= 3): the last one starts no new tile
-            if (i + 2 == p1) {
+            // one or two steps are left (q1 >= 3): the last one starts no new tile
+            if (i + 2 == q1) {
                 request_upto(i + AHEAD);
-                LOMA_STEP(true, true, true, i, Sa, dPa, Sb, dPb, pkb, pka);
+                LOMA_STEP(true, true, i, Sa, dPa, Sb, dPb, pkb, pka);
                 sync_after(i);
                 request_upto(i + 1 + AHEAD);
-                LOMA_STEP(false, true, true, i + 1, Sb, dPb, Sa, dPa, pka, pkb);
+                LOMA_STEP(false, true, i + 1, Sb, dPb, Sa, dPa, pka, pkb);
                 sync_after(i + 1);
-                LOMA_STEP(false, false, true, p1, Sa, dPa, Sb, dPb, pkb, pka);
+                pipe_step<D, PASS, false, false, true>(LOMA_STEP_ARGS(q1, Sa, dPa, Sb, dPb, pkb, pka));
             } else {
                 request_upto(i + AHEAD);
-                LOMA_STEP(false, true, true, i, Sa, dPa, Sb, dPb, pkb, pka);
+                LOMA_STEP(false, true, i, Sa, dPa, Sb, dPb, pkb, pka);
                 sync_after(i);
-                LOMA_STEP(false, false, true, p1, Sb, dPb, Sa, dPa, pka, pkb);
+                pipe_step<D, PASS, false, false, true>(LOMA_STEP_ARGS(q1, Sb, dPb, Sa, dPa, pka, pkb));
             }
 #undef LOMA_STEP
+#undef LOMA_STEP_ARGS
         }
     }
-    for (int kt = p1; kt < ntiles; ++kt) tile_by_tile(kt);
+    for (int kt = q1; kt < ntiles; ++kt) tile_by_tile(kt);
 
     // rows leave through the wave's own fp32 staging area (the tile stages are free: the loop ended on a barrier)
     float* Of = reinterpret_cast<float*>(smem) + w * (C::WAVE_STAGING_BYTES / 4);

@@ -116,12 +116,16 @@ __device__ __forceinline__ uint32_t pack_bf16_at(float a, float b) {
 }
 
 // MFMA with its accumulator in ordinary registers, as a volatile statement (same ordering guarantee).  Opaque to
-// the compiler's hazard bookkeeping: the result is read by other code only many instructions later.
+// the compiler's hazard bookkeeping in both directions.  After: the result is read by other code only many
+// instructions later (callers see to that).  Before: the compiler may have written an operand with a vector-ALU
+// instruction just ahead of the statement -- it copies a 16-register accumulator to other registers when it likes,
+// and did so right before an MFMA in a rarely run path -- and the matrix pipe must not read a register within two
+// wait states of such a write: the two idle cycles come with the instruction.
 __device__ __forceinline__ void mfma_at(f32x16& acc, bf16x8 a, bf16x8 b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void mfma_first_at(f32x16& acc, bf16x8 a, bf16x8 b) {   // accumulator starts at zero
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
 }
 
 // ---- accumulators that live in the accumulation registers a0..a127 BY NAME ------------------------------------
