@@ -150,7 +150,21 @@ def measured_peaks(samples):
     cms = time_median(lambda i: lib.loma_peaks_stream_copy(src.data_ptr(), dst.data_ptr(), n, 256 * 16, st), 1, samples)
     rms = time_median(lambda i: lib.loma_peaks_stream_read(src.data_ptr(), n, 256 * 16, sink.data_ptr(), st), 1, samples)
     tf = flops[0] / (ms * 1e-3) / 1e12
-    return {"mfma_loop_tflops": tf, "mfma_loop_frac_of_peak": tf / MFMA_BF16_PEAK_TF,
+    # what a vector instruction of the softmax occupies a SIMD for, next to the 32x32x16 MFMA (nanoseconds per
+    # instruction and SIMD; the clock differs between the loops, so no cycle counts)
+    lib.loma_peaks_valu_loop.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
+    lib.loma_peaks_valu_loop.restype = ctypes.c_double
+    simd_ns = {"v_mfma_f32_32x32x16_bf16_8_waves_per_simd": ms * 1e6 / (wgs * 4 / 1024 * iters * 8)}
+    for kind, name in ((0, "v_exp_f32"), (1, "v_fma_f32")):
+        for waves in (4, 8):
+            count = [0.0]
+
+            def run(i):
+                count[0] = lib.loma_peaks_valu_loop(kind, waves, 256, 8192, sink.data_ptr(), st)
+            vms = time_median(run, 1, samples)
+            assert count[0] > 0
+            simd_ns[f"{name}_{waves // 4}_wave{'s' if waves > 4 else ''}_per_simd"] = vms * 1e6 / (count[0] * (waves // 4))
+    return {"mfma_loop_tflops": tf, "ns_per_instruction_and_simd": simd_ns, "mfma_loop_frac_of_peak": tf / MFMA_BF16_PEAK_TF,
             "mfma_loop": f"v_mfma_f32_32x32x16_bf16, {wgs} workgroups x 4 waves x {iters * 8} instructions",
             "stream_copy_GBps": 2.0 * n / (cms * 1e-3) / 1e9, "stream_read_GBps": n / (rms * 1e-3) / 1e9,
             "stream_copy_frac_of_peak": 2.0 * n / (cms * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -1,6 +1,6 @@
-// Two measuring sticks for bench.py (built into their own small library, libloma_peaks.so; not part of the
-// product ABI): how fast this chip runs the matrix instruction the attention kernels are built on, and how fast
-// a plain streaming copy moves bytes.  The roofline fractions are quoted against the published peaks; these say
+// Measuring sticks for bench.py (built into their own small library, libloma_peaks.so; not part of the
+// product ABI): how fast this chip runs the matrix instruction the attention kernels are built on, how fast
+// a plain streaming copy moves bytes, and what a vector-ALU instruction of the softmax costs a SIMD.  The roofline fractions are quoted against the published peaks; these say
 // how much of those a kernel can reach at all on the box at hand.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -27,6 +27,28 @@ __global__ __launch_bounds__(256) void mfma_loop_kernel(int iters, float* sink) 
     for (int s = 0; s < 4; ++s)
         for (int i = 0; i < 16; ++i) x += acc[s][i];
     if (x == 12345.678f) sink[0] = x;   // keeps the loop alive without a store on the usual path
+}
+
+// Every wave issues `iters` x 16 vector-ALU instructions of one kind with no dependences between neighbours
+// (eight result registers in turn): KIND 0 = v_exp_f32 (the softmax's exponential, a transcendental), KIND 1 =
+// v_fma_f32 (stands for the plain fp32 instructions).  One workgroup per CU with 4 or 8 waves gives one or two
+// waves per SIMD: the time per instruction is what the instruction occupies the SIMD's vector ALU for (two waves)
+// or what a lone wave can issue (one wave).
+template <int KIND>
+__global__ __launch_bounds__(512) void valu_loop_kernel(int iters, float* sink) {
+    float x[8];
+    for (int i = 0; i < 8; ++i) x[i] = 0.001f * threadIdx.x + i;
+    const float a = 0.999f, b = 0.25f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            if (KIND == 0) asm volatile("v_exp_f32 %0, %1" : "=v"(x[s & 7]) : "v"(b));
+            else asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(x[s & 7]) : "v"(a), "v"(b));
+        }
+    }
+    float y = 0.f;
+    for (int i = 0; i < 8; ++i) y += x[i];
+    if (y == 12345.678f) sink[0] = y;
 }
 
 // Grid-stride copy with 16-byte accesses, four independent pieces per thread and trip: reads n16 * 16 bytes and
@@ -73,6 +95,16 @@ double loma_peaks_mfma_loop(int workgroups, int iters, float* sink, void* stream
     hipLaunchKernelGGL(mfma_loop_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream), iters, sink);
     if (hipGetLastError() != hipSuccess) return 0.0;
     return (double)workgroups * 4.0 * iters * 8.0 * (2.0 * 32 * 32 * 16);
+}
+
+// Enqueue the vector-ALU loop of `kind` (0: v_exp_f32, 1: v_fma_f32) on `workgroups` workgroups of `waves` waves (4 or 8).
+// Returns the instructions one wave issues (iters x 16), 0 on a bad argument or a failed launch.
+double loma_peaks_valu_loop(int kind, int waves, int workgroups, int iters, float* sink, void* stream) {
+    if ((kind != 0 && kind != 1) || (waves != 4 && waves != 8) || workgroups < 1 || iters < 1) return 0.0;
+    if (kind == 0) hipLaunchKernelGGL(valu_loop_kernel<0>, dim3(workgroups), dim3(64 * waves), 0, static_cast<hipStream_t>(stream), iters, sink);
+    else hipLaunchKernelGGL(valu_loop_kernel<1>, dim3(workgroups), dim3(64 * waves), 0, static_cast<hipStream_t>(stream), iters, sink);
+    if (hipGetLastError() != hipSuccess) return 0.0;
+    return (double)iters * 16.0;
 }
 
 // Enqueue a copy of `bytes` (multiple of 16) from src to dst; returns 0 on success.
