@@ -74,6 +74,7 @@ ROOFLINE_KERNELS = {
     "roofline_decode": ("c3", ("decode_split_kernel<128, 16, false, false>",)),
     "roofline_decode_layers": ("c3x{L}", ("decode_split_kernel<128, 16, true, false>",)),
     "roofline_prefill": ("c3", ("prefill_kernel<128, 4, 64, 2, 4>",)),
+    "roofline_decode_gqa": ("c5", ("decode_split_gqa_kernel<128, 4, 16, 4>",)),
 }
 
 
@@ -436,6 +437,27 @@ def main():
                              "useful_tflops": pflops / (pms * 1e-3) / 1e12, "vs_token_by_token": c3.R * dms / pms}
         result["roofline_prefill"] = roof_hbm("roofline_prefill", pbytes / (pms * 1e-3) / 1e9)
         del lay, pre, tabs
+        torch.cuda.empty_cache()
+
+        # ---- grouped-query decode: config 5's 32 query heads over 8 shared KV heads (a quarter of the cache per step) ---
+        Hkv = 8
+        gq = {"k_mem": pool.tensor((c5.B, Hkv, cap5, c5.d)), "v_mem": pool.tensor((c5.B, Hkv, cap5, c5.d)),
+              "k_read": pool.tensor((c5.B, Hkv, c5.R, c5.d)), "v_read": pool.tensor((c5.B, Hkv, c5.R, c5.d)),
+              "k_new": pool.tensor((c5.B, Hkv, 1, c5.d)), "v_new": pool.tensor((c5.B, Hkv, 1, c5.d))}
+        wsg = torch.empty(max(loma.loma_decode_gqa_workspace_bytes(c5.B, c5.H, Hkv, c5.d), 16), dtype=torch.uint8, device="cuda")
+
+        def dec_gqa(i):
+            loma.loma_decode_attn_gqa(q5, gq["k_new"], gq["v_new"], gq["k_mem"], gq["v_mem"], gq["k_read"], gq["v_read"],
+                                      c5.t, c5.c, nm5, i % c5.steps, c5.scale, out=o5, workspace=wsg)
+        gms = time_median(dec_gqa, 16, NS, warmup=2)
+        # K and V of the 8 KV heads once, their new rows in and out, q and out of all 32 heads
+        nk5 = nm5 * c5.t
+        gb5 = sum(c5.B * (Hkv * (2 * (nk5 + f + 1) * c5.d + 2 * c5.d) + c5.H * 2 * c5.d) * 2 for f in range(16)) / 16
+        result["decode_gqa"] = {"workload": f"{c5.name} with {Hkv} KV heads under {c5.H} query heads", "value": gb5 / (gms * 1e-3) / 1e9,
+                                "unit": "GB/s (algorithmic)", "frac_of_hbm_peak": gb5 / (gms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                "us_per_call": gms * 1e3, "bytes_per_call": gb5, "us_per_call_all_kv_heads": dec_ms * 1e3}
+        result["roofline_decode_gqa"] = roof_hbm("roofline_decode_gqa", gb5 / (gms * 1e-3) / 1e9)
+        del gq
         torch.cuda.empty_cache()
 
     if not args.no_peaks:

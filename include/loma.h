@@ -210,6 +210,27 @@ size_t loma_decode_layers_workspace_bytes(int n_layers, int B, int H, int head_d
                                           int n_mem_chunks, int dtype);
 
 /*
+ * The decode step with grouped-query attention: H query heads, H_kv <= H key/value heads, query head h
+ * reads the cache of KV head h / (H / H_kv) (Sec. 3.1 steps 1 and 3 on the cache layout of models
+ * other than the paper's Llama-2-7B, which the conclusion claims the method carries over to; the
+ * compressed cache then holds H_kv heads and a step streams it once for the H / H_kv queries that
+ * share a head).  Arguments as loma_decode_attn with: q, out DEVICE [B, H, head_dim]; k_new, v_new
+ * DEVICE [B, H_kv, head_dim] or both NULL; k_memcache, v_memcache DEVICE [B, H_kv, mem_capacity,
+ * head_dim]; k_read, v_read DEVICE [B, H_kv, t*c, head_dim] (row read_fill of every KV head is
+ * written when k_new is given).  H must be H_kv times 1, 2, 4 or 8 and the data bf16 with head_dim
+ * 64 or 128 (else LOMA_ERR_UNSUPPORTED).  workspace: at least loma_decode_gqa_workspace_bytes(...)
+ * bytes, caller-owned, 16-byte aligned.  Deterministic: fixed split plan, fixed merge order.
+ */
+int loma_decode_attn_gqa(const void* q, const void* k_new, const void* v_new,
+                         const void* k_memcache, const void* v_memcache,
+                         void* k_read, void* v_read, void* out,
+                         int B, int H, int H_kv, int head_dim, int t, int c,
+                         int n_mem_chunks, int mem_capacity, int read_fill,
+                         float scale, int dtype,
+                         void* workspace, size_t workspace_bytes, void* stream);
+size_t loma_decode_gqa_workspace_bytes(int B, int H, int H_kv, int head_dim, int dtype);
+
+/*
  * Position ids (Sec. 4.5, Eq. 14; Appendix A).  Host-only arithmetic on HOST arrays; launches nothing.
  * The text is cut into reading zones of R = t*c tokens; reading token j of chunk i keeps its original id
  * i*R + j.  The t memory tokens of chunk i (i = number of chunks compressed before it) take

@@ -238,6 +238,29 @@ class GenerationCache:
         v = np.concatenate([self.v_mem, self.v_read], axis=2)
         return self._attend(np.asarray(q, dtype=np.float64), k, v)
 
+    def decode_gqa(self, q, k_new, v_new):
+        """Grouped-query decode: this cache holds H = H_kv key/value heads; q is [B, Hq, 1, d] with Hq a multiple
+        of H, k_new, v_new are [B, H, 1, d].  Query head h reads KV head h // (Hq // H); otherwise decode()
+        (Appendix A with one input token; the head sharing is the cache layout of grouped-query models, not the
+        paper's Llama-2-7B)."""
+        q = np.asarray(q, dtype=np.float64)
+        Hq = q.shape[1]
+        if Hq % self.H:
+            raise ValueError("query heads must be a multiple of the cache's heads")
+        G = Hq // self.H
+        if self.read_fill >= self.R:
+            raise ValueError("reading zone is full: compress first")
+        self.k_read = np.concatenate([self.k_read, np.asarray(k_new, dtype=np.float64)], axis=2)
+        self.v_read = np.concatenate([self.v_read, np.asarray(v_new, dtype=np.float64)], axis=2)
+        k = np.concatenate([self.k_mem, self.k_read], axis=2)
+        v = np.concatenate([self.v_mem, self.v_read], axis=2)
+        ones = np.ones((1, k.shape[2]), dtype=np.uint8)
+        out = np.empty(q.shape, dtype=np.float64)
+        for b in range(self.B):
+            for h in range(Hq):
+                out[b, h], _, _ = masked_softmax_attention(q[b, h], k[b, h // G], v[b, h // G], ones, self.scale)
+        return out
+
     def prefill(self, q, k_new, v_new):
         """q, k_new, v_new: [B, H, l, d] -- l tokens fed at once (Appendix A, inference_input with
         several input tokens).  The l rows are appended to the reading zone; the mask over

@@ -291,6 +291,47 @@ int loma_decode_attn_rope(const void* q, const void* k_new, const void* v_new,
                             &rt);
 }
 
+static bool good_gqa_heads(int H, int H_kv) {
+    if (H < 1 || H_kv < 1 || H % H_kv != 0) return false;
+    return true;
+}
+
+size_t loma_decode_gqa_workspace_bytes(int B, int H, int H_kv, int head_dim, int dtype) {
+    if (B < 1 || !good_gqa_heads(H, H_kv) || !loma::use_mfma_path(dtype, head_dim)) return 0;
+    if ((long long)B * H_kv > 65535) return 0;
+    return loma::decode_gqa_workspace_bytes(B * H_kv, H / H_kv, head_dim);
+}
+
+int loma_decode_attn_gqa(const void* q, const void* k_new, const void* v_new,
+                         const void* k_memcache, const void* v_memcache,
+                         void* k_read, void* v_read, void* out,
+                         int B, int H, int H_kv, int head_dim, int t, int c,
+                         int n_mem_chunks, int mem_capacity, int read_fill,
+                         float scale, int dtype,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+    if ((k_new == nullptr) != (v_new == nullptr)) return LOMA_ERR_INVALID_ARG;
+    if (!good_gqa_heads(H, H_kv)) return LOMA_ERR_INVALID_ARG;
+    const bool has_new = k_new != nullptr;
+    long long n_mem_keys = 0;
+    // the cache state is that of B * H_kv sequences
+    if (int rc = check_decode_state(B, H_kv, head_dim, t, c, n_mem_chunks, mem_capacity, read_fill, has_new, scale, dtype,
+                                    &n_mem_keys))
+        return rc;
+    if (!good_ptr(q) || !good_ptr(out) || !good_ptr(k_read) || !good_ptr(v_read)) return LOMA_ERR_INVALID_ARG;
+    if (has_new && (!aligned16(k_new) || !aligned16(v_new))) return LOMA_ERR_INVALID_ARG;
+    if (n_mem_chunks > 0 && (!good_ptr(k_memcache) || !good_ptr(v_memcache))) return LOMA_ERR_INVALID_ARG;
+    const int G = H / H_kv;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return LOMA_ERR_UNSUPPORTED;
+    if (!loma::use_mfma_path(dtype, head_dim)) return LOMA_ERR_UNSUPPORTED;
+    if ((long long)B * H_kv > 65535) return LOMA_ERR_UNSUPPORTED;
+    const int nbh_kv = B * H_kv;
+    const size_t need = loma::decode_gqa_workspace_bytes(nbh_kv, G, head_dim);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned16(workspace))) return LOMA_ERR_WORKSPACE;
+    return loma::launch_decode_gqa(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, nbh_kv, G, head_dim,
+                                   t * c, (int)n_mem_keys, mem_capacity, read_fill, scale, need > 0 ? workspace : nullptr,
+                                   static_cast<hipStream_t>(stream));
+}
+
 size_t loma_decode_static_scratch_bytes(void) { return loma::decode_static_scratch_bytes(); }
 
 size_t loma_decode_layers_workspace_bytes(int n_layers, int B, int H, int head_dim, int t, int c,

@@ -250,6 +250,149 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodePara
     }
 }
 
+// Grouped-query form: G consecutive query heads share one KV head (models other than Llama-2-7B; with G = 1 this is
+// the kernel above without its layered and rotary variants).  A workgroup belongs to a KV head and a key split and
+// streams that head's K and V ONCE for all G queries: same loads, same lane layout, G online-softmax states per lane
+// group, worked through one query after the other while a batch of rows sits in registers (16-wave workgroups hold
+// half as many rows at a time: 128 registers per lane).  blockIdx.y = b * H_kv + hk;
+// query head (b, hk * G + gq) has index bh * G + gq in q, out and the partial results.
+template <int D, int G, int DEC_WAVES, int UNROLL>
+__global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_gqa_kernel(DecodeParams P) {
+    constexpr int LPR = D / 8;
+    constexpr int RPL = 64 / LPR;
+    constexpr int KPW = RPL * UNROLL;
+    __shared__ float sm_acc[DEC_WAVES][D];
+    __shared__ float sm_m[DEC_WAVES], sm_l[DEC_WAVES];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int sp = blockIdx.x;
+    const long bh = blockIdx.y;
+    const int col = lane % LPR, sub = lane / LPR;
+    const int kbeg = sp * P.keys_per_split;
+    const int kend = min(P.L, kbeg + P.keys_per_split);
+    const bf16_t* kmem = P.k_mem + bh * P.mem_rows * D;
+    const bf16_t* vmem = P.v_mem + bh * P.mem_rows * D;
+    const bf16_t* kread = P.k_read + bh * (long)P.R * D;
+    const bf16_t* vread = P.v_read + bh * (long)P.R * D;
+    const bf16_t* knew = P.k_new + bh * D;
+    const bf16_t* vnew = P.v_new + bh * D;
+
+    bf16x2 qq[G][4];
+    float m[G], l[G], acc[G][8];
+#pragma unroll
+    for (int gq = 0; gq < G; ++gq) {
+        const uint4 qv = *reinterpret_cast<const uint4*>(P.q + (bh * G + gq) * D + col * 8);
+        qq[gq][0] = as_bf16x2(qv.x); qq[gq][1] = as_bf16x2(qv.y); qq[gq][2] = as_bf16x2(qv.z); qq[gq][3] = as_bf16x2(qv.w);
+        m[gq] = -INFINITY; l[gq] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[gq][e] = 0.f;
+    }
+
+    for (int base = kbeg + w * KPW; base < kend; base += DEC_WAVES * KPW) {
+        u32x4 kk[UNROLL], vv[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int j = base + u * RPL + sub;
+            kk[u] = u32x4{0, 0, 0, 0};
+            vv[u] = u32x4{0, 0, 0, 0};
+            if (j < kend) {
+                const bf16_t *kp, *vp;
+                if (j < P.n_mem) { kp = kmem + (long)j * D; vp = vmem + (long)j * D; }
+                else if (j < P.n_mem + P.n_read) { kp = kread + (long)(j - P.n_mem) * D; vp = vread + (long)(j - P.n_mem) * D; }
+                else { kp = knew; vp = vnew; }
+                kk[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + col * 8));
+                vv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vp + col * 8));
+            }
+        }
+#pragma unroll
+        for (int gq = 0; gq < G; ++gq) {
+            float s[UNROLL];
+            float mx = m[gq];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t k0 = kk[u][0], k1 = kk[u][1], k2 = kk[u][2], k3 = kk[u][3];
+                float a = __builtin_amdgcn_fdot2_f32_bf16(qq[gq][0], as_bf16x2(k0), 0.f, false);
+                a = __builtin_amdgcn_fdot2_f32_bf16(qq[gq][1], as_bf16x2(k1), a, false);
+                a = __builtin_amdgcn_fdot2_f32_bf16(qq[gq][2], as_bf16x2(k2), a, false);
+                a = __builtin_amdgcn_fdot2_f32_bf16(qq[gq][3], as_bf16x2(k3), a, false);
+                a = row_sum<LPR>(a) * P.sc;
+                s[u] = (base + u * RPL + sub < kend) ? a : -INFINITY;
+                mx = fmaxf(mx, s[u]);
+            }
+            const float alpha = (mx == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m[gq] - mx);
+            float ps = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[gq][e] *= alpha;
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const float p = (s[u] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(s[u] - mx);
+                ps += p;
+                acc[gq][0] = fmaf(p, bf16_lo(vv[u].x), acc[gq][0]);
+                acc[gq][1] = fmaf(p, bf16_hi(vv[u].x), acc[gq][1]);
+                acc[gq][2] = fmaf(p, bf16_lo(vv[u].y), acc[gq][2]);
+                acc[gq][3] = fmaf(p, bf16_hi(vv[u].y), acc[gq][3]);
+                acc[gq][4] = fmaf(p, bf16_lo(vv[u].z), acc[gq][4]);
+                acc[gq][5] = fmaf(p, bf16_hi(vv[u].z), acc[gq][5]);
+                acc[gq][6] = fmaf(p, bf16_lo(vv[u].w), acc[gq][6]);
+                acc[gq][7] = fmaf(p, bf16_hi(vv[u].w), acc[gq][7]);
+            }
+            l[gq] = l[gq] * alpha + ps;
+            m[gq] = mx;
+        }
+    }
+
+#pragma unroll
+    for (int gq = 0; gq < G; ++gq) {
+        float mg = m[gq], lg = l[gq];
+        // merge the lane groups of the wave, then the waves of the workgroup, as in the kernel above
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) {
+            const float m2 = __shfl_xor(mg, off), l2 = __shfl_xor(lg, off);
+            const float M = fmaxf(mg, m2);
+            const float w1 = (mg == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mg - M);
+            const float w2 = (m2 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m2 - M);
+            lg = lg * w1 + l2 * w2;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[gq][e] = acc[gq][e] * w1 + __shfl_xor(acc[gq][e], off) * w2;
+            mg = M;
+        }
+        if (gq > 0) __syncthreads();   // the previous query's merge has read the buffers
+        if (sub == 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sm_acc[w][col * 8 + e] = acc[gq][e];
+            if (col == 0) { sm_m[w] = mg; sm_l[w] = lg; }
+        }
+        __syncthreads();
+        if (tid < D) {
+            float M = -INFINITY;
+#pragma unroll
+            for (int gidx = 0; gidx < DEC_WAVES; ++gidx) M = fmaxf(M, sm_m[gidx]);
+            float Lsum = 0.f, o = 0.f;
+#pragma unroll
+            for (int gidx = 0; gidx < DEC_WAVES; ++gidx) {
+                const float wgt = (sm_m[gidx] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sm_m[gidx] - M);
+                Lsum = fmaf(sm_l[gidx], wgt, Lsum);
+                o = fmaf(sm_acc[gidx][tid], wgt, o);
+            }
+            const long bhq = bh * G + gq;
+            if (P.nsplit == 1) {
+                P.out[bhq * D + tid] = f32_to_bf16(o / Lsum);
+            } else {
+                const long pi = bhq * P.nsplit + sp;
+                P.ws_acc[pi * D + tid] = o;
+                if (tid == 0) { P.ws_ml[pi * 2] = M; P.ws_ml[pi * 2 + 1] = Lsum; }
+            }
+        }
+    }
+    // append the new token to the KV head's reading zone
+    if (P.has_new && sp == 0 && tid < 2 * LPR) {
+        const int which = tid / LPR, piece = tid % LPR;
+        const uint4 x = *reinterpret_cast<const uint4*>((which ? vnew : knew) + piece * 8);
+        bf16_t* dst = (which ? P.v_read : P.k_read) + (bh * (long)P.R + P.n_read) * D;
+        *reinterpret_cast<uint4*>(dst + piece * 8) = x;
+    }
+}
+
 template <int D, bool LAYERED>
 __global__ __launch_bounds__(D) void decode_combine_kernel(DecodeParams P) {
     const long bh = blockIdx.x;
@@ -366,6 +509,73 @@ int launch_decode_splitk(const void* q, const void* k_new, const void* v_new,
                         : launch_decode_d<64, false, true>(P, nbh, 1, workspace, st, *rope);
     return D == 128 ? launch_decode_d<128, false>(P, nbh, 1, workspace, st)
                     : launch_decode_d<64, false>(P, nbh, 1, workspace, st);
+}
+
+// grouped-query form: split plan from the KV heads as in the plain form (few heads: 16-wave workgroups, about one per
+// CU; many: 4-wave workgroups), partial results per query head
+namespace {
+// eight queries per KV head do not fit the 128 registers a lane of a 16-wave workgroup has: 4-wave workgroups then
+inline bool gqa_wide(int nbh_kv, int G) { return wg_waves(nbh_kv) == 16 && G <= 4; }
+inline int gqa_target_splits(int nbh_kv, int G) {
+    return gqa_wide(nbh_kv, G) ? target_splits(nbh_kv) : (DEC_TARGET_WGS_4 + nbh_kv - 1) / nbh_kv;
+}
+template <int D, int G>
+int launch_decode_gqa_dg(DecodeParams& P, int nbh_kv, void* workspace, hipStream_t st) {
+    const bool wide = gqa_wide(nbh_kv, G);
+    const int kpi = (wide ? 16 * 4 : 4 * DEC_UNROLL) * (64 / (D / 8));   // keys per workgroup iteration
+    const int units = (P.L + kpi - 1) / kpi;
+    const int tgt = gqa_target_splits(nbh_kv, G);
+    const int ups = (units + tgt - 1) / tgt;
+    P.nsplit = (units + ups - 1) / ups;
+    P.keys_per_split = ups * kpi;
+    const long nbh_q = (long)nbh_kv * G;
+    P.ws_acc = static_cast<float*>(workspace);
+    P.ws_ml = P.ws_acc ? P.ws_acc + (size_t)nbh_q * tgt * D : nullptr;
+    if constexpr (G <= 4) {
+        if (wide) hipLaunchKernelGGL((decode_split_gqa_kernel<D, G, 16, 4>), dim3(P.nsplit, nbh_kv), dim3(1024), 0, st, P);
+    }
+    if (!wide) hipLaunchKernelGGL((decode_split_gqa_kernel<D, G, 4, DEC_UNROLL>), dim3(P.nsplit, nbh_kv), dim3(256), 0, st, P);
+    if (hipGetLastError() != hipSuccess) return LOMA_ERR_LAUNCH;
+    if (P.nsplit > 1) {
+        hipLaunchKernelGGL((decode_combine_kernel<D, false>), dim3((unsigned)nbh_q), dim3(D), 0, st, P);
+        if (hipGetLastError() != hipSuccess) return LOMA_ERR_LAUNCH;
+    }
+    return LOMA_OK;
+}
+template <int D>
+int launch_decode_gqa_d(DecodeParams& P, int nbh_kv, int G, void* workspace, hipStream_t st) {
+    switch (G) {
+        case 1: return launch_decode_gqa_dg<D, 1>(P, nbh_kv, workspace, st);
+        case 2: return launch_decode_gqa_dg<D, 2>(P, nbh_kv, workspace, st);
+        case 4: return launch_decode_gqa_dg<D, 4>(P, nbh_kv, workspace, st);
+        case 8: return launch_decode_gqa_dg<D, 8>(P, nbh_kv, workspace, st);
+        default: return LOMA_ERR_UNSUPPORTED;
+    }
+}
+}  // namespace
+
+size_t decode_gqa_workspace_bytes(int nbh_kv, int G, int D) {
+    const int tgt = gqa_target_splits(nbh_kv, G);
+    if (tgt <= 1) return 0;
+    return (size_t)nbh_kv * G * tgt * (D + 2) * sizeof(float);
+}
+
+int launch_decode_gqa(const void* q, const void* k_new, const void* v_new,
+                      const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
+                      void* out, int nbh_kv, int G, int D, int R, int n_mem_keys, int mem_capacity, int read_fill,
+                      float scale, void* workspace, hipStream_t st) {
+    DecodeParams P = {};
+    P.q = static_cast<const bf16_t*>(q);
+    P.k_new = static_cast<const bf16_t*>(k_new); P.v_new = static_cast<const bf16_t*>(v_new);
+    P.k_mem = static_cast<const bf16_t*>(k_memcache); P.v_mem = static_cast<const bf16_t*>(v_memcache);
+    P.k_read = static_cast<bf16_t*>(k_read); P.v_read = static_cast<bf16_t*>(v_read);
+    P.out = static_cast<bf16_t*>(out);
+    P.mem_rows = mem_capacity; P.R = R; P.n_mem = n_mem_keys; P.n_read = read_fill;
+    P.has_new = k_new != nullptr;
+    P.L = n_mem_keys + read_fill + (P.has_new ? 1 : 0);
+    P.sc = scale * LOG2E;
+    if (nbh_kv > 65535 || (long long)nbh_kv * G > 0x7fffffffLL) return LOMA_ERR_UNSUPPORTED;
+    return D == 128 ? launch_decode_gqa_d<128>(P, nbh_kv, G, workspace, st) : launch_decode_gqa_d<64>(P, nbh_kv, G, workspace, st);
 }
 
 int launch_decode_splitk_layers(const void* const* tables[8], bool has_new, int n_layers, int nbh, int D, int R,

@@ -158,6 +158,13 @@ int launch_decode_splitk(const void* q, const void* k_new, const void* v_new,
 int launch_decode_splitk_layers(const void* const* tables[8], bool has_new, int n_layers, int nbh, int D, int R,
                                 int n_mem_keys, int mem_capacity, int read_fill, float scale, void* workspace,
                                 hipStream_t st);
+// Grouped-query decode: G = H / H_kv consecutive query heads share a KV head (G in {1, 2, 4, 8}); q and out hold
+// nbh_kv * G rows, every cache tensor nbh_kv sequences.  The workspace holds decode_gqa_workspace_bytes().
+size_t decode_gqa_workspace_bytes(int nbh_kv, int G, int D);
+int launch_decode_gqa(const void* q, const void* k_new, const void* v_new,
+                      const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
+                      void* out, int nbh_kv, int G, int D, int R, int n_mem_keys, int mem_capacity, int read_fill,
+                      float scale, void* workspace, hipStream_t st);
 // Fixed split-K scratch inside the library's device image (for callers that cannot allocate): its size, and its
 // address on the current device (nullptr if the runtime cannot resolve it).
 size_t decode_static_scratch_bytes();

@@ -55,6 +55,10 @@ def _load() -> ctypes.CDLL:
     lib.loma_decode_attn_layers.restype = I
     lib.loma_decode_layers_workspace_bytes.argtypes = [I, I, I, I, I, I, I, I]
     lib.loma_decode_layers_workspace_bytes.restype = Z
+    lib.loma_decode_attn_gqa.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, I, F, I, vp, Z, vp]
+    lib.loma_decode_attn_gqa.restype = I
+    lib.loma_decode_gqa_workspace_bytes.argtypes = [I, I, I, I, I]
+    lib.loma_decode_gqa_workspace_bytes.restype = Z
     lib.loma_decode_attn_rope.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, F, I, I, F, vp, Z, vp]
     lib.loma_decode_attn_rope.restype = I
     lib.loma_compress_step_rope.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, F, I, I, I, F, vp]
@@ -249,6 +253,40 @@ def loma_decode_attn(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, t,
                               pws, nws, _stream(stream))
     if rc != OK:
         raise LomaError(rc, "loma_decode_attn")
+    return out
+
+
+def loma_decode_gqa_workspace_bytes(B, H, H_kv, d, dtype=torch.bfloat16) -> int:
+    code = F32 if dtype == torch.float32 else BF16
+    return int(lib.loma_decode_gqa_workspace_bytes(B, H, H_kv, d, code))
+
+
+def loma_decode_attn_gqa(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, t, c, n_mem_chunks, read_fill, scale,
+                         out=None, workspace=None, stream=None):
+    """loma_decode_attn with H query heads (q, out: [B, H, 1, d]) over H_kv shared key/value heads (every other
+    tensor: [B, H_kv, ...]); query head h reads KV head h // (H // H_kv)."""
+    B, H, one, d = q.shape
+    if one != 1:
+        raise ValueError("q must be [B, H, 1, d]")
+    H_kv = k_read.shape[1]
+    if out is None:
+        out = torch.empty_like(q)
+    dt = q.dtype
+    pkn = None if k_new is None else _dev(k_new, "k_new", (B, H_kv, 1, d), dt)
+    pvn = None if v_new is None else _dev(v_new, "v_new", (B, H_kv, 1, d), dt)
+    cap = 0 if k_memcache is None else k_memcache.shape[2]
+    pkm = None if k_memcache is None else _dev(k_memcache, "k_memcache", (B, H_kv, cap, d), dt)
+    pvm = None if v_memcache is None else _dev(v_memcache, "v_memcache", (B, H_kv, cap, d), dt)
+    pkr = _dev(k_read, "k_read", (B, H_kv, t * c, d), dt)
+    pvr = _dev(v_read, "v_read", (B, H_kv, t * c, d), dt)
+    pws, nws = None, 0
+    if workspace is not None:
+        pws, nws = _dev(workspace, "workspace"), workspace.numel() * workspace.element_size()
+    rc = lib.loma_decode_attn_gqa(_dev(q, "q"), pkn, pvn, pkm, pvm, pkr, pvr, _dev(out, "out", q.shape, dt),
+                                  B, H, H_kv, d, t, c, n_mem_chunks, cap, read_fill, float(scale), _dtype_code(q),
+                                  pws, nws, _stream(stream))
+    if rc != OK:
+        raise LomaError(rc, "loma_decode_attn_gqa")
     return out
 
 

@@ -259,3 +259,31 @@ def test_new_decode_forms_reject_bad_arguments(lib):
     assert need == 4 * lib.loma_decode_workspace_bytes(1, 8, 128, 16, 4, 4, BF16) > 0
     assert layers_call(ws=None) == EWS
     assert layers_call(wsb=need - 1) == EWS
+
+
+def test_grouped_query_decode_rejects_bad_arguments(lib):
+    def call(**kw):
+        a = dict(q=P, kn=P, vn=P, kc=P, vc=P, kr=P, vr=P, out=P, B=1, H=8, Hkv=2, d=128, t=16, c=4, nmem=4, cap=64,
+                 fill=3, scale=0.1, dtype=BF16, ws=P, wsb=1 << 30)
+        a.update(kw)
+        return lib.loma_decode_attn_gqa(a["q"], a["kn"], a["vn"], a["kc"], a["vc"], a["kr"], a["vr"], a["out"], a["B"],
+                                        a["H"], a["Hkv"], a["d"], a["t"], a["c"], a["nmem"], a["cap"], a["fill"],
+                                        a["scale"], a["dtype"], a["ws"], a["wsb"], None)
+    assert call(q=None) == EINVAL
+    assert call(Hkv=3) == EINVAL                  # query heads not a multiple of the KV heads
+    assert call(Hkv=0) == EINVAL
+    assert call(H=6) == EUNSUP                    # three query heads per KV head
+    assert call(H=32, Hkv=2) == EUNSUP            # sixteen
+    assert call(kn=None) == EINVAL                # k_new without v_new
+    assert call(kc=None) == EINVAL                # memory rows but no cache
+    assert call(fill=64) == EINVAL
+    assert call(nmem=5) == EINVAL
+    assert call(dtype=F32) == EUNSUP
+    assert call(d=96) == EUNSUP
+    need = lib.loma_decode_gqa_workspace_bytes(1, 8, 2, 128, BF16)
+    # partial results per QUERY head: four times what the two KV heads alone would need at the same split plan
+    assert need > 0 and need % (8 * 130 * 4) == 0
+    assert call(ws=None) == EWS
+    assert call(wsb=need - 1) == EWS
+    assert lib.loma_decode_gqa_workspace_bytes(1, 8, 3, 128, BF16) == 0
+    assert lib.loma_decode_gqa_workspace_bytes(1, 8, 2, 128, F32) == 0

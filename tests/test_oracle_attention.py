@@ -417,3 +417,41 @@ def test_backward_invariants(c_oracle):
     k2 = np.broadcast_to(k[:, :, :1], k.shape).copy()
     dq2, _, _ = lo.mask_attn_bwd(q, k2, v, g, t, c, n, scale)
     np.testing.assert_allclose(dq2, 0.0, atol=1e-13)
+
+
+def test_grouped_query_decode_is_plain_decode_on_repeated_kv_heads():
+    """decode_gqa against what head sharing means: the same step on a cache in which every KV head is written out
+    once per query head that reads it.  A wrong head mapping (h % G for h // G), a missed append or a transposed
+    group fails here; G = 1 must be decode() itself."""
+    rng = np.random.default_rng(7)
+    B, Hkv, G, d, t, c = 2, 3, 4, 8, 4, 2
+    Hq = Hkv * G
+    scale = 0.3
+    km, vm = rng.standard_normal((2, B, Hkv, 2 * t, d))
+    kr, vr = rng.standard_normal((2, B, Hkv, 5, d))
+    q = rng.standard_normal((B, Hq, 1, d))
+    kn, vn = rng.standard_normal((2, B, Hkv, 1, d))
+    orc = lo
+    a = orc.GenerationCache(B, Hkv, d, t, c, scale)
+    a.load_state(km, vm, kr, vr)
+    got = a.decode_gqa(q, kn, vn)
+    rep = lambda x: np.repeat(x, G, axis=1)
+    b = orc.GenerationCache(B, Hq, d, t, c, scale)
+    b.load_state(rep(km), rep(vm), rep(kr), rep(vr))
+    want = b.decode(q, rep(kn), rep(vn))
+    assert np.allclose(got, want, rtol=0, atol=1e-13)
+    assert a.read_fill == 6 and np.array_equal(a.k_read[:, :, 5:], kn) and np.array_equal(a.v_read[:, :, 5:], vn)
+    # two query heads of one group with the same query give the same output; heads of different groups do not
+    q2 = q.copy()
+    q2[:, 1] = q2[:, 0]
+    q2[:, G] = q2[:, 0]
+    a2 = orc.GenerationCache(B, Hkv, d, t, c, scale)
+    a2.load_state(km, vm, kr, vr)
+    o2 = a2.decode_gqa(q2, kn, vn)
+    assert np.array_equal(o2[:, 1], o2[:, 0]) and not np.allclose(o2[:, G], o2[:, 0])
+    # G = 1
+    c1 = orc.GenerationCache(B, Hkv, d, t, c, scale)
+    c1.load_state(km, vm, kr, vr)
+    d1 = orc.GenerationCache(B, Hkv, d, t, c, scale)
+    d1.load_state(km, vm, kr, vr)
+    assert np.array_equal(c1.decode_gqa(q[:, :Hkv], kn, vn), d1.decode(q[:, :Hkv], kn, vn))
