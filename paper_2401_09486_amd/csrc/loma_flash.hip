@@ -698,10 +698,11 @@ struct PipeCfg {
 // statements, which the compiler keeps in source order among themselves and against the fences (written as plain
 // arithmetic it sank every exponential behind the MFMAs; given as scheduling groups the order held but ran 2-3 %
 // slower than this).  Nothing reads an MFMA's result before the next step.
-template <int D, bool HAVE_S, bool HAVE_PV, bool HAVE_P = true>
+template <int D, bool HAVE_S, bool HAVE_PV, bool HAVE_P = true, bool MASKED = false>
 __device__ __forceinline__ float pipe_half(const bf16_t* Kh, const bf16_t* Vh, const int (&koff)[D / 16], const int (&voff)[D / 32],
                                            const bf16x8 (&qreg)[D / 16], const f32x16& Sc, f32x16& Sn,
-                                           const bf16x8 (&Pp)[2], bf16x8 (&Pc)[2], f32x16 (&O)[D / 32], float sc, float mc) {
+                                           const bf16x8 (&Pp)[2], bf16x8 (&Pc)[2], f32x16 (&O)[D / 32], float sc, float mc,
+                                           int thr = 0) {
     constexpr int KSTEPS = D / 16, DT = D / 32, NPV = 2 * DT;
     static_assert(NPV == KSTEPS, "as many P.V products as score products per half tile");
     constexpr int NSLOT = 2 * KSTEPS, EPS = 16 / NSLOT;      // slots of one MFMA each; scores handled per slot
@@ -730,7 +731,10 @@ __device__ __forceinline__ float pipe_half(const bf16_t* Kh, const bf16_t* Vh, c
         if constexpr (HAVE_P) {
             static_for<slot * EPS, (slot + 1) * EPS>([&](auto ec) {
                 constexpr int e = ec.value;
-                const float y = exp2_at(__builtin_fmaf(Sc[e], sc, -mc));
+                float y = exp2_at(__builtin_fmaf(Sc[e], sc, -mc));
+                // MASKED: element e is key 8 (e / 4) + e % 4 (+ 4 g, folded into thr) of the half tile; the lane's row
+                // sees it iff that number does not exceed the lane's threshold
+                if constexpr (MASKED) y = (8 * (e / 4) + e % 4 <= thr) ? y : 0.f;
                 pe[e & 1] = y;
                 ps += y;
                 if constexpr (e & 1) pw[e >> 1] = pack_bf16_at(pe[0], pe[1]);
@@ -862,12 +866,18 @@ __device__ __forceinline__ void flash_job_pipe(const FlashJob& J, float sc, bf16
     // tile-by-tile loop below, which moves the reference as it goes, takes over at `resume`, after redoing the
     // half in question (`redo_half`) if the tile's first half had already been accumulated.
     int resume = 0;          // first tile the tile-by-tile loop has to do
-    int redo_half = -1;      // tile whose second half it has to do first, from the scores kept in `Sredo`
-    f32x16 Sredo[1];
+    int redo_half = -1;      // tile whose second half it has to do first, from its scores, which `Sb` still holds
+    int redo_thr = 64;       // ... of whose keys the lane's row sees those up to this number (see pipe_half)
+    f32x16 Sa, Sbv[1];       // the two score sets of the pipelined loop; the second one holds the scores to redo
+    f32x16& Sb = Sbv[0];
+    // Tiles cut by the causal diagonal or by the end of the key list go through the same loop with a per-lane key
+    // threshold (MASKED steps), up to the last tile any row of the wave sees; the tile-by-tile loop is left with
+    // the barriers and requests of the tiles after it -- and with everything when no tile is fully visible (the
+    // reference needs a first half tile without a mask) or the range test trips.
+    const int npipe = nfull > 0 ? min(ntiles, (kend_w + BN - 1) / BN) : 0;
     if (nfull > 0) {
-        resume = nfull;
+        resume = npipe;
         if (has_rows) {
-            f32x16 Sa, Sb;
             bf16x8 Pa[2], Pb[2];
             const float range = __builtin_amdgcn_exp2f(PIPE_TAU);
             // scores of the first half tile, alone; the reference is their maximum
@@ -887,30 +897,43 @@ __device__ __forceinline__ void flash_job_pipe(const FlashJob& J, float sc, bf16
             const float mc = m * sc;
             // first half of tile 0: nothing to multiply by V yet (no probability exceeds 1 here)
             lsum += pipe_half<D, true, false>(kstage(0) + 32 * D, nullptr, koff, voff, qreg, Sa, Sb, Pb, Pa, O, sc, mc);
+            // One trip: every wave is done with K stage t and V stage t-1, and everybody's part of tile t+1 is in;
+            // second half of tile t (its probabilities; scores of (t+1, 0); P.V of (t, 0)), then first half of tile
+            // t+1 (its probabilities; scores of (t+1, 1); P.V of (t, 1)).  The lane's row sees key k of half (T, h)
+            // iff 64 T + 32 h + k <= my_lim.
+#define LOMA_PIPE_TILE(MASKED_)                                                                                              \
+    {                                                                                                                        \
+        wait_tile(t + 1);                                                                                                    \
+        __syncthreads();                                                                                                     \
+        if (next_req < ntiles) request_next(); /* tile t + NSK */                                                            \
+        const int thr_b = my_lim - BN * t - 32 - 4 * g, thr_a = my_lim - BN * (t + 1) - 4 * g;                               \
+        const float psb = pipe_half<D, true, true, true, MASKED_>(kstage(t + 1), vstage(t), koff, voff, qreg, Sb, Sa, Pa, Pb, \
+                                                                  O, sc, mc, thr_b);                                         \
+        if (__builtin_amdgcn_ballot_w64(!(psb <= range)) != 0) {                                                             \
+            redo_half = t; redo_thr = MASKED_ ? thr_b : 64; resume = t + 1;                                                  \
+            break;                                                                                                           \
+        }                                                                                                                    \
+        lsum += psb;                                                                                                         \
+        const float psa = pipe_half<D, true, true, true, MASKED_>(kstage(t + 1) + 32 * D, vstage(t) + 32 * D, koff, voff,    \
+                                                                  qreg, Sa, Sb, Pb, Pa, O, sc, mc, thr_a);                   \
+        if (__builtin_amdgcn_ballot_w64(!(psa <= range)) != 0) { resume = t + 1; break; }                                    \
+        lsum += psa;                                                                                                         \
+    }
             int t = 0;
-            for (; t + 1 < nfull; ++t) {
-                // every wave is done with K stage t and V stage t-1, and everybody's part of tile t+1 is in
-                wait_tile(t + 1);
-                __syncthreads();
-                if (next_req < ntiles) request_next();      // tile t + NSK
-                // second half of tile t: its probabilities; scores of (t+1, 0); P.V of (t, 0)
-                const float psb = pipe_half<D, true, true>(kstage(t + 1), vstage(t), koff, voff, qreg, Sb, Sa, Pa, Pb, O, sc, mc);
-                if (__builtin_amdgcn_ballot_w64(!(psb <= range)) != 0) { redo_half = t; resume = t + 1; Sredo[0] = Sb; break; }
-                lsum += psb;
-                // first half of tile t+1: its probabilities; scores of (t+1, 1); P.V of (t, 1)
-                const float psa = pipe_half<D, true, true>(kstage(t + 1) + 32 * D, vstage(t) + 32 * D, koff, voff, qreg, Sa, Sb, Pb, Pa, O,
-                                                           sc, mc);
-                if (__builtin_amdgcn_ballot_w64(!(psa <= range)) != 0) { resume = t + 1; break; }
-                lsum += psa;
-            }
-            if (t + 1 == nfull) {       // the loop ran to its end: second half of the last full tile, then its P.V
+            for (; t + 1 < nfull; ++t) LOMA_PIPE_TILE(false)
+            if (resume == npipe)      // (a trip that left the loop early has set `resume` to an earlier tile)
+                for (; t + 1 < npipe; ++t) LOMA_PIPE_TILE(true)
+#undef LOMA_PIPE_TILE
+            if (resume == npipe && t + 1 == npipe) {   // the loop ran to its end: second half of the last tile, then its P.V
                 wait_tile(t + 1);
                 __syncthreads();
                 if (next_req < ntiles) request_next();
-                const float psb = pipe_half<D, false, true>(nullptr, vstage(t), koff, voff, qreg, Sb, Sa, Pa, Pb, O, sc, mc);
+                const int thr_b = my_lim - BN * t - 32 - 4 * g;
+                // (masked in any case: a fully visible half passes the test in every lane)
+                const float psb = pipe_half<D, false, true, true, true>(nullptr, vstage(t), koff, voff, qreg, Sb, Sa, Pa, Pb, O, sc, mc, thr_b);
                 if (__builtin_amdgcn_ballot_w64(!(psb <= range)) != 0) {
                     redo_half = t;
-                    Sredo[0] = Sb;
+                    redo_thr = thr_b;
                 } else {
                     lsum += psb;
                     f32x16 none;
@@ -924,9 +947,12 @@ __device__ __forceinline__ void flash_job_pipe(const FlashJob& J, float sc, bf16
     // accumulator before ordinary code reads the scores or the output accumulators
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
     if (redo_half >= 0) {
-        // second half of tile `redo_half` with a moving reference, from its scores (every key of a full tile is
-        // visible: nothing to mask; its K rows may be gone by now, its V rows stay until tile redo_half + 3 is requested)
-        softmax_pv_phase<D, NW, 32, false>(vstage(redo_half) + 32 * D, voff, Sredo, O, m, lsum, sc, 1, lane);
+        // second half of tile `redo_half` with a moving reference, from its scores (masked here if the half is a cut
+        // one; its K rows may be gone by now, its V rows stay until tile redo_half + 3 is requested)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (8 * (i >> 2) + (i & 3) > redo_thr) Sbv[0][i] = -INFINITY;
+        softmax_pv_phase<D, NW, 32, false>(vstage(redo_half) + 32 * D, voff, Sbv, O, m, lsum, sc, 1, lane);
     }
     // Tile by tile: what the pipelined loop left, and the tiles cut by the causal diagonal or by the end of the key
     // list, differently for every wave.  Tile kt is in (everybody's part: the barrier that ended the previous tile
