@@ -94,3 +94,45 @@ def test_gqa_rejects_what_it_cannot_do():
     with pytest.raises(loma.LomaError) as e:      # not a multiple at all
         loma.loma_decode_attn_gqa(q5, kn, kn.clone(), None, None, kr, kr.clone(), t, c, 0, 0, 0.1)
     assert e.value.status == loma.ERR_INVALID_ARG
+
+
+def test_gqa_decode_high_ratio_shape_full_size(c_oracle):
+    """The launch configuration the benchmark times: B64, 32 query heads over 8 KV heads, 8208 memory KVs plus a
+    part-filled reading zone, tensors filled on the device from a host-drawn pool.  The oracle follows 12 sampled
+    (b, KV head) pairs with their four query heads each through 6 steps on the same bits."""
+    from paper_2401_09486_amd import loma
+    c5 = wl.CONFIGS[4]
+    B, Hq, Hkv, d, t, c = c5.B, c5.H, 8, c5.d, c5.t, c5.c
+    G = Hq // Hkv
+    n_mem, cap = c5.prior_chunks + 1, c5.mem_capacity
+    pool = wl.TiledPool(c5.seed + 7)
+    st = {"k_mem": pool.tensor((B, Hkv, cap, d)), "v_mem": pool.tensor((B, Hkv, cap, d)),
+          "k_read": pool.tensor((B, Hkv, t * c, d)), "v_read": pool.tensor((B, Hkv, t * c, d))}
+    nkv = B * Hkv
+    sel = np.array(sorted(set(np.linspace(0, nkv - 1, 12).astype(int))), dtype=np.int64)
+    tsel = torch.from_numpy(sel).cuda()
+    qsel = (tsel[:, None] * G + torch.arange(G, device="cuda")[None, :]).reshape(-1)     # their query heads
+
+    def pick_kv(x):   # [B, Hkv, L, d] device -> [1, nsel * G, L, d] host bits, every KV head once per query head
+        flat = x.view(nkv, x.shape[2], x.shape[3])
+        return np.repeat(host_bits(flat[tsel].contiguous()), G, axis=0)[None]
+
+    fill0 = 37
+    orc = c_oracle.GenerationCache(pick_kv(st["k_mem"]), pick_kv(st["v_mem"]), n_mem, pick_kv(st["k_read"]),
+                                   pick_kv(st["v_read"]), fill0, t, c, c5.scale)
+    ws = torch.empty(max(loma.loma_decode_gqa_workspace_bytes(B, Hq, Hkv, d), 16), dtype=torch.uint8, device="cuda")
+    worst = 0.0
+    for step in range(6):
+        fill = fill0 + step
+        print(f"[case] gqa high-ratio shape step {step} fill {fill}", flush=True)
+        q = pool.tensor((B, Hq, 1, d), c5.q_scale)
+        kn, vn = pool.tensor((B, Hkv, 1, d)), pool.tensor((B, Hkv, 1, d))
+        out = loma.loma_decode_attn_gqa(q, kn, vn, st["k_mem"], st["v_mem"], st["k_read"], st["v_read"], t, c, n_mem, fill,
+                                        c5.scale, workspace=ws)
+        qh = host_bits(q.view(B * Hq, 1, d)[qsel].contiguous())[None]
+        ref = orc.decode(qh, pick_kv(kn), pick_kv(vn))
+        mx, _ = check(to_host_f64(out.view(B * Hq, 1, d)[qsel]), ref.reshape(-1, 1, d), "bf16", f"gqa full-size step {step}")
+        worst = max(worst, mx)
+        assert torch.equal(st["k_read"][:, :, fill], kn[:, :, 0]) and torch.equal(st["v_read"][:, :, fill], vn[:, :, 0])
+    assert torch.isfinite(out.float()).all()
+    print(f"[result] gqa high-ratio shape: worst max abs {worst:.3e}", flush=True)
