@@ -664,7 +664,8 @@ __device__ __forceinline__ void flash_job(const FlashJob& J, float sc, bf16_t* s
 // For blocks with long key lists (reading rows behind many memory zones) the matrix pipe and the vector ALU have
 // about the same amount of work per tile (32 MFMAs of 32 cycles against ~800 cycles of exponentials, packing and
 // sums), and a wave that does them one after the other leaves each unit idle half of the time.  Here the loop
-// over fully visible tiles is software-pipelined over HALF tiles of 32 keys: while the vector ALU turns the
+// over the tiles (fully visible ones first, then those cut by the causal diagonal or the end of the key list, with a
+// per-lane key threshold) is software-pipelined over HALF tiles of 32 keys: while the vector ALU turns the
 // scores of half h into probabilities, the matrix pipe multiplies the scores of half h+1 and the P.V product of
 // half h-1, one MFMA every few vector instructions, in one instruction stream.  Half h-1's V rows must stay
 // while half h+1's K rows are read, so the ring holds two K stages and three V stages of 64 keys (80 KB at
@@ -861,7 +862,7 @@ __device__ __forceinline__ void flash_job_pipe(const FlashJob& J, float sc, bf16
     for (int t = 0; t < PC::QP; ++t)
         if (next_req < ntiles) request_next();   // tiles up to NSK-1
 
-    // Pipelined loop over the fully visible tiles.  It runs while every probability stays in range; a half
+    // Pipelined loop.  It runs while every probability stays in range; a half
     // that leaves the range ends it (wave by wave: the barrier count per tile is the same on both paths), and the
     // tile-by-tile loop below, which moves the reference as it goes, takes over at `resume`, after redoing the
     // half in question (`redo_half`) if the tile's first half had already been accumulated.
