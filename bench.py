@@ -74,7 +74,7 @@ ROOFLINE_KERNELS = {
     "roofline_decode": ("c3", ("decode_split_kernel<128, 16, false, false>",)),
     "roofline_decode_layers": ("c3x{L}", ("decode_split_kernel<128, 16, true, false>",)),
     "roofline_prefill": ("c3", ("prefill_kernel<128, 4, 64, 2, 4>",)),
-    "roofline_decode_gqa": ("c5", ("decode_split_gqa_kernel<128, 4, 16, 4>",)),
+    "roofline_decode_gqa": ("c5", ("decode_split_gqa_kernel<128, 4, 16, 4, false>",)),
 }
 
 

@@ -231,6 +231,21 @@ int loma_decode_attn_gqa(const void* q, const void* k_new, const void* v_new,
 size_t loma_decode_gqa_workspace_bytes(int B, int H, int H_kv, int head_dim, int dtype);
 
 /*
+ * loma_decode_attn_gqa for n_layers caches in ONE launch: the tensor arguments become DEVICE arrays of
+ * n_layers device pointers as in loma_decode_attn_layers (same alignment and NULL rules), shapes per
+ * layer as in loma_decode_attn_gqa.  Layer l's result and appended rows are bit-identical to a
+ * loma_decode_attn_gqa call on its tensors.  workspace: at least n_layers times
+ * loma_decode_gqa_workspace_bytes(...) bytes.
+ */
+int loma_decode_attn_gqa_layers(const void* const* q, const void* const* k_new, const void* const* v_new,
+                                const void* const* k_memcache, const void* const* v_memcache,
+                                void* const* k_read, void* const* v_read, void* const* out,
+                                int n_layers, int B, int H, int H_kv, int head_dim, int t, int c,
+                                int n_mem_chunks, int mem_capacity, int read_fill,
+                                float scale, int dtype,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Position ids (Sec. 4.5, Eq. 14; Appendix A).  Host-only arithmetic on HOST arrays; launches nothing.
  * The text is cut into reading zones of R = t*c tokens; reading token j of chunk i keeps its original id
  * i*R + j.  The t memory tokens of chunk i (i = number of chunks compressed before it) take

@@ -332,6 +332,39 @@ int loma_decode_attn_gqa(const void* q, const void* k_new, const void* v_new,
                                    static_cast<hipStream_t>(stream));
 }
 
+int loma_decode_attn_gqa_layers(const void* const* q, const void* const* k_new, const void* const* v_new,
+                                const void* const* k_memcache, const void* const* v_memcache,
+                                void* const* k_read, void* const* v_read, void* const* out,
+                                int n_layers, int B, int H, int H_kv, int head_dim, int t, int c,
+                                int n_mem_chunks, int mem_capacity, int read_fill,
+                                float scale, int dtype,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    if (n_layers < 1) return LOMA_ERR_INVALID_ARG;
+    if ((k_new == nullptr) != (v_new == nullptr)) return LOMA_ERR_INVALID_ARG;
+    if (!good_gqa_heads(H, H_kv)) return LOMA_ERR_INVALID_ARG;
+    const bool has_new = k_new != nullptr;
+    long long n_mem_keys = 0;
+    if (int rc = check_decode_state(B, H_kv, head_dim, t, c, n_mem_chunks, mem_capacity, read_fill, has_new, scale, dtype,
+                                    &n_mem_keys))
+        return rc;
+    auto good_table = [](const void* p) { return p != nullptr && (reinterpret_cast<uintptr_t>(p) & 7u) == 0; };
+    if (!good_table(q) || !good_table(out) || !good_table(k_read) || !good_table(v_read)) return LOMA_ERR_INVALID_ARG;
+    if (has_new && (!good_table(k_new) || !good_table(v_new))) return LOMA_ERR_INVALID_ARG;
+    if (n_mem_chunks > 0 && (!good_table(k_memcache) || !good_table(v_memcache))) return LOMA_ERR_INVALID_ARG;
+    const int G = H / H_kv;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return LOMA_ERR_UNSUPPORTED;
+    if (!loma::use_mfma_path(dtype, head_dim)) return LOMA_ERR_UNSUPPORTED;
+    if ((long long)B * H_kv > 65535 || n_layers > 65535) return LOMA_ERR_UNSUPPORTED;
+    const int nbh_kv = B * H_kv;
+    const size_t need = (size_t)n_layers * loma::decode_gqa_workspace_bytes(nbh_kv, G, head_dim);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned16(workspace))) return LOMA_ERR_WORKSPACE;
+    const void* const* tables[8] = {q, k_new, v_new, k_memcache, v_memcache,
+                                    const_cast<const void* const*>(k_read), const_cast<const void* const*>(v_read),
+                                    const_cast<const void* const*>(out)};
+    return loma::launch_decode_gqa_layers(tables, has_new, n_layers, nbh_kv, G, head_dim, t * c, (int)n_mem_keys, mem_capacity,
+                                          read_fill, scale, need > 0 ? workspace : nullptr, static_cast<hipStream_t>(stream));
+}
+
 size_t loma_decode_static_scratch_bytes(void) { return loma::decode_static_scratch_bytes(); }
 
 size_t loma_decode_layers_workspace_bytes(int n_layers, int B, int H, int head_dim, int t, int c,

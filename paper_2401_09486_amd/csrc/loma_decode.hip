@@ -256,7 +256,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_kernel(DecodePara
 // group, worked through one query after the other while a batch of rows sits in registers (16-wave workgroups hold
 // half as many rows at a time: 128 registers per lane).  blockIdx.y = b * H_kv + hk;
 // query head (b, hk * G + gq) has index bh * G + gq in q, out and the partial results.
-template <int D, int G, int DEC_WAVES, int UNROLL>
+template <int D, int G, int DEC_WAVES, int UNROLL, bool LAYERED>
 __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_gqa_kernel(DecodeParams P) {
     constexpr int LPR = D / 8;
     constexpr int RPL = 64 / LPR;
@@ -270,6 +270,18 @@ __global__ __launch_bounds__(64 * DEC_WAVES) void decode_split_gqa_kernel(Decode
     const int col = lane % LPR, sub = lane / LPR;
     const int kbeg = sp * P.keys_per_split;
     const int kend = min(P.L, kbeg + P.keys_per_split);
+    if constexpr (LAYERED) {   // blockIdx.z is a layer: its tensors from the pointer tables, its own block of partial results
+        const int layer = blockIdx.z;
+        P.q = P.tab.q[layer];
+        P.k_new = P.has_new ? P.tab.k_new[layer] : nullptr;
+        P.v_new = P.has_new ? P.tab.v_new[layer] : nullptr;
+        P.k_mem = P.n_mem > 0 ? P.tab.k_mem[layer] : nullptr;
+        P.v_mem = P.n_mem > 0 ? P.tab.v_mem[layer] : nullptr;
+        P.k_read = P.tab.k_read[layer];
+        P.v_read = P.tab.v_read[layer];
+        P.out = P.tab.out[layer];
+        if (P.ws_acc != nullptr) { P.ws_acc += layer * P.ws_layer_floats; P.ws_ml += layer * P.ws_layer_floats; }
+    }
     const bf16_t* kmem = P.k_mem + bh * P.mem_rows * D;
     const bf16_t* vmem = P.v_mem + bh * P.mem_rows * D;
     const bf16_t* kread = P.k_read + bh * (long)P.R * D;
@@ -519,8 +531,8 @@ inline bool gqa_wide(int nbh_kv, int G) { return wg_waves(nbh_kv) == 16 && G <= 
 inline int gqa_target_splits(int nbh_kv, int G) {
     return gqa_wide(nbh_kv, G) ? target_splits(nbh_kv) : (DEC_TARGET_WGS_4 + nbh_kv - 1) / nbh_kv;
 }
-template <int D, int G>
-int launch_decode_gqa_dg(DecodeParams& P, int nbh_kv, void* workspace, hipStream_t st) {
+template <int D, int G, bool LAYERED>
+int launch_decode_gqa_dg(DecodeParams& P, int nbh_kv, int n_layers, void* workspace, hipStream_t st) {
     const bool wide = gqa_wide(nbh_kv, G);
     const int kpi = (wide ? 16 * 4 : 4 * DEC_UNROLL) * (64 / (D / 8));   // keys per workgroup iteration
     const int units = (P.L + kpi - 1) / kpi;
@@ -531,24 +543,26 @@ int launch_decode_gqa_dg(DecodeParams& P, int nbh_kv, void* workspace, hipStream
     const long nbh_q = (long)nbh_kv * G;
     P.ws_acc = static_cast<float*>(workspace);
     P.ws_ml = P.ws_acc ? P.ws_acc + (size_t)nbh_q * tgt * D : nullptr;
+    P.ws_layer_floats = nbh_q * tgt * (D + 2);
+    if (n_layers > 65535) return LOMA_ERR_UNSUPPORTED;
     if constexpr (G <= 4) {
-        if (wide) hipLaunchKernelGGL((decode_split_gqa_kernel<D, G, 16, 4>), dim3(P.nsplit, nbh_kv), dim3(1024), 0, st, P);
+        if (wide) hipLaunchKernelGGL((decode_split_gqa_kernel<D, G, 16, 4, LAYERED>), dim3(P.nsplit, nbh_kv, n_layers), dim3(1024), 0, st, P);
     }
-    if (!wide) hipLaunchKernelGGL((decode_split_gqa_kernel<D, G, 4, DEC_UNROLL>), dim3(P.nsplit, nbh_kv), dim3(256), 0, st, P);
+    if (!wide) hipLaunchKernelGGL((decode_split_gqa_kernel<D, G, 4, DEC_UNROLL, LAYERED>), dim3(P.nsplit, nbh_kv, n_layers), dim3(256), 0, st, P);
     if (hipGetLastError() != hipSuccess) return LOMA_ERR_LAUNCH;
     if (P.nsplit > 1) {
-        hipLaunchKernelGGL((decode_combine_kernel<D, false>), dim3((unsigned)nbh_q), dim3(D), 0, st, P);
+        hipLaunchKernelGGL((decode_combine_kernel<D, LAYERED>), dim3((unsigned)nbh_q, n_layers), dim3(D), 0, st, P);
         if (hipGetLastError() != hipSuccess) return LOMA_ERR_LAUNCH;
     }
     return LOMA_OK;
 }
-template <int D>
-int launch_decode_gqa_d(DecodeParams& P, int nbh_kv, int G, void* workspace, hipStream_t st) {
+template <int D, bool LAYERED>
+int launch_decode_gqa_d(DecodeParams& P, int nbh_kv, int G, int n_layers, void* workspace, hipStream_t st) {
     switch (G) {
-        case 1: return launch_decode_gqa_dg<D, 1>(P, nbh_kv, workspace, st);
-        case 2: return launch_decode_gqa_dg<D, 2>(P, nbh_kv, workspace, st);
-        case 4: return launch_decode_gqa_dg<D, 4>(P, nbh_kv, workspace, st);
-        case 8: return launch_decode_gqa_dg<D, 8>(P, nbh_kv, workspace, st);
+        case 1: return launch_decode_gqa_dg<D, 1, LAYERED>(P, nbh_kv, n_layers, workspace, st);
+        case 2: return launch_decode_gqa_dg<D, 2, LAYERED>(P, nbh_kv, n_layers, workspace, st);
+        case 4: return launch_decode_gqa_dg<D, 4, LAYERED>(P, nbh_kv, n_layers, workspace, st);
+        case 8: return launch_decode_gqa_dg<D, 8, LAYERED>(P, nbh_kv, n_layers, workspace, st);
         default: return LOMA_ERR_UNSUPPORTED;
     }
 }
@@ -575,7 +589,28 @@ int launch_decode_gqa(const void* q, const void* k_new, const void* v_new,
     P.L = n_mem_keys + read_fill + (P.has_new ? 1 : 0);
     P.sc = scale * LOG2E;
     if (nbh_kv > 65535 || (long long)nbh_kv * G > 0x7fffffffLL) return LOMA_ERR_UNSUPPORTED;
-    return D == 128 ? launch_decode_gqa_d<128>(P, nbh_kv, G, workspace, st) : launch_decode_gqa_d<64>(P, nbh_kv, G, workspace, st);
+    return D == 128 ? launch_decode_gqa_d<128, false>(P, nbh_kv, G, 1, workspace, st)
+                    : launch_decode_gqa_d<64, false>(P, nbh_kv, G, 1, workspace, st);
+}
+
+int launch_decode_gqa_layers(const void* const* tables[8], bool has_new, int n_layers, int nbh_kv, int G, int D, int R,
+                             int n_mem_keys, int mem_capacity, int read_fill, float scale, void* workspace, hipStream_t st) {
+    DecodeParams P = {};
+    P.tab.q = reinterpret_cast<const bf16_t* const*>(tables[0]);
+    P.tab.k_new = reinterpret_cast<const bf16_t* const*>(tables[1]);
+    P.tab.v_new = reinterpret_cast<const bf16_t* const*>(tables[2]);
+    P.tab.k_mem = reinterpret_cast<const bf16_t* const*>(tables[3]);
+    P.tab.v_mem = reinterpret_cast<const bf16_t* const*>(tables[4]);
+    P.tab.k_read = (bf16_t* const*)(tables[5]);
+    P.tab.v_read = (bf16_t* const*)(tables[6]);
+    P.tab.out = (bf16_t* const*)(tables[7]);
+    P.mem_rows = mem_capacity; P.R = R; P.n_mem = n_mem_keys; P.n_read = read_fill;
+    P.has_new = has_new;
+    P.L = n_mem_keys + read_fill + (has_new ? 1 : 0);
+    P.sc = scale * LOG2E;
+    if (nbh_kv > 65535 || (long long)nbh_kv * G > 0x7fffffffLL) return LOMA_ERR_UNSUPPORTED;
+    return D == 128 ? launch_decode_gqa_d<128, true>(P, nbh_kv, G, n_layers, workspace, st)
+                    : launch_decode_gqa_d<64, true>(P, nbh_kv, G, n_layers, workspace, st);
 }
 
 int launch_decode_splitk_layers(const void* const* tables[8], bool has_new, int n_layers, int nbh, int D, int R,

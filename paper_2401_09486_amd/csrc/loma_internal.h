@@ -165,6 +165,10 @@ int launch_decode_gqa(const void* q, const void* k_new, const void* v_new,
                       const void* k_memcache, const void* v_memcache, void* k_read, void* v_read,
                       void* out, int nbh_kv, int G, int D, int R, int n_mem_keys, int mem_capacity, int read_fill,
                       float scale, void* workspace, hipStream_t st);
+// ... and for n_layers caches in one launch (pointer tables as in launch_decode_splitk_layers; the workspace holds n_layers
+// blocks of decode_gqa_workspace_bytes() each)
+int launch_decode_gqa_layers(const void* const* tables[8], bool has_new, int n_layers, int nbh_kv, int G, int D, int R,
+                             int n_mem_keys, int mem_capacity, int read_fill, float scale, void* workspace, hipStream_t st);
 // Fixed split-K scratch inside the library's device image (for callers that cannot allocate): its size, and its
 // address on the current device (nullptr if the runtime cannot resolve it).
 size_t decode_static_scratch_bytes();

@@ -57,6 +57,8 @@ def _load() -> ctypes.CDLL:
     lib.loma_decode_layers_workspace_bytes.restype = Z
     lib.loma_decode_attn_gqa.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, I, F, I, vp, Z, vp]
     lib.loma_decode_attn_gqa.restype = I
+    lib.loma_decode_attn_gqa_layers.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, I, I, F, I, vp, Z, vp]
+    lib.loma_decode_attn_gqa_layers.restype = I
     lib.loma_decode_gqa_workspace_bytes.argtypes = [I, I, I, I, I]
     lib.loma_decode_gqa_workspace_bytes.restype = Z
     lib.loma_decode_attn_rope.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, I, I, F, I, I, F, vp, Z, vp]
@@ -373,6 +375,24 @@ def loma_decode_attn_layers(q, k_new, v_new, k_memcache, v_memcache, k_read, v_r
                                      float(scale), code, pws, nws, _stream(stream))
     if rc != OK:
         raise LomaError(rc, "loma_decode_attn_layers")
+
+
+def loma_decode_attn_gqa_layers(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, out, n_layers, B, H, H_kv, d, t, c,
+                                n_mem_chunks, mem_capacity, read_fill, scale, dtype=torch.bfloat16, workspace=None,
+                                stream=None):
+    """loma_decode_attn_gqa on n_layers caches in one launch (pointer tables as for loma_decode_attn_layers)."""
+    tabs = []
+    for name, tab in (("q", q), ("k_new", k_new), ("v_new", v_new), ("k_memcache", k_memcache),
+                      ("v_memcache", v_memcache), ("k_read", k_read), ("v_read", v_read), ("out", out)):
+        tabs.append(None if tab is None else _dev(tab, name, (n_layers,), torch.int64))
+    pws, nws = None, 0
+    if workspace is not None:
+        pws, nws = _dev(workspace, "workspace"), workspace.numel() * workspace.element_size()
+    code = F32 if dtype == torch.float32 else BF16
+    rc = lib.loma_decode_attn_gqa_layers(*tabs, n_layers, B, H, H_kv, d, t, c, n_mem_chunks, mem_capacity, read_fill,
+                                         float(scale), code, pws, nws, _stream(stream))
+    if rc != OK:
+        raise LomaError(rc, "loma_decode_attn_gqa_layers")
 
 
 def loma_prefill_attn(q, k_new, v_new, k_memcache, v_memcache, k_read, v_read, t, c, n_mem_chunks, read_fill, scale,

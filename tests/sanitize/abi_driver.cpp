@@ -63,6 +63,8 @@ int main() {
     EXPECT(loma_decode_attn_gqa(P, P, P, P, P, P, P, P, 1, 6, 2, 128, 16, 4, 4, 64, 3, 0.1f, LOMA_BF16, P, 1 << 30, nullptr), LOMA_ERR_UNSUPPORTED);
     EXPECT(loma_decode_attn_gqa(P, P, P, P, P, P, P, P, 1, 8, 2, 128, 16, 4, 4, 64, 3, 0.1f, LOMA_BF16, nullptr, 0, nullptr), LOMA_ERR_WORKSPACE);
     EXPECT(loma_decode_gqa_workspace_bytes(1, 8, 3, 128, LOMA_BF16), 0u);
+    EXPECT(loma_decode_attn_gqa_layers(T, T, T, T, T, Tw, Tw, Tw, 0, 1, 8, 2, 128, 16, 4, 4, 64, 3, 0.1f, LOMA_BF16, P, 1 << 30, nullptr), LOMA_ERR_INVALID_ARG);
+    EXPECT(loma_decode_attn_gqa_layers(T, T, T, T, T, Tw, Tw, Tw, 3, 1, 8, 2, 128, 16, 4, 4, 64, 3, 0.1f, LOMA_BF16, nullptr, 0, nullptr), LOMA_ERR_WORKSPACE);
     // prompt form
     EXPECT(loma_prefill_attn(P, P, P, P, P, P, P, P, nullptr, 1, 8, 128, 16, 4, 4, 64, 60, 5, 0.1f, LOMA_BF16, nullptr), LOMA_ERR_INVALID_ARG);
     EXPECT(loma_prefill_attn(P, nullptr, P, P, P, P, P, P, nullptr, 1, 8, 128, 16, 4, 4, 64, 0, 5, 0.1f, LOMA_BF16, nullptr), LOMA_ERR_INVALID_ARG);

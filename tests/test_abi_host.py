@@ -287,3 +287,24 @@ def test_grouped_query_decode_rejects_bad_arguments(lib):
     assert call(wsb=need - 1) == EWS
     assert lib.loma_decode_gqa_workspace_bytes(1, 8, 3, 128, BF16) == 0
     assert lib.loma_decode_gqa_workspace_bytes(1, 8, 2, 128, F32) == 0
+
+
+def test_layered_grouped_query_decode_rejects_bad_arguments(lib):
+    def call(**kw):
+        a = dict(q=P, kn=P, vn=P, kc=P, vc=P, kr=P, vr=P, out=P, L=3, B=1, H=8, Hkv=2, d=128, t=16, c=4, nmem=4, cap=64,
+                 fill=3, scale=0.1, dtype=BF16, ws=P, wsb=1 << 30)
+        a.update(kw)
+        return lib.loma_decode_attn_gqa_layers(a["q"], a["kn"], a["vn"], a["kc"], a["vc"], a["kr"], a["vr"], a["out"], a["L"],
+                                               a["B"], a["H"], a["Hkv"], a["d"], a["t"], a["c"], a["nmem"], a["cap"],
+                                               a["fill"], a["scale"], a["dtype"], a["ws"], a["wsb"], None)
+    assert call(L=0) == EINVAL
+    assert call(out=None) == EINVAL
+    assert call(kr=P + 4) == EINVAL               # a pointer table must be 8-byte aligned
+    assert call(Hkv=3) == EINVAL
+    assert call(H=6) == EUNSUP
+    assert call(vn=None) == EINVAL                # k_new without v_new
+    assert call(fill=64) == EINVAL
+    assert call(dtype=F32) == EUNSUP
+    need = 3 * lib.loma_decode_gqa_workspace_bytes(1, 8, 2, 128, BF16)
+    assert call(ws=None) == EWS
+    assert call(wsb=need - 1) == EWS

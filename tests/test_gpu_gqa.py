@@ -136,3 +136,49 @@ def test_gqa_decode_high_ratio_shape_full_size(c_oracle):
         assert torch.equal(st["k_read"][:, :, fill], kn[:, :, 0]) and torch.equal(st["v_read"][:, :, fill], vn[:, :, 0])
     assert torch.isfinite(out.float()).all()
     print(f"[result] gqa high-ratio shape: worst max abs {worst:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("shape,fill,with_new", [
+    ((2, 8, 2, 128, 16, 4, 12), 17, True),       # G = 4, keys split over workgroups, combine kernel
+    ((8, 32, 8, 128, 16, 4, 20), 5, True),       # 64 KV heads per layer
+    ((1, 16, 2, 64, 8, 4, 9), 3, True),          # G = 8 (4-wave workgroups), head_dim 64
+    ((1, 4, 2, 128, 16, 4, 0), 7, True),         # no memory yet: the cache tables may be NULL
+    ((1, 8, 4, 128, 16, 4, 30), 40, False),      # no new token
+], ids=["g4_splitk", "kv64", "g8_d64", "empty_memory", "no_new_token"])
+def test_gqa_layered_decode_is_the_single_layer_call_per_layer(c_oracle, shape, fill, with_new):
+    """loma_decode_attn_gqa_layers: every layer's output and cache rows bit for bit what loma_decode_attn_gqa gives
+    on that layer's tensors (which the tests above hold against the oracle)."""
+    from paper_2401_09486_amd import loma
+    B, Hq, Hkv, d, t, c, prior = shape
+    L = 3
+    print(f"[case] layered gqa decode {shape} fill={fill} new={with_new}", flush=True)
+    layers = []
+    for l in range(L):
+        kv_cfg = wl.GenConfig(60 + 2 * l, "gqa_layers_kv", B, Hkv, d, t, c, prior, 1, "bf16", 1.0, 1.0)
+        q_cfg = wl.GenConfig(61 + 2 * l, "gqa_layers_q", B, Hq, d, t, c, prior, 1, "bf16", 1.0, 1.0)
+        st = wl.gen_initial_state(kv_cfg)
+        _, kn, vn = wl.gen_step_inputs(kv_cfg, fill)
+        q, _, _ = wl.gen_step_inputs(q_cfg, fill)
+        layers.append({"st": {k: to_dev(v) for k, v in st.items()}, "single": {k: to_dev(v) for k, v in st.items()},
+                       "q": to_dev(q), "kn": to_dev(kn), "vn": to_dev(vn), "scale": kv_cfg.scale})
+    cap = layers[0]["st"]["k_mem"].shape[2]
+    outs = [torch.empty_like(x["q"]) for x in layers]
+    tab = loma.pointer_table
+    ws = torch.empty(max(L * loma.loma_decode_gqa_workspace_bytes(B, Hq, Hkv, d), 16), dtype=torch.uint8, device="cuda")
+    loma.loma_decode_attn_gqa_layers(
+        tab([x["q"] for x in layers]), tab([x["kn"] for x in layers]) if with_new else None,
+        tab([x["vn"] for x in layers]) if with_new else None,
+        tab([x["st"]["k_mem"] for x in layers]) if prior > 0 else None, tab([x["st"]["v_mem"] for x in layers]) if prior > 0 else None,
+        tab([x["st"]["k_read"] for x in layers]), tab([x["st"]["v_read"] for x in layers]), tab(outs),
+        L, B, Hq, Hkv, d, t, c, prior, cap, fill, layers[0]["scale"], workspace=ws)
+    torch.cuda.synchronize()
+    ws1 = torch.empty(max(loma.loma_decode_gqa_workspace_bytes(B, Hq, Hkv, d), 16), dtype=torch.uint8, device="cuda")
+    for l, x in enumerate(layers):
+        s1 = x["single"]
+        ref = loma.loma_decode_attn_gqa(x["q"], x["kn"] if with_new else None, x["vn"] if with_new else None,
+                                        s1["k_mem"] if prior > 0 else None, s1["v_mem"] if prior > 0 else None,
+                                        s1["k_read"], s1["v_read"], t, c, prior, fill, x["scale"], workspace=ws1)
+        torch.cuda.synchronize()
+        assert torch.equal(outs[l], ref), f"layer {l}: output differs from the single-layer call"
+        assert torch.equal(x["st"]["k_read"], s1["k_read"]) and torch.equal(x["st"]["v_read"], s1["v_read"])
+        assert torch.equal(x["st"]["k_mem"], s1["k_mem"])
